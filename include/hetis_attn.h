@@ -1,0 +1,179 @@
+/*
+ * hetis_attn.h - C ABI of the MI355X (gfx950) head-subset decode-Attention library.
+ *
+ * The operation (Section 4.2, Eq. (2a)/(2b) of the Hetis paper): a device that
+ * holds the KV cache of some attention heads computes, for every running
+ * sequence b and every such head h,
+ *         out[b, h, :] = softmax( scale * q[b, h, :] . K[b, :, kv(h), :]^T ) . V[b, :, kv(h), :]
+ * over the L_b tokens stored so far (decode phase: one query row per sequence,
+ * Section 5.1), and the per-device results are concatenated along the head
+ * axis (Eq. (2a)); heads are independent, so no softmax state ever crosses
+ * devices (Section 6, "Attention computation").  K and V live in fixed-size
+ * blocks that are split again on the head dimension and are addressed by
+ * (sequence, position, head) through a block table (Section 6, "KV cache
+ * management").
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device unless
+ *     marked "host".  The caller owns every buffer and keeps it alive until
+ *     `stream` has passed the enqueued work.  Calls enqueue on `stream`
+ *     (a hipStream_t passed as void*; NULL = the null stream) and return
+ *     without synchronising.
+ *   - fp16 = IEEE binary16.  q/out: [batch, n_q_heads, head_dim], indexed by the
+ *     GLOBAL query head.  Only rows of selected heads are read / written.
+ *   - Cache: the (block, kv head) tile starts at element
+ *     block * kv_stride_block + head * kv_stride_head and holds block_size rows
+ *     of head_dim contiguous fp16 (token-major inside the tile).  K and V use the
+ *     same strides.  Tiles must be 16-byte aligned (strides multiples of 8).
+ *   - block_table: int32 [batch, max_blocks_per_seq]; entry j of row b is the
+ *     physical block of tokens [16 j, 16 j + 16).  Entries at or beyond
+ *     ceil(seq_lens[b] / 16) are never read.  Slots past the end of a sequence
+ *     inside its last block are loaded but never enter a result (they may hold
+ *     NaN).
+ *   - seq_lens: int32 [batch], number of cached tokens including the current
+ *     one; 0 <= seq_lens[b] <= 16 * max_blocks_per_seq.  Length 0 gives zeros.
+ *   - head_ids: int32 [n_sel_heads] KV-head ids in [0, n_kv_heads).  Selecting
+ *     KV head g computes query heads g*r .. g*r + r - 1, r = n_q_heads /
+ *     n_kv_heads (grouped-query models move whole groups, Section 5.2.1; for
+ *     r = 1 these are plain head ids).  Duplicates are allowed and wasteful.
+ *   - The work done for one (sequence, KV head) depends only on that sequence's
+ *     length and on compile-time constants, never on n_sel_heads or on the grid:
+ *     a head-subset call returns, bit for bit, the matching rows of the
+ *     all-heads call.  No floating-point atomics are used; results are
+ *     deterministic run to run.
+ *   - Device-side contents (lengths, block ids, head ids) are NOT checked on the
+ *     hot path; out-of-range values are undefined behaviour.  Use
+ *     hetis_attn_validate in debug builds and tests.
+ *   - Every function returns a status (0 = HETIS_OK, negative = error) and
+ *     never throws, aborts or prints.  Argument errors are detected before any
+ *     HIP call is made.
+ *
+ * Supported: head_dim in {64, 128}; block_size 16; r in {1, 2, 4, 8}.
+ */
+#ifndef HETIS_ATTN_H
+#define HETIS_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    HETIS_OK = 0,
+    HETIS_ERR_NULL = -1,        /* a required pointer is NULL */
+    HETIS_ERR_BAD_SHAPE = -2,   /* non-positive size, n_q_heads % n_kv_heads != 0, bad strides */
+    HETIS_ERR_UNSUPPORTED = -3, /* head_dim, block_size, group size or chunk_tokens not supported */
+    HETIS_ERR_BAD_HEADS = -4,   /* n_sel_heads outside [1, n_kv_heads] */
+    HETIS_ERR_WORKSPACE = -5,   /* max_seq_len inconsistent with the shape / chunking */
+    HETIS_ERR_LAUNCH = -6,      /* HIP reported an error when launching */
+    HETIS_ERR_ALLOC = -7,       /* the internal workspace could not be allocated */
+    HETIS_ERR_BAD_CONTENT = -8  /* hetis_attn_validate found an out-of-range value */
+};
+
+typedef struct {
+    int32_t batch;              /* B  > 0 */
+    int32_t n_q_heads;          /* Hq > 0 */
+    int32_t n_kv_heads;         /* Hkv > 0, Hq % Hkv == 0 */
+    int32_t head_dim;           /* D: 64 or 128 */
+    int32_t block_size;         /* 16 */
+    int32_t max_blocks_per_seq; /* row stride of block_table, > 0 */
+    int64_t kv_stride_block;    /* elements between blocks; 0 = Hkv * block_size * D */
+    int64_t kv_stride_head;     /* elements between heads of a block; 0 = block_size * D */
+} hetis_attn_shape;
+
+/* Library version, major * 100 + minor. */
+int hetis_attn_version(void);
+
+/* Static, human-readable name of a status code (host pointer, never NULL). */
+const char *hetis_attn_status_string(int status);
+
+/*
+ * Decode Attention for the selected heads (Eq. (2b)), one call = one layer of
+ * one decode step for this device's head share.
+ *   shape        host
+ *   q            fp16 [B, Hq, D]
+ *   k_cache      fp16 tiles as described above
+ *   v_cache      fp16, same layout
+ *   block_table  int32 [B, max_blocks_per_seq]
+ *   seq_lens     int32 [B]
+ *   head_ids     int32 [n_sel_heads]
+ *   n_sel_heads  host, 1 .. Hkv
+ *   scale        host, normally 1/sqrt(D)
+ *   out          fp16 [B, Hq, D]; rows of unselected heads are left untouched
+ * Sequences longer than an internal fixed chunk (a compile-time constant) are
+ * processed as several chunks whose fp32 partial results go through a
+ * workspace that the library owns: it is allocated with hipMalloc on the first
+ * call on a device and grown when a call needs more (both synchronise the
+ * device); steady-state calls allocate nothing.  The workspace is shared by all
+ * calls on one device: calls on different streams that may overlap must be
+ * serialised by the caller, or use the split entry points with their own
+ * buffers.  Errors: NULL, BAD_SHAPE, UNSUPPORTED, BAD_HEADS, ALLOC, LAUNCH.
+ */
+int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                      const void *v_cache, const int32_t *block_table, const int32_t *seq_lens,
+                      const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
+                      void *stream);
+
+/* Frees the internal workspace of every device (synchronises).  Optional. */
+int hetis_attn_release_workspace(void);
+
+/*
+ * Split-KV variant: the token axis of every sequence is cut into chunks of
+ * chunk_tokens tokens starting at token 0 (an exact decomposition of Eq. (2b)
+ * inside one device; the paper itself only splits on heads).  Chunk c of
+ * sequence b covers tokens [c*chunk_tokens, min((c+1)*chunk_tokens, L_b)).
+ *
+ * hetis_attn_split_num_chunks: C_max = ceil(max_seq_len / chunk_tokens), or a
+ *   negative status.  chunk_tokens must be a positive multiple of 16.
+ * hetis_attn_split_workspace_bytes: sizes in bytes of the two partial buffers
+ *   (host out-pointers).
+ */
+int hetis_attn_split_num_chunks(int32_t max_seq_len, int32_t chunk_tokens);
+int hetis_attn_split_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,
+                                     int32_t max_seq_len, int32_t chunk_tokens,
+                                     size_t *o_partial_bytes, size_t *lse_partial_bytes);
+
+/*
+ * Partial pass.  With row j = i*r + (h - head_ids[i]*r) for the i-th selected
+ * KV head, and per chunk m_c = max_t s_t, Z_c = sum_t exp(s_t - m_c):
+ *   o_partial   fp32 [B, n_sel_heads*r, C_max, D]  = sum_t exp(s_t - m_c) V_t / Z_c
+ *   lse_partial fp32 [B, n_sel_heads*r, C_max]     = m_c + ln Z_c   (natural log)
+ * Entries of chunks c >= ceil(L_b / chunk_tokens) are not written.
+ * max_seq_len (host) bounds every seq_lens[b]; it fixes C_max and the grid.
+ * Errors: as hetis_attn_decode, plus WORKSPACE when max_seq_len is not in
+ * [1, 16 * max_blocks_per_seq].
+ */
+int hetis_attn_decode_split(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                            const void *v_cache, const int32_t *block_table,
+                            const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
+                            float scale, int32_t chunk_tokens, int32_t max_seq_len,
+                            float *o_partial, float *lse_partial, void *stream);
+
+/*
+ * Log-sum-exp merge of the partials, ascending chunk order, in fp32:
+ *   M = max_c lse_c, w_c = exp(lse_c - M), out = fp16( sum_c w_c o_c / sum_c w_c ).
+ * Only chunks c < ceil(L_b / chunk_tokens) are read; L_b = 0 writes zeros.
+ *   out fp16 [B, Hq, D], selected rows only.
+ */
+int hetis_attn_merge(const hetis_attn_shape *shape, const float *o_partial,
+                     const float *lse_partial, const int32_t *seq_lens, const int32_t *head_ids,
+                     int32_t n_sel_heads, int32_t chunk_tokens, int32_t max_seq_len, void *out,
+                     void *stream);
+
+/*
+ * Debug helper, not for the hot path: copies seq_lens, head_ids and the used
+ * part of block_table to the host (synchronises `stream`) and checks
+ * 0 <= seq_lens[b] <= 16*max_blocks_per_seq, 0 <= head_ids[i] < Hkv and
+ * 0 <= block id < num_blocks for every entry a call would read.
+ * Returns HETIS_OK or HETIS_ERR_BAD_CONTENT (or an argument error).
+ */
+int hetis_attn_validate(const hetis_attn_shape *shape, const int32_t *block_table,
+                        const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
+                        int64_t num_blocks, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HETIS_ATTN_H */

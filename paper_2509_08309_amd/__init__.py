@@ -1,0 +1,14 @@
+"""MI355X-native head-subset decode Attention over a block-paged KV cache.
+
+The product is the HIP library built from csrc/ (C ABI in include/hetis_attn.h);
+`binding` exposes it under the same names, `workloads` draws seeded inputs.
+Importing this package loads nothing; the library is loaded on first call and
+its absence is an error, never a fallback.
+"""
+from . import binding  # noqa: F401
+from .binding import (  # noqa: F401
+    HetisError, check, hetis_attn_decode, hetis_attn_decode_split, hetis_attn_merge,
+    hetis_attn_release_workspace, hetis_attn_shape, hetis_attn_split_num_chunks,
+    hetis_attn_split_workspace_bytes, hetis_attn_status_string, hetis_attn_validate,
+    hetis_attn_version, make_shape,
+)

@@ -1,0 +1,168 @@
+"""ctypes binding of libhetis_attn.so: same names as include/hetis_attn.h.
+
+Argument marshalling only.  Tensors are torch tensors that already live on the
+GPU (PyTorch is used for device memory and streams, nothing else); every
+function passes raw device pointers to the C ABI and returns its status.  The
+library is loaded on first use and loading fails loudly when it has not been
+built: there is no CPU fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhetis_attn.so")
+
+HETIS_OK = 0
+HETIS_ERR_NULL = -1
+HETIS_ERR_BAD_SHAPE = -2
+HETIS_ERR_UNSUPPORTED = -3
+HETIS_ERR_BAD_HEADS = -4
+HETIS_ERR_WORKSPACE = -5
+HETIS_ERR_LAUNCH = -6
+HETIS_ERR_ALLOC = -7
+HETIS_ERR_BAD_CONTENT = -8
+
+
+class hetis_attn_shape(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("block_size", C.c_int32),
+                ("max_blocks_per_seq", C.c_int32),
+                ("kv_stride_block", C.c_int64), ("kv_stride_head", C.c_int64)]
+
+
+class HetisError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({hetis_attn_status_string(status)})")
+
+
+_lib = None
+
+
+def load(build_if_missing: bool = False):
+    """Load the built library; optionally build it first when nothing is built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if build_if_missing:
+            from .build import build
+            build()
+        else:
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2509_08309_amd.build` "
+                "(the HIP library is required, there is no fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    shp = C.POINTER(hetis_attn_shape)
+    lib.hetis_attn_version.restype = C.c_int
+    lib.hetis_attn_version.argtypes = []
+    lib.hetis_attn_status_string.restype = C.c_char_p
+    lib.hetis_attn_status_string.argtypes = [C.c_int]
+    lib.hetis_attn_decode.restype = C.c_int
+    lib.hetis_attn_decode.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
+    lib.hetis_attn_release_workspace.restype = C.c_int
+    lib.hetis_attn_release_workspace.argtypes = []
+    lib.hetis_attn_split_num_chunks.restype = C.c_int
+    lib.hetis_attn_split_num_chunks.argtypes = [i32, i32]
+    lib.hetis_attn_split_workspace_bytes.restype = C.c_int
+    lib.hetis_attn_split_workspace_bytes.argtypes = [shp, i32, i32, i32, C.POINTER(C.c_size_t),
+                                                     C.POINTER(C.c_size_t)]
+    lib.hetis_attn_decode_split.restype = C.c_int
+    lib.hetis_attn_decode_split.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, i32, i32,
+                                            vp, vp, vp]
+    lib.hetis_attn_merge.restype = C.c_int
+    lib.hetis_attn_merge.argtypes = [shp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.hetis_attn_validate.restype = C.c_int
+    lib.hetis_attn_validate.argtypes = [shp, vp, vp, vp, i32, i64, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor / raw int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def make_shape(batch, n_q_heads, n_kv_heads, head_dim, max_blocks_per_seq, block_size=16,
+               kv_stride_block=0, kv_stride_head=0) -> hetis_attn_shape:
+    return hetis_attn_shape(batch, n_q_heads, n_kv_heads, head_dim, block_size,
+                            max_blocks_per_seq, kv_stride_block, kv_stride_head)
+
+
+def hetis_attn_version() -> int:
+    return load().hetis_attn_version()
+
+
+def hetis_attn_status_string(status: int) -> str:
+    return load().hetis_attn_status_string(status).decode()
+
+
+def hetis_attn_decode(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
+                      scale, out, stream=None) -> int:
+    return load().hetis_attn_decode(C.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                    _ptr(block_table), _ptr(seq_lens), _ptr(head_ids),
+                                    int(n_sel_heads), float(scale), _ptr(out), _stream(stream))
+
+
+def hetis_attn_release_workspace() -> int:
+    return load().hetis_attn_release_workspace()
+
+
+def hetis_attn_split_num_chunks(max_seq_len: int, chunk_tokens: int) -> int:
+    return load().hetis_attn_split_num_chunks(int(max_seq_len), int(chunk_tokens))
+
+
+def hetis_attn_split_workspace_bytes(shape, n_sel_heads, max_seq_len, chunk_tokens):
+    """(status, o_partial_bytes, lse_partial_bytes)."""
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    rc = load().hetis_attn_split_workspace_bytes(C.byref(shape), int(n_sel_heads),
+                                                 int(max_seq_len), int(chunk_tokens),
+                                                 C.byref(a), C.byref(b))
+    return rc, a.value, b.value
+
+
+def hetis_attn_decode_split(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                            n_sel_heads, scale, chunk_tokens, max_seq_len, o_partial,
+                            lse_partial, stream=None) -> int:
+    return load().hetis_attn_decode_split(C.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                          _ptr(block_table), _ptr(seq_lens), _ptr(head_ids),
+                                          int(n_sel_heads), float(scale), int(chunk_tokens),
+                                          int(max_seq_len), _ptr(o_partial), _ptr(lse_partial),
+                                          _stream(stream))
+
+
+def hetis_attn_merge(shape, o_partial, lse_partial, seq_lens, head_ids, n_sel_heads,
+                     chunk_tokens, max_seq_len, out, stream=None) -> int:
+    return load().hetis_attn_merge(C.byref(shape), _ptr(o_partial), _ptr(lse_partial),
+                                   _ptr(seq_lens), _ptr(head_ids), int(n_sel_heads),
+                                   int(chunk_tokens), int(max_seq_len), _ptr(out),
+                                   _stream(stream))
+
+
+def hetis_attn_validate(shape, block_table, seq_lens, head_ids, n_sel_heads, num_blocks,
+                        stream=None) -> int:
+    return load().hetis_attn_validate(C.byref(shape), _ptr(block_table), _ptr(seq_lens),
+                                      _ptr(head_ids), int(n_sel_heads), int(num_blocks),
+                                      _stream(stream))
+
+
+def check(status: int, where: str = "hetis_attn") -> None:
+    if status != HETIS_OK:
+        raise HetisError(status, where)

@@ -1,0 +1,63 @@
+// Shared device helpers and launch parameters of the decode-Attention kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace hetis {
+
+constexpr int kBlockTokens = 16;          // tokens per cache block
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLog2e = 1.4426950408889634f;
+// Finite stand-in for "no token seen yet": keeps exp2(m_old - m_new) free of inf - inf.
+constexpr float kNegBig = -1.0e30f;
+
+struct AttnParams {
+    const __half *q;            // [B, Hq, D]
+    const __half *k_cache;
+    const __half *v_cache;
+    const int32_t *block_table; // [B, max_blocks_per_seq]
+    const int32_t *seq_lens;    // [B]
+    const int32_t *head_ids;    // [n_sel]
+    __half *out;                // [B, Hq, D]
+    float *o_partial;           // [B, n_sel*r, max_chunks, D]
+    float *lse_partial;         // [B, n_sel*r, max_chunks]
+    int64_t stride_block;       // elements
+    int64_t stride_head;        // elements
+    int32_t n_q_heads;
+    int32_t n_sel;
+    int32_t max_blocks_per_seq;
+    int32_t chunk_tokens;       // multiple of 16
+    int32_t max_chunks;
+    int32_t direct_single;      // 1: a sequence of <= 1 chunk is written to `out` by the partial pass
+    float scale_log2;           // scale * log2(e): scores are kept in the base-2 domain
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Cross-lane move inside a row of 16 lanes (DPP), no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over aligned groups of LANES lanes (LANES = 8 or 16); every lane gets the total.
+template <int LANES>
+__device__ __forceinline__ float group_sum(float x)
+{
+    x += dpp_mov<0xB1>(x);    // quad_perm [1,0,3,2]
+    x += dpp_mov<0x4E>(x);    // quad_perm [2,3,0,1]
+    x += dpp_mov<0x141>(x);   // row_half_mirror: pairs the two quads of each 8 lanes
+    if (LANES == 16) x += dpp_mov<0x140>(x);  // row_mirror: pairs the two halves of the row
+    return x;
+}
+
+union Pack16 {
+    uint4 u;
+    __half2 h2[4];
+    __half h[8];
+};
+
+}  // namespace hetis

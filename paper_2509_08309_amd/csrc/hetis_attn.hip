@@ -1,0 +1,319 @@
+// C ABI of the head-subset decode-Attention library: argument checks, kernel choice, launches.
+// Every argument error is reported before the first HIP call, so the checks can be
+// exercised on a machine without a GPU.
+#include "../../include/hetis_attn.h"
+
+#include <mutex>
+#include <vector>
+
+#include "attn_vec.hpp"
+
+namespace hetis {
+
+// Tokens per chunk of hetis_attn_decode.  A compile-time constant: the chunking of a
+// sequence must depend on its length only, or a head-subset call could not reproduce
+// the all-heads call bit for bit.
+constexpr int kDecodeChunkTokens = 256;
+constexpr int kVecWaves = 4;
+
+struct Checked {
+    int group;          // r
+    int64_t stride_block, stride_head;
+};
+
+static int check_shape(const hetis_attn_shape *s, int32_t n_sel, Checked *c)
+{
+    if (!s) return HETIS_ERR_NULL;
+    if (s->batch <= 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0 ||
+        s->block_size <= 0 || s->max_blocks_per_seq <= 0)
+        return HETIS_ERR_BAD_SHAPE;
+    if (s->n_q_heads % s->n_kv_heads != 0) return HETIS_ERR_BAD_SHAPE;
+    if (s->kv_stride_block < 0 || s->kv_stride_head < 0) return HETIS_ERR_BAD_SHAPE;
+    if (s->head_dim != 64 && s->head_dim != 128) return HETIS_ERR_UNSUPPORTED;
+    if (s->block_size != kBlockTokens) return HETIS_ERR_UNSUPPORTED;
+    const int r = s->n_q_heads / s->n_kv_heads;
+    if (r != 1 && r != 2 && r != 4 && r != 8) return HETIS_ERR_UNSUPPORTED;
+    if (s->batch > 65535) return HETIS_ERR_UNSUPPORTED;
+    const int64_t tile = (int64_t)s->block_size * s->head_dim;
+    c->group = r;
+    c->stride_head = s->kv_stride_head ? s->kv_stride_head : tile;
+    c->stride_block = s->kv_stride_block ? s->kv_stride_block : tile * s->n_kv_heads;
+    if (c->stride_head % 8 != 0 || c->stride_block % 8 != 0) return HETIS_ERR_BAD_SHAPE;
+    if (c->stride_head < tile) return HETIS_ERR_BAD_SHAPE;
+    if (n_sel < 1 || n_sel > s->n_kv_heads) return HETIS_ERR_BAD_HEADS;
+    if ((int64_t)n_sel > 65535) return HETIS_ERR_UNSUPPORTED;
+    return HETIS_OK;
+}
+
+static int check_chunking(const hetis_attn_shape *s, int32_t chunk_tokens, int32_t max_seq_len)
+{
+    if (chunk_tokens <= 0 || chunk_tokens % kBlockTokens != 0) return HETIS_ERR_UNSUPPORTED;
+    if (max_seq_len < 1 || (int64_t)max_seq_len > (int64_t)s->max_blocks_per_seq * kBlockTokens)
+        return HETIS_ERR_WORKSPACE;
+    return HETIS_OK;
+}
+
+template <int D, int R>
+static void launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
+{
+    dim3 grid(p.max_chunks, p.n_sel, batch);
+    attn_chunk_vec_kernel<D, R, kVecWaves><<<grid, kVecWaves * 64, 0, st>>>(p);
+}
+
+static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
+{
+#define HETIS_CASE(DD, RR) \
+    if (D == DD && r == RR) { launch_chunk_vec<DD, RR>(p, batch, st); return HETIS_OK; }
+    HETIS_CASE(128, 1) HETIS_CASE(128, 2) HETIS_CASE(128, 4) HETIS_CASE(128, 8)
+    HETIS_CASE(64, 1) HETIS_CASE(64, 2) HETIS_CASE(64, 4) HETIS_CASE(64, 8)
+#undef HETIS_CASE
+    return HETIS_ERR_UNSUPPORTED;
+}
+
+static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream_t st)
+{
+    dim3 grid(p.n_sel * r, batch);
+    if (D == 128)
+        attn_merge_kernel<128><<<grid, 128, 0, st>>>(p, r);
+    else
+        attn_merge_kernel<64><<<grid, 64, 0, st>>>(p, r);
+}
+
+// Internal workspace of hetis_attn_decode, one per device, grown on demand.
+struct Workspace {
+    float *ptr = nullptr;
+    size_t bytes = 0;
+};
+static std::mutex g_ws_mutex;
+static std::vector<Workspace> g_ws;
+
+static int workspace_for(size_t need, float **out)
+{
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return HETIS_ERR_ALLOC;
+    if ((size_t)dev >= g_ws.size()) g_ws.resize(dev + 1);
+    Workspace &w = g_ws[dev];
+    if (w.bytes < need) {
+        if (w.ptr) {
+            if (hipDeviceSynchronize() != hipSuccess) return HETIS_ERR_ALLOC;
+            (void)hipFree(w.ptr);
+            w.ptr = nullptr;
+            w.bytes = 0;
+        }
+        const size_t want = need + need / 4;
+        if (hipMalloc((void **)&w.ptr, want) != hipSuccess) {
+            w.ptr = nullptr;
+            (void)hipGetLastError();
+            return HETIS_ERR_ALLOC;
+        }
+        w.bytes = want;
+    }
+    *out = w.ptr;
+    return HETIS_OK;
+}
+
+static AttnParams make_params(const hetis_attn_shape *s, const Checked &c, const void *q,
+                              const void *k, const void *v, const int32_t *bt,
+                              const int32_t *sl, const int32_t *hid, int32_t n_sel, float scale,
+                              void *out)
+{
+    AttnParams p{};
+    p.q = (const __half *)q;
+    p.k_cache = (const __half *)k;
+    p.v_cache = (const __half *)v;
+    p.block_table = bt;
+    p.seq_lens = sl;
+    p.head_ids = hid;
+    p.out = (__half *)out;
+    p.stride_block = c.stride_block;
+    p.stride_head = c.stride_head;
+    p.n_q_heads = s->n_q_heads;
+    p.n_sel = n_sel;
+    p.max_blocks_per_seq = s->max_blocks_per_seq;
+    p.scale_log2 = scale * kLog2e;
+    return p;
+}
+
+}  // namespace hetis
+
+using namespace hetis;
+
+extern "C" {
+
+int hetis_attn_version(void) { return 100; }
+
+const char *hetis_attn_status_string(int status)
+{
+    switch (status) {
+    case HETIS_OK: return "ok";
+    case HETIS_ERR_NULL: return "null pointer argument";
+    case HETIS_ERR_BAD_SHAPE: return "bad shape";
+    case HETIS_ERR_UNSUPPORTED: return "unsupported head_dim, block_size, group size or chunk_tokens";
+    case HETIS_ERR_BAD_HEADS: return "n_sel_heads outside [1, n_kv_heads]";
+    case HETIS_ERR_WORKSPACE: return "max_seq_len inconsistent with shape or chunking";
+    case HETIS_ERR_LAUNCH: return "kernel launch failed";
+    case HETIS_ERR_ALLOC: return "internal workspace allocation failed";
+    case HETIS_ERR_BAD_CONTENT: return "device-side argument content out of range";
+    default: return "unknown status";
+    }
+}
+
+int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                      const void *v_cache, const int32_t *block_table, const int32_t *seq_lens,
+                      const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
+                      void *stream)
+{
+    Checked c;
+    if (!shape || !q || !k_cache || !v_cache || !block_table || !seq_lens || !head_ids || !out)
+        return HETIS_ERR_NULL;
+    int rc = check_shape(shape, n_sel_heads, &c);
+    if (rc != HETIS_OK) return rc;
+
+    AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                               n_sel_heads, scale, out);
+    p.chunk_tokens = kDecodeChunkTokens;
+    const int64_t max_tokens = (int64_t)shape->max_blocks_per_seq * kBlockTokens;
+    p.max_chunks = (int)((max_tokens + kDecodeChunkTokens - 1) / kDecodeChunkTokens);
+    p.direct_single = 1;
+    hipStream_t st = (hipStream_t)stream;
+    if (p.max_chunks > 1) {
+        const size_t rows = (size_t)shape->batch * n_sel_heads * c.group * p.max_chunks;
+        const size_t need = rows * (shape->head_dim + 1) * sizeof(float);
+        float *ws = nullptr;
+        rc = workspace_for(need, &ws);
+        if (rc != HETIS_OK) return rc;
+        p.o_partial = ws;
+        p.lse_partial = ws + rows * shape->head_dim;
+    }
+    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, st);
+    if (rc != HETIS_OK) return rc;
+    if (p.max_chunks > 1) launch_merge(p, shape->head_dim, c.group, shape->batch, st);
+    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
+
+int hetis_attn_release_workspace(void)
+{
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    int cur = 0;
+    bool any = false;
+    for (size_t d = 0; d < g_ws.size(); ++d)
+        if (g_ws[d].ptr) any = true;
+    if (!any) return HETIS_OK;
+    if (hipGetDevice(&cur) != hipSuccess) return HETIS_ERR_ALLOC;
+    for (size_t d = 0; d < g_ws.size(); ++d) {
+        if (!g_ws[d].ptr) continue;
+        (void)hipSetDevice((int)d);
+        (void)hipDeviceSynchronize();
+        (void)hipFree(g_ws[d].ptr);
+        g_ws[d] = Workspace();
+    }
+    (void)hipSetDevice(cur);
+    return HETIS_OK;
+}
+
+int hetis_attn_split_num_chunks(int32_t max_seq_len, int32_t chunk_tokens)
+{
+    if (chunk_tokens <= 0 || chunk_tokens % kBlockTokens != 0) return HETIS_ERR_UNSUPPORTED;
+    if (max_seq_len < 1) return HETIS_ERR_WORKSPACE;
+    return (int)(((int64_t)max_seq_len + chunk_tokens - 1) / chunk_tokens);
+}
+
+int hetis_attn_split_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,
+                                     int32_t max_seq_len, int32_t chunk_tokens,
+                                     size_t *o_partial_bytes, size_t *lse_partial_bytes)
+{
+    Checked c;
+    if (!shape || !o_partial_bytes || !lse_partial_bytes) return HETIS_ERR_NULL;
+    int rc = check_shape(shape, n_sel_heads, &c);
+    if (rc != HETIS_OK) return rc;
+    rc = check_chunking(shape, chunk_tokens, max_seq_len);
+    if (rc != HETIS_OK) return rc;
+    const size_t n_chunks = (size_t)hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
+    const size_t rows = (size_t)shape->batch * n_sel_heads * c.group * n_chunks;
+    *o_partial_bytes = rows * shape->head_dim * sizeof(float);
+    *lse_partial_bytes = rows * sizeof(float);
+    return HETIS_OK;
+}
+
+int hetis_attn_decode_split(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                            const void *v_cache, const int32_t *block_table,
+                            const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
+                            float scale, int32_t chunk_tokens, int32_t max_seq_len,
+                            float *o_partial, float *lse_partial, void *stream)
+{
+    Checked c;
+    if (!shape || !q || !k_cache || !v_cache || !block_table || !seq_lens || !head_ids ||
+        !o_partial || !lse_partial)
+        return HETIS_ERR_NULL;
+    int rc = check_shape(shape, n_sel_heads, &c);
+    if (rc != HETIS_OK) return rc;
+    rc = check_chunking(shape, chunk_tokens, max_seq_len);
+    if (rc != HETIS_OK) return rc;
+    AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                               n_sel_heads, scale, nullptr);
+    p.chunk_tokens = chunk_tokens;
+    p.max_chunks = hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
+    p.direct_single = 0;
+    p.o_partial = o_partial;
+    p.lse_partial = lse_partial;
+    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, (hipStream_t)stream);
+    if (rc != HETIS_OK) return rc;
+    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
+
+int hetis_attn_merge(const hetis_attn_shape *shape, const float *o_partial,
+                     const float *lse_partial, const int32_t *seq_lens, const int32_t *head_ids,
+                     int32_t n_sel_heads, int32_t chunk_tokens, int32_t max_seq_len, void *out,
+                     void *stream)
+{
+    Checked c;
+    if (!shape || !o_partial || !lse_partial || !seq_lens || !head_ids || !out)
+        return HETIS_ERR_NULL;
+    int rc = check_shape(shape, n_sel_heads, &c);
+    if (rc != HETIS_OK) return rc;
+    rc = check_chunking(shape, chunk_tokens, max_seq_len);
+    if (rc != HETIS_OK) return rc;
+    AttnParams p = make_params(shape, c, nullptr, nullptr, nullptr, nullptr, seq_lens, head_ids,
+                               n_sel_heads, 0.f, out);
+    p.chunk_tokens = chunk_tokens;
+    p.max_chunks = hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
+    p.direct_single = 0;
+    p.o_partial = const_cast<float *>(o_partial);
+    p.lse_partial = const_cast<float *>(lse_partial);
+    launch_merge(p, shape->head_dim, c.group, shape->batch, (hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
+
+int hetis_attn_validate(const hetis_attn_shape *shape, const int32_t *block_table,
+                        const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
+                        int64_t num_blocks, void *stream)
+{
+    Checked c;
+    if (!shape || !block_table || !seq_lens || !head_ids) return HETIS_ERR_NULL;
+    int rc = check_shape(shape, n_sel_heads, &c);
+    if (rc != HETIS_OK) return rc;
+    if (num_blocks <= 0) return HETIS_ERR_BAD_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t B = (size_t)shape->batch, MB = (size_t)shape->max_blocks_per_seq;
+    std::vector<int32_t> sl(B), hid((size_t)n_sel_heads), bt(B * MB);
+    if (hipStreamSynchronize(st) != hipSuccess) return HETIS_ERR_LAUNCH;
+    if (hipMemcpy(sl.data(), seq_lens, B * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(hid.data(), head_ids, hid.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(bt.data(), block_table, bt.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return HETIS_ERR_LAUNCH;
+    for (int32_t h : hid)
+        if (h < 0 || h >= shape->n_kv_heads) return HETIS_ERR_BAD_CONTENT;
+    for (size_t b = 0; b < B; ++b) {
+        const int64_t L = sl[b];
+        if (L < 0 || L > (int64_t)MB * kBlockTokens) return HETIS_ERR_BAD_CONTENT;
+        const size_t nb = (size_t)((L + kBlockTokens - 1) / kBlockTokens);
+        for (size_t j = 0; j < nb; ++j) {
+            const int64_t blk = bt[b * MB + j];
+            if (blk < 0 || blk >= num_blocks) return HETIS_ERR_BAD_CONTENT;
+        }
+    }
+    return HETIS_OK;
+}
+
+}  // extern "C"

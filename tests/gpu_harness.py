@@ -1,0 +1,96 @@
+"""Helpers shared by the GPU parity tests: upload a workload, call the C ABI, fetch results."""
+import numpy as np
+import torch
+
+import paper_2509_08309_amd as H
+from paper_2509_08309_amd import workloads as W
+
+TOL = 4e-3          # max abs error of the fp16 output against the fp64 checker
+SENTINEL = 0x7BFF   # fp16 65504: rows the library must not touch keep this bit pattern
+
+
+class Dev:
+    """A workload resident on the GPU plus the ABI shape that describes it."""
+
+    def __init__(self, w: W.Workload):
+        assert torch.cuda.is_available(), "GPU tests need a GPU"
+        H.binding.load()
+        self.w = w
+        dev = torch.device("cuda:0")
+        self.q = w.q.to(dev)
+        self.k = w.k_cache.to(dev)
+        self.v = w.v_cache.to(dev)
+        self.bt = torch.from_numpy(w.block_table).to(dev)
+        self.sl = torch.from_numpy(w.seq_lens).to(dev)
+        s = w.spec
+        self.shape = H.make_shape(s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim,
+                                  w.block_table.shape[1])
+        self.scale = s.scale
+
+    def heads(self, head_ids):
+        hid = np.asarray(head_ids, dtype=np.int32)
+        return torch.from_numpy(hid).cuda(), len(hid)
+
+    def new_out(self):
+        B, Hq, D = self.q.shape
+        out = torch.empty((B, Hq, D), dtype=torch.float16, device="cuda:0")
+        out.view(torch.int16).fill_(np.int16(SENTINEL))
+        return out
+
+    def validate(self, head_ids):
+        hid, n = self.heads(head_ids)
+        H.check(H.hetis_attn_validate(self.shape, self.bt, self.sl, hid, n, self.w.num_blocks),
+                "validate")
+
+    def decode(self, head_ids, out=None):
+        self.validate(head_ids)
+        hid, n = self.heads(head_ids)
+        out = self.new_out() if out is None else out
+        H.check(H.hetis_attn_decode(self.shape, self.q, self.k, self.v, self.bt, self.sl, hid, n,
+                                    self.scale, out), "hetis_attn_decode")
+        torch.cuda.synchronize()
+        return out
+
+    def split(self, head_ids, chunk_tokens, max_seq_len, fill=float("nan")):
+        self.validate(head_ids)
+        hid, n = self.heads(head_ids)
+        s = self.w.spec
+        C = H.hetis_attn_split_num_chunks(max_seq_len, chunk_tokens)
+        assert C > 0
+        rc, ob, lb = H.hetis_attn_split_workspace_bytes(self.shape, n, max_seq_len, chunk_tokens)
+        H.check(rc, "workspace_bytes")
+        rows = n * s.group_size
+        o_p = torch.full((s.batch, rows, C, s.head_dim), fill, dtype=torch.float32, device="cuda:0")
+        lse_p = torch.full((s.batch, rows, C), fill, dtype=torch.float32, device="cuda:0")
+        assert o_p.numel() * 4 == ob and lse_p.numel() * 4 == lb
+        H.check(H.hetis_attn_decode_split(self.shape, self.q, self.k, self.v, self.bt, self.sl,
+                                          hid, n, self.scale, chunk_tokens, max_seq_len, o_p,
+                                          lse_p), "hetis_attn_decode_split")
+        torch.cuda.synchronize()
+        return o_p, lse_p
+
+    def merge(self, o_p, lse_p, head_ids, chunk_tokens, max_seq_len, out=None):
+        hid, n = self.heads(head_ids)
+        out = self.new_out() if out is None else out
+        H.check(H.hetis_attn_merge(self.shape, o_p, lse_p, self.sl, hid, n, chunk_tokens,
+                                   max_seq_len, out), "hetis_attn_merge")
+        torch.cuda.synchronize()
+        return out
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def as_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy().astype(np.float64)
+
+
+def selected_rows(spec: W.WorkloadSpec, head_ids):
+    r = spec.group_size
+    return sorted(g * r + i for g in head_ids for i in range(r))
+
+
+def unselected_rows(spec: W.WorkloadSpec, head_ids):
+    sel = set(selected_rows(spec, head_ids))
+    return [h for h in range(spec.n_q_heads) if h not in sel]

@@ -1,0 +1,150 @@
+"""Host-side checks of the C ABI that need no GPU: exported symbols and argument errors."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2509_08309_amd as H
+from paper_2509_08309_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load(build_if_missing=True)
+
+
+def declared_functions():
+    names = []
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names += re.findall(r"\b(hetis_attn_\w+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
+        assert hasattr(binding, n), f"{n} has no Python binding of the same name"
+
+
+def test_version_and_status_strings(lib):
+    assert H.hetis_attn_version() >= 100
+    seen = {H.hetis_attn_status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert H.hetis_attn_status_string(-99) == "unknown status"
+
+
+P = 0x1000  # a non-null fake pointer: every call below must fail before touching it
+
+
+def good():
+    return H.make_shape(4, 8, 8, 64, 16)
+
+
+def decode(shape, n_sel=4, **kw):
+    a = dict(q=P, k=P, v=P, bt=P, sl=P, hid=P, out=P)
+    a.update(kw)
+    return H.hetis_attn_decode(shape, a["q"], a["k"], a["v"], a["bt"], a["sl"], a["hid"], n_sel,
+                               0.125, a["out"], 0)
+
+
+@pytest.mark.parametrize("arg", ["q", "k", "v", "bt", "sl", "hid", "out"])
+def test_null_pointers(lib, arg):
+    assert decode(good(), **{arg: None}) == binding.HETIS_ERR_NULL
+
+
+def test_null_shape(lib):
+    rc = lib.hetis_attn_decode(None, P, P, P, P, P, P, 4, 0.125, P, None)
+    assert rc == binding.HETIS_ERR_NULL
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("batch", 0, binding.HETIS_ERR_BAD_SHAPE),
+    ("batch", -3, binding.HETIS_ERR_BAD_SHAPE),
+    ("n_q_heads", 0, binding.HETIS_ERR_BAD_SHAPE),
+    ("n_kv_heads", 3, binding.HETIS_ERR_BAD_SHAPE),       # 8 % 3 != 0
+    ("max_blocks_per_seq", 0, binding.HETIS_ERR_BAD_SHAPE),
+    ("kv_stride_head", -8, binding.HETIS_ERR_BAD_SHAPE),
+    ("kv_stride_head", 1028, binding.HETIS_ERR_BAD_SHAPE),  # not a multiple of 8
+    ("kv_stride_head", 512, binding.HETIS_ERR_BAD_SHAPE),   # smaller than a tile
+    ("head_dim", 96, binding.HETIS_ERR_UNSUPPORTED),
+    ("head_dim", 256, binding.HETIS_ERR_UNSUPPORTED),
+    ("block_size", 32, binding.HETIS_ERR_UNSUPPORTED),
+    ("n_kv_heads", 1, binding.HETIS_ERR_BAD_HEADS),        # r = 8 fine, but n_sel = 4 > 1
+    ("batch", 70000, binding.HETIS_ERR_UNSUPPORTED),
+])
+def test_bad_shapes(lib, field, value, status):
+    s = good()
+    setattr(s, field, value)
+    assert decode(s) == status
+
+
+def test_unsupported_group_size(lib):
+    s = H.make_shape(4, 24, 8, 64, 16)       # r = 3
+    assert decode(s) == binding.HETIS_ERR_UNSUPPORTED
+    s = H.make_shape(4, 128, 8, 64, 16)      # r = 16
+    assert decode(s) == binding.HETIS_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("n_sel", [0, -1, 9])
+def test_bad_head_count(lib, n_sel):
+    assert decode(good(), n_sel=n_sel) == binding.HETIS_ERR_BAD_HEADS
+
+
+def test_split_argument_errors(lib):
+    s = good()
+    assert H.hetis_attn_split_num_chunks(255, 512) == 1
+    assert H.hetis_attn_split_num_chunks(32768, 512) == 64
+    assert H.hetis_attn_split_num_chunks(513, 512) == 2
+    assert H.hetis_attn_split_num_chunks(100, 0) == binding.HETIS_ERR_UNSUPPORTED
+    assert H.hetis_attn_split_num_chunks(100, 24) == binding.HETIS_ERR_UNSUPPORTED
+    assert H.hetis_attn_split_num_chunks(0, 16) == binding.HETIS_ERR_WORKSPACE
+    rc, ob, lb = H.hetis_attn_split_workspace_bytes(s, 4, 256, 48)
+    assert rc == 0 and ob == 4 * 4 * 6 * 64 * 4 and lb == 4 * 4 * 6 * 4
+    assert H.hetis_attn_split_workspace_bytes(s, 4, 257, 48)[0] == binding.HETIS_ERR_WORKSPACE
+    assert H.hetis_attn_split_workspace_bytes(s, 4, 256, 40)[0] == binding.HETIS_ERR_UNSUPPORTED
+    assert H.hetis_attn_split_workspace_bytes(s, 0, 256, 48)[0] == binding.HETIS_ERR_BAD_HEADS
+
+    def split(chunk=48, msl=256, o=P, lse=P, n_sel=4):
+        return H.hetis_attn_decode_split(s, P, P, P, P, P, P, n_sel, 0.125, chunk, msl, o, lse, 0)
+    assert split(o=None) == binding.HETIS_ERR_NULL
+    assert split(lse=None) == binding.HETIS_ERR_NULL
+    assert split(chunk=8) == binding.HETIS_ERR_UNSUPPORTED
+    assert split(msl=0) == binding.HETIS_ERR_WORKSPACE
+    assert split(msl=4096) == binding.HETIS_ERR_WORKSPACE
+    assert split(n_sel=9) == binding.HETIS_ERR_BAD_HEADS
+
+    def merge(chunk=48, msl=256, o=P, lse=P, out=P):
+        return H.hetis_attn_merge(s, o, lse, P, P, 4, chunk, msl, out, 0)
+    assert merge(o=None) == binding.HETIS_ERR_NULL
+    assert merge(out=None) == binding.HETIS_ERR_NULL
+    assert merge(chunk=-16) == binding.HETIS_ERR_UNSUPPORTED
+    assert merge(msl=257) == binding.HETIS_ERR_WORKSPACE
+
+
+def test_validate_argument_errors(lib):
+    s = good()
+    assert H.hetis_attn_validate(s, None, P, P, 4, 10, 0) == binding.HETIS_ERR_NULL
+    assert H.hetis_attn_validate(s, P, P, P, 4, 0, 0) == binding.HETIS_ERR_BAD_SHAPE
+    assert H.hetis_attn_validate(s, P, P, P, 0, 10, 0) == binding.HETIS_ERR_BAD_HEADS
+
+
+def test_release_workspace_without_gpu_is_ok(lib):
+    assert H.hetis_attn_release_workspace() == binding.HETIS_OK
+
+
+def test_product_never_imports_the_checker():
+    pkg = os.path.join(ROOT, "paper_2509_08309_amd")
+    for root, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(root, fn)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), fn
+                assert "hetis_oracle" not in text and "liboracle" not in text, fn

@@ -1,0 +1,239 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 CPU checker.
+
+Bars: max abs error <= 4e-3 on fp16 outputs; head-subset rows bit-identical to
+the all-heads run; run-to-run determinism; rows of unselected heads untouched.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_08309_amd as H
+from paper_2509_08309_amd import workloads as W
+
+from gpu_harness import (SENTINEL, TOL, Dev, as_f64, bits, selected_rows, unselected_rows)
+
+pytestmark = pytest.mark.gpu
+
+PARTIAL_TOL = 1e-4   # fp32 partials are not rounded to fp16
+
+
+def oracle_of(w, head_ids=None, batch_idx=None):
+    hid = w.head_ids if head_ids is None else np.asarray(head_ids, dtype=np.int32)
+    q, bt, sl = w.q.numpy(), w.block_table, w.seq_lens
+    if batch_idx is not None:
+        q, bt, sl = q[batch_idx], bt[batch_idx], sl[batch_idx]
+    return oracle.attn_decode(q, w.k_cache.numpy(), w.v_cache.numpy(), bt, sl, hid, w.spec.scale)
+
+
+def check_against_oracle(out, ref, spec, head_ids, tol=TOL):
+    rows = selected_rows(spec, head_ids)
+    got = as_f64(out)[:, rows]
+    assert not np.isnan(got).any()
+    err = np.abs(got - ref[:, rows]).max()
+    assert err <= tol, f"max abs err {err:.3e} > {tol}"
+    return err
+
+
+def check_untouched(out, spec, head_ids):
+    rows = unselected_rows(spec, head_ids)
+    if rows:
+        assert (bits(out)[:, rows] == SENTINEL).all(), "rows of unselected heads were written"
+
+
+# ------------------------------------------------------------------ config 1
+def test_c1_tiny_subset_parity_and_bit_identity():
+    w = W.make_workload(W.SPECS["c1_tiny"])
+    d = Dev(w)
+    ref = oracle_of(w, list(range(8)))
+    sub = d.decode([1, 3, 4, 6])
+    full = d.decode(list(range(8)))
+    check_against_oracle(sub, ref, w.spec, [1, 3, 4, 6])
+    check_against_oracle(full, ref, w.spec, list(range(8)))
+    check_untouched(sub, w.spec, [1, 3, 4, 6])
+    assert np.array_equal(bits(sub)[:, [1, 3, 4, 6]], bits(full)[:, [1, 3, 4, 6]])
+    again = d.decode([6, 4, 3, 1])                      # order of head_ids is irrelevant
+    assert np.array_equal(bits(again), bits(sub))
+
+
+# ------------------------------------------------------------------ edge cases
+EDGE_LENS = [0, 1, 2, 15, 16, 17, 31, 33, 255, 256, 257, 300, 511, 512, 513, 1000]
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,hid", [
+    (4, 4, 64, [0, 2, 3]),
+    (4, 4, 128, [1, 3]),
+    (8, 4, 128, [0, 3]),       # r = 2
+    (8, 2, 64, [1]),           # r = 4
+    (16, 2, 128, [0, 1]),      # r = 8
+    (8, 1, 64, [0]),           # r = 8, D = 64
+])
+def test_edge_lengths(Hq, Hkv, D, hid):
+    w = W.make_custom(EDGE_LENS, Hq, Hkv, D, hid, seed=31, max_seq_len=1024)
+    d = Dev(w)
+    out = d.decode(hid)
+    ref = oracle_of(w, hid)
+    check_against_oracle(out, ref, w.spec, hid)
+    check_untouched(out, w.spec, hid)
+    rows = selected_rows(w.spec, hid)
+    assert (bits(out)[0, rows] == 0).all()               # length 0 -> +0.0
+    # length 1 returns that token's V row exactly
+    blk = w.block_table[1, 0]
+    r = Hq // Hkv
+    for g in hid:
+        for h in range(g * r, g * r + r):
+            assert np.array_equal(bits(out)[1, h], w.v_cache.numpy()[blk, g, 0].view(np.uint16))
+    full = d.decode(list(range(Hkv)))
+    assert np.array_equal(bits(full)[:, rows], bits(out)[:, rows])
+    assert np.array_equal(bits(d.decode(hid)), bits(out))   # deterministic
+
+
+def test_constant_keys_give_mean_and_shift_invariance():
+    w = W.make_custom([37, 300, 700], 2, 2, 128, [0, 1], seed=32, poison=False)
+    w.k_cache[...] = 0.375
+    d = Dev(w)
+    out = as_f64(d.decode([0, 1]))
+    v = w.v_cache.numpy().astype(np.float64)
+    for b, L in enumerate(w.seq_lens):
+        t = np.arange(L)
+        mean = v[w.block_table[b][t // 16], :, t % 16].mean(axis=0)
+        assert np.abs(out[b] - mean).max() <= TOL
+
+
+def test_block_permutation_invariance_bitwise():
+    w = W.make_custom([50, 333, 16, 600], 4, 4, 128, [0, 2], seed=33, max_seq_len=1024)
+    a = Dev(w).decode([0, 2])
+    rng = np.random.default_rng(5)
+    perm = rng.permutation(w.num_blocks)
+    k2 = torch.empty_like(w.k_cache)
+    v2 = torch.empty_like(w.v_cache)
+    k2[perm] = w.k_cache
+    v2[perm] = w.v_cache
+    w2 = W.Workload(w.spec, w.seq_lens,
+                    np.where(w.block_table >= 0, perm[np.maximum(w.block_table, 0)], -1).astype(np.int32),
+                    w.num_blocks, w.q, k2, v2, w.head_ids)
+    b = Dev(w2).decode([0, 2])
+    assert np.array_equal(bits(a), bits(b))
+
+
+def test_head_major_pool_through_strides():
+    w = W.make_custom([20, 45, 290], 3, 3, 64, [0, 2], seed=34, max_seq_len=512)
+    ref = Dev(w).decode([0, 2])
+    d = Dev(w)
+    d.k = w.k_cache.permute(1, 0, 2, 3).contiguous().cuda()     # [Hkv, num_blocks, 16, D]
+    d.v = w.v_cache.permute(1, 0, 2, 3).contiguous().cuda()
+    d.shape.kv_stride_block = 16 * 64
+    d.shape.kv_stride_head = w.num_blocks * 16 * 64
+    assert np.array_equal(bits(d.decode([0, 2])), bits(ref))
+
+
+# ------------------------------------------------------------------ split-KV and merge
+@pytest.mark.parametrize("chunk", [16, 48, 512])
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 128), (8, 2, 64)])
+def test_split_partials_and_merge(chunk, Hq, Hkv, D):
+    lens = [0, 1, 16, 49, 700, 513, 512]
+    hid = [1, 0]
+    w = W.make_custom(lens, Hq, Hkv, D, hid, seed=35, max_seq_len=704)
+    d = Dev(w)
+    msl = 700
+    C = H.hetis_attn_split_num_chunks(msl, chunk)
+    o_p, lse_p = d.split(hid, chunk, msl)
+    ro, rl = oracle.attn_partial(w.q.numpy(), w.k_cache.numpy(), w.v_cache.numpy(), w.block_table,
+                                 w.seq_lens, hid, w.spec.scale, chunk, C)
+    go, gl = as_f64(o_p), as_f64(lse_p)
+    assert np.array_equal(np.isnan(gl), np.isnan(rl)), "written chunk set differs"
+    assert np.array_equal(np.isnan(go), np.isnan(ro))
+    m = ~np.isnan(rl)
+    assert np.abs(gl[m] - rl[m]).max() <= PARTIAL_TOL
+    assert np.abs(go[~np.isnan(ro)] - ro[~np.isnan(ro)]).max() <= PARTIAL_TOL
+    out = d.merge(o_p, lse_p, hid, chunk, msl)
+    ref = oracle_of(w, hid)
+    check_against_oracle(out, ref, w.spec, hid)
+    check_untouched(out, w.spec, hid)
+    # split subset vs split full: bit-identical partials and outputs
+    o_f, lse_f = d.split(list(range(Hkv)), chunk, msl)
+    out_f = d.merge(o_f, lse_f, list(range(Hkv)), chunk, msl)
+    rows = selected_rows(w.spec, hid)
+    assert np.array_equal(bits(out_f)[:, rows], bits(out)[:, rows])
+
+
+def test_merge_kernel_alone_on_checker_partials():
+    lens = [0, 5, 100, 640]
+    hid = [0, 1]
+    w = W.make_custom(lens, 4, 2, 128, hid, seed=36, max_seq_len=640)
+    chunk, msl = 64, 640
+    C = 10
+    ro, rl = oracle.attn_partial(w.q.numpy(), w.k_cache.numpy(), w.v_cache.numpy(), w.block_table,
+                                 w.seq_lens, hid, w.spec.scale, chunk, C, fill=np.nan)
+    ref = oracle.attn_merge(ro, rl, w.seq_lens, hid, 4, 2, chunk)
+    d = Dev(w)
+    o_p = torch.from_numpy(ro.astype(np.float32)).cuda()
+    lse_p = torch.from_numpy(rl.astype(np.float32)).cuda()
+    out = d.merge(o_p, lse_p, hid, chunk, msl)
+    check_against_oracle(out, ref, w.spec, hid)
+    assert (bits(out)[0] == 0).all()
+
+
+# ------------------------------------------------------------------ full-size configs, sampled rows
+def sample_batch(w, n, seed):
+    """Indices of n sequences: the longest, the shortest and seeded random others."""
+    rng = np.random.default_rng(seed)
+    order = np.argsort(w.seq_lens)
+    pick = {int(order[0]), int(order[-1])}
+    while len(pick) < min(n, w.spec.batch):
+        pick.add(int(rng.integers(0, w.spec.batch)))
+    return np.array(sorted(pick))
+
+
+def full_size_check(name, n_seq, head_sample, all_heads):
+    spec = W.SPECS[name]
+    w = W.make_workload(spec, device="cuda:0")
+    d = Dev(w)
+    sub = d.decode(list(spec.head_ids))
+    idx = sample_batch(w, n_seq, spec.seed)
+    # the checker reads host memory
+    wh = W.Workload(spec, w.seq_lens, w.block_table, w.num_blocks, w.q.cpu(), w.k_cache.cpu(),
+                    w.v_cache.cpu(), w.head_ids)
+    ref = oracle_of(wh, head_sample, idx)
+    rows = selected_rows(spec, head_sample)
+    got = as_f64(sub)[idx][:, rows]
+    assert not np.isnan(got).any()
+    err = np.abs(got - ref[:, rows]).max()
+    assert err <= TOL, f"{name}: max abs err {err:.3e}"
+    check_untouched(sub, spec, spec.head_ids)
+    assert not torch.isnan(sub[:, selected_rows(spec, spec.head_ids)].float()).any()
+    if all_heads:
+        full = d.decode(list(range(spec.n_kv_heads)))
+        srows = selected_rows(spec, spec.head_ids)
+        assert np.array_equal(bits(full)[:, srows], bits(sub)[:, srows]), \
+            f"{name}: subset is not bit-identical to the slice of the all-heads run"
+    return d, wh, sub, idx
+
+
+def test_c2_7b_half_vs_all():
+    full_size_check("c2_7b_half", 6, [0, 7, 15], all_heads=True)
+
+
+def test_c3_13b_subset():
+    full_size_check("c3_13b_subset", 6, [27, 33, 39], all_heads=True)
+
+
+def test_c5_70b_gqa():
+    full_size_check("c5_70b_gqa", 5, [2, 7], all_heads=True)
+
+
+def test_c4_long_split_512_and_decode():
+    spec = W.SPECS["c4_13b_long"]
+    d, wh, out_dec, idx = full_size_check("c4_13b_long", 3, [0, 21, 39], all_heads=False)
+    hid = list(spec.head_ids)
+    o_p, lse_p = d.split(hid, spec.chunk_tokens, spec.max_seq_len)
+    out = d.merge(o_p, lse_p, hid, spec.chunk_tokens, spec.max_seq_len)
+    ref = oracle_of(wh, [0, 21, 39], idx)
+    got = as_f64(out)[idx][:, [0, 21, 39]]
+    err = np.abs(got - ref[:, [0, 21, 39]]).max()
+    assert err <= TOL, f"split path: max abs err {err:.3e}"
+    # head subset through the split path: bit-identical to the slice of the all-heads split run
+    sub_ids = [3, 17, 38]
+    o_s, lse_s = d.split(sub_ids, spec.chunk_tokens, spec.max_seq_len)
+    out_s = d.merge(o_s, lse_s, sub_ids, spec.chunk_tokens, spec.max_seq_len)
+    assert np.array_equal(bits(out_s)[:, sub_ids], bits(out)[:, sub_ids])
