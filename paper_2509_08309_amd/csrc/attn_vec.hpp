@@ -1,15 +1,14 @@
-// Vector (non-MFMA) chunk kernel: one workgroup per (sequence, selected KV head, chunk).
-//
-// Eq. (2b) restricted to the tokens of one chunk.  The path is HBM-bound (r flop per
-// KV byte), so the layout is chosen for the loads, not for the ALUs:
+// Vector (non-MFMA) chunk kernels: Eq. (2b) restricted to the tokens of one chunk of one
+// (sequence, selected KV head).  The path is HBM-bound (r flop per KV byte), so the layout
+// is chosen for the loads, not for the ALUs:
 //   - a (block, head) tile is 16 rows of D fp16 = 16*D*2 contiguous bytes; a wave reads
 //     it with 128-bit loads, lane l taking bytes [16 l, 16 l + 16) of each 1 KB slice, so
 //     D/8 neighbouring lanes hold one token row and a slice holds 64/(D/8) tokens;
 //   - q.k is a v_dot2 chain per lane followed by a DPP sum over the D/8 lanes of a row;
 //   - each group of D/8 lanes runs its own online softmax over the tokens it sees
 //     (exp2 domain, fp32), so p never leaves registers between q.k and p.v;
-//   - the lane groups of a wave, then the waves of the workgroup, are merged once at the
-//     end, in a fixed order, through shuffles and LDS.
+//   - the lane groups of a wave, then the waves of the workgroup, are merged once per
+//     chunk, in a fixed order, through shuffles and LDS.
 // Nothing depends on how many heads were selected: the result for one (sequence, head)
 // is a function of that sequence's length alone.
 #pragma once
@@ -22,12 +21,42 @@ struct VecState {
     float m[R];
     float l[R];
     float o[R][8];
+
+    __device__ __forceinline__ void reset()
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            m[r] = kNegBig;
+            l[r] = 0.f;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) o[r][x] = 0.f;
+        }
+    }
 };
+
+template <int D>
+struct TileRegs {
+    static constexpr int NI = 16 / (512 / D);   // 1 KB slices per tile
+    uint4 k[NI];
+    uint4 v[NI];
+};
+
+// Issue the 128-bit loads of one K tile and one V tile (no wait).
+template <int D>
+__device__ __forceinline__ void tile_issue(TileRegs<D> &t, const __half *k_cache,
+                                           const __half *v_cache, int64_t base, int lane)
+{
+    const uint4 *kp = reinterpret_cast<const uint4 *>(k_cache + base) + lane;
+    const uint4 *vp = reinterpret_cast<const uint4 *>(v_cache + base) + lane;
+#pragma unroll
+    for (int i = 0; i < TileRegs<D>::NI; ++i) t.k[i] = kp[i * 64];
+#pragma unroll
+    for (int i = 0; i < TileRegs<D>::NI; ++i) t.v[i] = vp[i * 64];
+}
 
 // One tile (16 tokens) of K and V held in registers -> update of the running state.
 template <int D, int R, bool MASKED>
-__device__ __forceinline__ void vec_tile_update(VecState<D, R> &st, const uint4 (&kb)[16 / (512 / D)],
-                                                const uint4 (&vb)[16 / (512 / D)],
+__device__ __forceinline__ void vec_tile_update(VecState<D, R> &st, const TileRegs<D> &t,
                                                 const __half2 (&qh)[R][4], float scale_log2,
                                                 int gid, int n_valid)
 {
@@ -38,7 +67,7 @@ __device__ __forceinline__ void vec_tile_update(VecState<D, R> &st, const uint4 
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         Pack16 kk;
-        kk.u = kb[i];
+        kk.u = t.k[i];
         const bool valid = !MASKED || (i * TPI + gid < n_valid);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -71,7 +100,7 @@ __device__ __forceinline__ void vec_tile_update(VecState<D, R> &st, const uint4 
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         Pack16 vv;
-        vv.u = vb[i];
+        vv.u = t.v[i];
         if (MASKED && !(i * TPI + gid < n_valid)) vv.u = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
@@ -82,108 +111,24 @@ __device__ __forceinline__ void vec_tile_update(VecState<D, R> &st, const uint4 
     }
 }
 
-template <int D, int R, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParams p)
+// Tile that may be the ragged last block of a sequence (n_valid < 16).
+template <int D, int R>
+__device__ __forceinline__ void vec_tile_update_any(VecState<D, R> &st, const TileRegs<D> &t,
+                                                    const __half2 (&qh)[R][4], float scale_log2,
+                                                    int gid, int n_valid)
 {
-    constexpr int LPR = D / 8;
-    constexpr int TPI = 64 / LPR;
-    constexpr int NI = 16 / TPI;
-    constexpr int TILE = kBlockTokens * D;      // elements per tile
+    if (n_valid < kBlockTokens)
+        vec_tile_update<D, R, true>(st, t, qh, scale_log2, gid, n_valid);
+    else
+        vec_tile_update<D, R, false>(st, t, qh, scale_log2, gid, kBlockTokens);
+}
 
-    const int c = blockIdx.x;
-    const int si = blockIdx.y;
-    const int b = blockIdx.z;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int gid = lane / LPR;
-    const int sub = lane % LPR;
-
-    const int L = p.seq_lens[b];
-    const int g = p.head_ids[si];
-    const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-    const bool to_out = p.direct_single && n_chunks <= 1;
-
-    if (L <= 0) {
-        // zero-length sequence: zeros, written once (by chunk 0) when this pass owns `out`
-        if (to_out && c == 0) {
-            for (int idx = tid; idx < R * D; idx += NW * 64) {
-                const int r = idx / D, d = idx % D;
-                p.out[((int64_t)b * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(0.f);
-            }
-        }
-        return;
-    }
-    if (c >= n_chunks) return;
-
-    const int t0 = c * p.chunk_tokens;
-    const int t1 = min(L, t0 + p.chunk_tokens);
-    const int n_tok = t1 - t0;
-    const int nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
-    const int rem = n_tok & (kBlockTokens - 1);
-    const int32_t *bt = p.block_table + (int64_t)b * p.max_blocks_per_seq + t0 / kBlockTokens;
-    const int64_t head_off = (int64_t)g * p.stride_head;
-
-    // this lane's 8 query dims for each of the R heads of the group
-    __half2 qh[R][4];
+// Merge the 64/(D/8) lane groups of a wave (xor butterfly over the group index).
+template <int D, int R>
+__device__ __forceinline__ void vec_wave_merge(VecState<D, R> &st)
+{
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        Pack16 t;
-        t.u = *reinterpret_cast<const uint4 *>(p.q + ((int64_t)b * p.n_q_heads + g * R + r) * D + sub * 8);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) qh[r][x] = t.h2[x];
-    }
-
-    VecState<D, R> st;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        st.m[r] = kNegBig;
-        st.l[r] = 0.f;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) st.o[r][x] = 0.f;
-    }
-
-    // wave w takes blocks w, w+NW, ...; the next tile is in flight while one is consumed
-    uint4 kc[NI], vc[NI], kn[NI], vn[NI];
-    int j = wave;
-    if (j < nblk) {
-        const int64_t base = (int64_t)bt[j] * p.stride_block + head_off;
-        const uint4 *kp = reinterpret_cast<const uint4 *>(p.k_cache + base) + lane;
-        const uint4 *vp = reinterpret_cast<const uint4 *>(p.v_cache + base) + lane;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) kc[i] = kp[i * 64];
-#pragma unroll
-        for (int i = 0; i < NI; ++i) vc[i] = vp[i * 64];
-    }
-    int blk_next = (j + NW < nblk) ? bt[j + NW] : 0;
-    while (j < nblk) {
-        const int jn = j + NW;
-        if (jn < nblk) {
-            const int64_t base = (int64_t)blk_next * p.stride_block + head_off;
-            const uint4 *kp = reinterpret_cast<const uint4 *>(p.k_cache + base) + lane;
-            const uint4 *vp = reinterpret_cast<const uint4 *>(p.v_cache + base) + lane;
-#pragma unroll
-            for (int i = 0; i < NI; ++i) kn[i] = kp[i * 64];
-#pragma unroll
-            for (int i = 0; i < NI; ++i) vn[i] = vp[i * 64];
-            blk_next = (jn + NW < nblk) ? bt[jn + NW] : 0;
-        }
-        if (rem != 0 && j == nblk - 1)
-            vec_tile_update<D, R, true>(st, kc, vc, qh, p.scale_log2, gid, rem);
-        else
-            vec_tile_update<D, R, false>(st, kc, vc, qh, p.scale_log2, gid, kBlockTokens);
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            kc[i] = kn[i];
-            vc[i] = vn[i];
-        }
-        j = jn;
-    }
-    (void)TILE;
-
-    // merge the TPI lane groups of the wave (xor butterfly over the group index)
-#pragma unroll
-    for (int mask = LPR; mask < 64; mask <<= 1) {
+    for (int mask = D / 8; mask < 64; mask <<= 1) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const float m2 = __shfl_xor(st.m[r], mask, 64);
@@ -200,35 +145,51 @@ __global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParam
             }
         }
     }
+}
 
-    // merge the waves through LDS, ascending wave order
-    __shared__ float sm_o[NW][R][D];
-    __shared__ float sm_m[NW][R];
-    __shared__ float sm_l[NW][R];
+// LDS area through which the waves of a workgroup are merged (ascending wave order).
+template <int D, int R, int NW>
+struct WaveMergeLds {
+    float o[NW][R][D];
+    float m[NW][R];
+    float l[NW][R];
+};
+
+template <int D, int R, int NW>
+__device__ __forceinline__ void vec_lds_put(WaveMergeLds<D, R, NW> &sm, const VecState<D, R> &st,
+                                            int wave, int gid, int sub)
+{
     if (gid == 0) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
 #pragma unroll
-            for (int x = 0; x < 8; ++x) sm_o[wave][r][sub * 8 + x] = st.o[r][x];
+            for (int x = 0; x < 8; ++x) sm.o[wave][r][sub * 8 + x] = st.o[r][x];
             if (sub == 0) {
-                sm_m[wave][r] = st.m[r];
-                sm_l[wave][r] = st.l[r];
+                sm.m[wave][r] = st.m[r];
+                sm.l[wave][r] = st.l[r];
             }
         }
     }
-    __syncthreads();
+}
+
+// After a barrier: final result of the chunk, to `out` (fp16) or to the partial buffers.
+template <int D, int R, int NW>
+__device__ __forceinline__ void vec_lds_finish(const WaveMergeLds<D, R, NW> &sm,
+                                               const AttnParams &p, int tid, int b, int g, int si,
+                                               int c, bool to_out)
+{
     const int rows = p.n_sel * R;
     for (int idx = tid; idx < R * D; idx += NW * 64) {
         const int r = idx / D, d = idx % D;
-        float M = sm_m[0][r];
+        float M = sm.m[0][r];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w][r]);
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm.m[w][r]);
         float acc = 0.f, lsum = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-            const float a = fast_exp2(sm_m[w][r] - M);
-            acc += sm_o[w][r][d] * a;
-            lsum += sm_l[w][r] * a;
+            const float a = fast_exp2(sm.m[w][r] - M);
+            acc += sm.o[w][r][d] * a;
+            lsum += sm.l[w][r] * a;
         }
         const float res = acc / lsum;
         if (to_out) {
@@ -238,6 +199,250 @@ __global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParam
             p.o_partial[row * D + d] = res;
             if (d == 0) p.lse_partial[row] = (M + fast_log2(lsum)) * kLn2;
         }
+    }
+}
+
+template <int D, int R, int NW>
+__device__ __forceinline__ void vec_write_zeros(const AttnParams &p, int tid, int b, int g)
+{
+    for (int idx = tid; idx < R * D; idx += NW * 64) {
+        const int r = idx / D, d = idx % D;
+        p.out[((int64_t)b * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(0.f);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Simple form: one workgroup per (chunk slot, selected head, sequence); slots past the end
+// of a sequence exit at once.  Used when the batch is too large for the persistent form.
+// ---------------------------------------------------------------------------------------
+template <int D, int R, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParams p)
+{
+    constexpr int LPR = D / 8;
+    const int c = blockIdx.x;
+    const int si = blockIdx.y;
+    const int b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int gid = lane / LPR;
+    const int sub = lane % LPR;
+
+    const int L = p.seq_lens[b];
+    const int g = p.head_ids[si];
+    const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+    const bool to_out = p.direct_single && n_chunks <= 1;
+
+    if (L <= 0) {
+        if (to_out && c == 0) vec_write_zeros<D, R, NW>(p, tid, b, g);
+        return;
+    }
+    if (c >= n_chunks) return;
+
+    const int t0 = c * p.chunk_tokens;
+    const int n_tok = min(L, t0 + p.chunk_tokens) - t0;
+    const int nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
+    const int rem = n_tok & (kBlockTokens - 1);
+    const int32_t *bt = p.block_table + (int64_t)b * p.max_blocks_per_seq + t0 / kBlockTokens;
+    const int64_t head_off = (int64_t)g * p.stride_head;
+
+    __half2 qh[R][4];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        Pack16 t;
+        t.u = *reinterpret_cast<const uint4 *>(p.q + ((int64_t)b * p.n_q_heads + g * R + r) * D + sub * 8);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) qh[r][x] = t.h2[x];
+    }
+
+    VecState<D, R> st;
+    st.reset();
+    TileRegs<D> cur, nxt;
+    int j = wave;
+    if (j < nblk) tile_issue<D>(cur, p.k_cache, p.v_cache, (int64_t)bt[j] * p.stride_block + head_off, lane);
+    while (j < nblk) {
+        const int jn = j + NW;
+        if (jn < nblk)
+            tile_issue<D>(nxt, p.k_cache, p.v_cache, (int64_t)bt[jn] * p.stride_block + head_off, lane);
+        const int n_valid = (rem != 0 && j == nblk - 1) ? rem : kBlockTokens;
+        vec_tile_update_any<D, R>(st, cur, qh, p.scale_log2, gid, n_valid);
+        cur = nxt;
+        j = jn;
+    }
+    vec_wave_merge<D, R>(st);
+    __shared__ WaveMergeLds<D, R, NW> sm;
+    vec_lds_put<D, R, NW>(sm, st, wave, gid, sub);
+    __syncthreads();
+    vec_lds_finish<D, R, NW>(sm, p, tid, b, g, si, c, to_out);
+}
+
+// ---------------------------------------------------------------------------------------
+// Persistent form.  Work enumeration: every workgroup scans the sequence lengths into a
+// table of first-chunk indices (LDS), which turns a flat item number into (sequence,
+// chunk, selected head) without launching a workgroup per possible chunk.  Workgroup k
+// takes items k, k + G, k + 2G, ...  Inside an item each wave streams its tiles through a
+// two-slot register ring: a slot is refilled right after it has been consumed, so that one
+// to two tile pairs (8-16 KB per wave) are always in flight, and the first two tiles of the
+// next item are requested before the current item's merge and store.
+// Dynamic LDS: int lens[batch], int first[batch + 1], then two WaveMergeLds areas.
+// ---------------------------------------------------------------------------------------
+template <int D, int R, int NW>
+struct PersistItem {
+    int b, si, c, g;
+    int nblk;       // blocks of this chunk
+    int rem;        // tokens in the ragged last block (0: none)
+    int n_my;       // tiles this wave owns: blocks wave, wave+NW, ...
+    int ids;        // lane i: physical block of this wave's i-th tile
+    bool to_out;
+    bool zero;      // length-0 sequence whose zeros this pass writes
+    int64_t head_off;
+    __half2 qh[R][4];
+};
+
+template <int D, int R, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_chunk_vec_persistent_kernel(const AttnParams p,
+                                                                            const int batch)
+{
+    constexpr int LPR = D / 8;
+    constexpr int NT = NW * 64;
+    using Lds = WaveMergeLds<D, R, NW>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    int *lens = reinterpret_cast<int *>(smem);
+    int *first = lens + batch;
+    Lds *sm = reinterpret_cast<Lds *>(smem + (((size_t)(2 * batch + 1) * sizeof(int) + 15) & ~(size_t)15));
+    __shared__ int scan[NT];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int gid = lane / LPR;
+    const int sub = lane % LPR;
+
+    // ---- work enumeration: exclusive scan of items per sequence
+    {
+        const int seg = (batch + NT - 1) / NT;
+        const int lo = min(batch, tid * seg), hi = min(batch, lo + seg);
+        int sum = 0;
+        for (int b = lo; b < hi; ++b) {
+            const int L = p.seq_lens[b];
+            lens[b] = L;
+            int n = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+            if (L <= 0) n = p.direct_single ? 1 : 0;      // the item that writes the zeros
+            sum += n;
+        }
+        scan[tid] = sum;
+        __syncthreads();
+        for (int off = 1; off < NT; off <<= 1) {
+            const int v = (tid >= off) ? scan[tid - off] : 0;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        int run = scan[tid] - sum;
+        for (int b = lo; b < hi; ++b) {
+            first[b] = run;
+            const int L = lens[b];
+            int n = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+            if (L <= 0) n = p.direct_single ? 1 : 0;
+            run += n;
+        }
+        if (tid == NT - 1) first[batch] = scan[NT - 1];
+        __syncthreads();
+    }
+    const int total = first[batch] * p.n_sel;
+    const int G = gridDim.x;
+
+    int b_scan = 0;   // sequences are visited in ascending order: resume the search where it ended
+    auto setup = [&](int w, PersistItem<D, R, NW> &it) {
+        const int cg = w / p.n_sel;
+        it.si = w - cg * p.n_sel;
+        while (first[b_scan + 1] <= cg) ++b_scan;
+        b_scan = __builtin_amdgcn_readfirstlane(b_scan);
+        it.b = b_scan;
+        it.c = __builtin_amdgcn_readfirstlane(cg - first[it.b]);
+        const int L = __builtin_amdgcn_readfirstlane(lens[it.b]);
+        it.g = p.head_ids[it.si];
+        const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+        it.to_out = p.direct_single && n_chunks <= 1;
+        it.zero = L <= 0;
+        const int t0 = it.c * p.chunk_tokens;
+        const int n_tok = it.zero ? 0 : min(L, t0 + p.chunk_tokens) - t0;
+        it.nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
+        it.rem = n_tok & (kBlockTokens - 1);
+        it.n_my = (it.nblk > wave) ? (it.nblk - wave + NW - 1) / NW : 0;
+        it.head_off = (int64_t)it.g * p.stride_head;
+        const int32_t *bt = p.block_table + (int64_t)it.b * p.max_blocks_per_seq + t0 / kBlockTokens;
+        it.ids = (lane < it.n_my) ? bt[wave + NW * lane] : 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            Pack16 t;
+            t.u = *reinterpret_cast<const uint4 *>(
+                p.q + ((int64_t)it.b * p.n_q_heads + it.g * R + r) * D + sub * 8);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) it.qh[r][x] = t.h2[x];
+        }
+    };
+    auto issue = [&](TileRegs<D> &t, const PersistItem<D, R, NW> &it, int i) {
+        const int blk = __builtin_amdgcn_readlane(it.ids, i);
+        tile_issue<D>(t, p.k_cache, p.v_cache, (int64_t)blk * p.stride_block + it.head_off, lane);
+    };
+
+    int w = blockIdx.x;
+    if (w >= total) return;
+    PersistItem<D, R, NW> cur, nxt;
+    TileRegs<D> A, B;
+    setup(w, cur);
+    if (cur.n_my > 0) issue(A, cur, 0);
+    if (cur.n_my > 1) issue(B, cur, 1);
+    int parity = 0;
+    for (;;) {
+        const int wn = w + G;
+        const bool more = wn < total;
+        if (more) setup(wn, nxt);
+
+        VecState<D, R> st;
+        st.reset();
+        const int n_my = cur.n_my;
+        // the ragged block, if any, is the chunk's last block: the last tile of one wave
+        const bool mine_ragged = cur.rem != 0 && ((cur.nblk - 1) % NW) == wave;
+        int i = 0;
+        for (; i + 3 < n_my; i += 2) {            // steady state: both slots are refilled
+            vec_tile_update<D, R, false>(st, A, cur.qh, p.scale_log2, gid, kBlockTokens);
+            issue(A, cur, i + 2);
+            vec_tile_update<D, R, false>(st, B, cur.qh, p.scale_log2, gid, kBlockTokens);
+            issue(B, cur, i + 3);
+        }
+        const int left = n_my - i;                // 0..3 tiles, A = tile i, B = tile i+1
+        if (left >= 1) {
+            const int nv = (mine_ragged && left == 1) ? cur.rem : kBlockTokens;
+            vec_tile_update_any<D, R>(st, A, cur.qh, p.scale_log2, gid, nv);
+            if (left == 3) issue(A, cur, i + 2);
+        }
+        if (left >= 2) {
+            const int nv = (mine_ragged && left == 2) ? cur.rem : kBlockTokens;
+            vec_tile_update_any<D, R>(st, B, cur.qh, p.scale_log2, gid, nv);
+        }
+        if (left == 3) {
+            const int nv = mine_ragged ? cur.rem : kBlockTokens;
+            vec_tile_update_any<D, R>(st, A, cur.qh, p.scale_log2, gid, nv);
+        }
+        // request the next item's first tiles before this item's merge and store
+        if (more) {
+            if (nxt.n_my > 0) issue(A, nxt, 0);
+            if (nxt.n_my > 1) issue(B, nxt, 1);
+        }
+        if (cur.zero) {
+            vec_write_zeros<D, R, NW>(p, tid, cur.b, cur.g);
+        } else {
+            vec_wave_merge<D, R>(st);
+            vec_lds_put<D, R, NW>(sm[parity], st, wave, gid, sub);
+            __syncthreads();
+            vec_lds_finish<D, R, NW>(sm[parity], p, tid, cur.b, cur.g, cur.si, cur.c, cur.to_out);
+            parity ^= 1;
+        }
+        if (!more) break;
+        cur = nxt;
+        w = wn;
     }
 }
 

@@ -15,6 +15,10 @@ namespace hetis {
 // the all-heads call bit for bit.
 constexpr int kDecodeChunkTokens = 256;
 constexpr int kVecWaves = 4;
+// Largest batch whose length scan fits the persistent kernel's LDS table.
+constexpr int kMaxPersistBatch = 4096;
+// A wave keeps the block ids of its tiles of one chunk in one register (64 lanes).
+constexpr int kMaxChunkTokens = 64 * kVecWaves * kBlockTokens;
 
 struct Checked {
     int group;          // r
@@ -47,23 +51,74 @@ static int check_shape(const hetis_attn_shape *s, int32_t n_sel, Checked *c)
 
 static int check_chunking(const hetis_attn_shape *s, int32_t chunk_tokens, int32_t max_seq_len)
 {
-    if (chunk_tokens <= 0 || chunk_tokens % kBlockTokens != 0) return HETIS_ERR_UNSUPPORTED;
+    if (chunk_tokens <= 0 || chunk_tokens % kBlockTokens != 0 || chunk_tokens > kMaxChunkTokens)
+        return HETIS_ERR_UNSUPPORTED;
     if (max_seq_len < 1 || (int64_t)max_seq_len > (int64_t)s->max_blocks_per_seq * kBlockTokens)
         return HETIS_ERR_WORKSPACE;
     return HETIS_OK;
 }
 
-template <int D, int R>
-static void launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
+// Number of compute units of the current device (cached per device).
+static int device_cu_count()
 {
-    dim3 grid(p.max_chunks, p.n_sel, batch);
-    attn_chunk_vec_kernel<D, R, kVecWaves><<<grid, kVecWaves * 64, 0, st>>>(p);
+    static std::mutex mu;
+    static std::vector<int> cus;
+    std::lock_guard<std::mutex> lock(mu);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if ((size_t)dev >= cus.size()) cus.resize(dev + 1, 0);
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
+template <int D, int R>
+static int launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
+{
+    constexpr int NW = kVecWaves;
+    const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
+    if (batch > kMaxPersistBatch || max_items >= (int64_t)1 << 31) {
+        dim3 grid(p.max_chunks, p.n_sel, batch);
+        attn_chunk_vec_kernel<D, R, NW><<<grid, NW * 64, 0, st>>>(p);
+        return HETIS_OK;
+    }
+    auto kernel = attn_chunk_vec_persistent_kernel<D, R, NW>;
+    const size_t lds = (((size_t)(2 * batch + 1) * sizeof(int) + 15) & ~(size_t)15) +
+                       2 * sizeof(WaveMergeLds<D, R, NW>);
+    // resident workgroups per compute unit for this instantiation and LDS size
+    static std::mutex mu;
+    static size_t cached_lds = (size_t)-1;
+    static int cached_occ = 0;
+    int occ = 0;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (cached_lds != lds) {
+            int n = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, NW * 64, lds) != hipSuccess || n < 1)
+                return HETIS_ERR_LAUNCH;
+            cached_occ = n;
+            cached_lds = lds;
+        }
+        occ = cached_occ;
+    }
+    const int cus = device_cu_count();
+    if (cus <= 0) return HETIS_ERR_LAUNCH;
+    int64_t G = (int64_t)cus * occ;
+    if (G > max_items) G = max_items;
+    // a multiple of the head count keeps the heads of one chunk on neighbouring workgroups
+    if (G > p.n_sel) G -= G % p.n_sel;
+    kernel<<<dim3((unsigned)G), NW * 64, lds, st>>>(p, batch);
+    return HETIS_OK;
 }
 
 static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
 {
 #define HETIS_CASE(DD, RR) \
-    if (D == DD && r == RR) { launch_chunk_vec<DD, RR>(p, batch, st); return HETIS_OK; }
+    if (D == DD && r == RR) return launch_chunk_vec<DD, RR>(p, batch, st);
     HETIS_CASE(128, 1) HETIS_CASE(128, 2) HETIS_CASE(128, 4) HETIS_CASE(128, 8)
     HETIS_CASE(64, 1) HETIS_CASE(64, 2) HETIS_CASE(64, 4) HETIS_CASE(64, 8)
 #undef HETIS_CASE
@@ -214,7 +269,8 @@ int hetis_attn_release_workspace(void)
 
 int hetis_attn_split_num_chunks(int32_t max_seq_len, int32_t chunk_tokens)
 {
-    if (chunk_tokens <= 0 || chunk_tokens % kBlockTokens != 0) return HETIS_ERR_UNSUPPORTED;
+    if (chunk_tokens <= 0 || chunk_tokens % kBlockTokens != 0 || chunk_tokens > kMaxChunkTokens)
+        return HETIS_ERR_UNSUPPORTED;
     if (max_seq_len < 1) return HETIS_ERR_WORKSPACE;
     return (int)(((int64_t)max_seq_len + chunk_tokens - 1) / chunk_tokens);
 }
