@@ -163,6 +163,17 @@ int hetis_attn_merge(const hetis_attn_shape *shape, const float *o_partial,
                      void *stream);
 
 /*
+ * Measurement hook.  After hetis_attn_profile_events(begin, end) with two hipEvent_t
+ * (passed as void*, created by the caller with timing enabled), every later
+ * hetis_attn_decode / hetis_attn_decode_split call made by the SAME host thread
+ * records `begin` on its stream right before, and `end` right after, the launch
+ * of its chunk kernel (the kernel that streams the KV cache; the merge launch is
+ * outside the pair).  Pass (NULL, NULL) to switch the hook off.  The state is
+ * per host thread.  Returns HETIS_OK, or HETIS_ERR_NULL if exactly one is NULL.
+ */
+int hetis_attn_profile_events(void *begin, void *end);
+
+/*
  * Debug helper, not for the hot path: copies seq_lens, head_ids and the used
  * part of block_table to the host (synchronises `stream`) and checks
  * 0 <= seq_lens[b] <= 16*max_blocks_per_seq, 0 <= head_ids[i] < Hkv and

@@ -7,7 +7,7 @@ its absence is an error, never a fallback.
 """
 from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
-    HetisError, check, hetis_attn_decode, hetis_attn_decode_split, hetis_attn_merge,
+    HetisError, check, hetis_attn_decode, hetis_attn_decode_split, hetis_attn_merge, hetis_attn_profile_events,
     hetis_attn_release_workspace, hetis_attn_shape, hetis_attn_split_num_chunks,
     hetis_attn_split_workspace_bytes, hetis_attn_status_string, hetis_attn_validate,
     hetis_attn_version, make_shape,

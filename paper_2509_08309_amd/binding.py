@@ -13,7 +13,8 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libhetis_attn.so")
+# HETIS_ATTN_LIB (optional) points at another build of the same library, e.g. a tuning variant.
+LIB_PATH = os.environ.get("HETIS_ATTN_LIB") or os.path.join(HERE, "libhetis_attn.so")
 
 HETIS_OK = 0
 HETIS_ERR_NULL = -1
@@ -76,6 +77,8 @@ def load(build_if_missing: bool = False):
                                             vp, vp, vp]
     lib.hetis_attn_merge.restype = C.c_int
     lib.hetis_attn_merge.argtypes = [shp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.hetis_attn_profile_events.restype = C.c_int
+    lib.hetis_attn_profile_events.argtypes = [vp, vp]
     lib.hetis_attn_validate.restype = C.c_int
     lib.hetis_attn_validate.argtypes = [shp, vp, vp, vp, i32, i64, vp]
     _lib = lib
@@ -154,6 +157,11 @@ def hetis_attn_merge(shape, o_partial, lse_partial, seq_lens, head_ids, n_sel_he
                                    _ptr(seq_lens), _ptr(head_ids), int(n_sel_heads),
                                    int(chunk_tokens), int(max_seq_len), _ptr(out),
                                    _stream(stream))
+
+
+def hetis_attn_profile_events(begin, end) -> int:
+    """begin/end: raw hipEvent_t handles (ints, e.g. torch.cuda.Event.cuda_event) or None."""
+    return load().hetis_attn_profile_events(begin, end)
 
 
 def hetis_attn_validate(shape, block_table, seq_lens, head_ids, n_sel_heads, num_blocks,

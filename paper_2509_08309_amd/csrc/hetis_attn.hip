@@ -3,6 +3,7 @@
 // exercised on a machine without a GPU.
 #include "../../include/hetis_attn.h"
 
+#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -13,10 +14,14 @@ namespace hetis {
 // Tokens per chunk of hetis_attn_decode.  A compile-time constant: the chunking of a
 // sequence must depend on its length only, or a head-subset call could not reproduce
 // the all-heads call bit for bit.
-constexpr int kDecodeChunkTokens = 256;
+#ifndef HETIS_DECODE_CHUNK_TOKENS
+#define HETIS_DECODE_CHUNK_TOKENS 256
+#endif
+constexpr int kDecodeChunkTokens = HETIS_DECODE_CHUNK_TOKENS;
 constexpr int kVecWaves = 4;
 // Largest batch whose length scan fits the persistent kernel's LDS table.
 constexpr int kMaxPersistBatch = 4096;
+constexpr int kMaxPersistHeads = 1024;
 // A wave keeps the block ids of its tiles of one chunk in one register (64 lanes).
 constexpr int kMaxChunkTokens = 64 * kVecWaves * kBlockTokens;
 
@@ -81,14 +86,13 @@ static int launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
 {
     constexpr int NW = kVecWaves;
     const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
-    if (batch > kMaxPersistBatch || max_items >= (int64_t)1 << 31) {
+    if (batch > kMaxPersistBatch || p.n_sel > kMaxPersistHeads || max_items >= (int64_t)1 << 31) {
         dim3 grid(p.max_chunks, p.n_sel, batch);
         attn_chunk_vec_kernel<D, R, NW><<<grid, NW * 64, 0, st>>>(p);
         return HETIS_OK;
     }
     auto kernel = attn_chunk_vec_persistent_kernel<D, R, NW>;
-    const size_t lds = (((size_t)(2 * batch + 1) * sizeof(int) + 15) & ~(size_t)15) +
-                       2 * sizeof(WaveMergeLds<D, R, NW>);
+    const size_t lds = persist_table_bytes<D, R, NW>(batch, p.n_sel) + 2 * sizeof(WaveMergeLds<D, R, NW>);
     // resident workgroups per compute unit for this instantiation and LDS size
     static std::mutex mu;
     static size_t cached_lds = (size_t)-1;
@@ -98,7 +102,7 @@ static int launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
         std::lock_guard<std::mutex> lock(mu);
         if (cached_lds != lds) {
             int n = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, NW * 64, lds) != hipSuccess || n < 1)
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, (NW + 1) * 64, lds) != hipSuccess || n < 1)
                 return HETIS_ERR_LAUNCH;
             cached_occ = n;
             cached_lds = lds;
@@ -107,15 +111,23 @@ static int launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
     }
     const int cus = device_cu_count();
     if (cus <= 0) return HETIS_ERR_LAUNCH;
+    // HETIS_ATTN_WGS_PER_CU (optional, read once): cap on resident workgroups per compute unit.
+    // It changes how items are spread over workgroups, never the arithmetic of an item.
+    static const int env_cap = [] {
+        const char *e = std::getenv("HETIS_ATTN_WGS_PER_CU");
+        const int v = e ? std::atoi(e) : 0;
+        return v > 0 ? v : 0;
+    }();
+    if (env_cap > 0 && occ > env_cap) occ = env_cap;
     int64_t G = (int64_t)cus * occ;
     if (G > max_items) G = max_items;
     // a multiple of the head count keeps the heads of one chunk on neighbouring workgroups
     if (G > p.n_sel) G -= G % p.n_sel;
-    kernel<<<dim3((unsigned)G), NW * 64, lds, st>>>(p, batch);
+    kernel<<<dim3((unsigned)G), (NW + 1) * 64, lds, st>>>(p, batch);
     return HETIS_OK;
 }
 
-static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
+static int dispatch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
 {
 #define HETIS_CASE(DD, RR) \
     if (D == DD && r == RR) return launch_chunk_vec<DD, RR>(p, batch, st);
@@ -123,6 +135,19 @@ static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream
     HETIS_CASE(64, 1) HETIS_CASE(64, 2) HETIS_CASE(64, 4) HETIS_CASE(64, 8)
 #undef HETIS_CASE
     return HETIS_ERR_UNSUPPORTED;
+}
+
+// Optional events around the chunk-kernel launch (measurement hook, per host thread).
+static thread_local hipEvent_t t_prof_begin = nullptr;
+static thread_local hipEvent_t t_prof_end = nullptr;
+
+static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
+{
+    if (t_prof_begin && hipEventRecord(t_prof_begin, st) != hipSuccess) return HETIS_ERR_LAUNCH;
+    const int rc = dispatch_chunks(p, D, r, batch, st);
+    if (rc != HETIS_OK) return rc;
+    if (t_prof_end && hipEventRecord(t_prof_end, st) != hipSuccess) return HETIS_ERR_LAUNCH;
+    return HETIS_OK;
 }
 
 static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream_t st)
@@ -134,7 +159,8 @@ static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream
         attn_merge_kernel<64><<<grid, 64, 0, st>>>(p, r);
 }
 
-// Internal workspace of hetis_attn_decode, one per device, grown on demand.
+// Internal workspace of hetis_attn_decode (fp32 chunk partials), one per device, grown on
+// demand; its contents are meaningless between launches.
 struct Workspace {
     float *ptr = nullptr;
     size_t bytes = 0;
@@ -153,15 +179,15 @@ static int workspace_for(size_t need, float **out)
         if (w.ptr) {
             if (hipDeviceSynchronize() != hipSuccess) return HETIS_ERR_ALLOC;
             (void)hipFree(w.ptr);
-            w.ptr = nullptr;
-            w.bytes = 0;
+            w = Workspace();
         }
         const size_t want = need + need / 4;
-        if (hipMalloc((void **)&w.ptr, want) != hipSuccess) {
-            w.ptr = nullptr;
+        void *ptr = nullptr;
+        if (hipMalloc(&ptr, want) != hipSuccess) {
             (void)hipGetLastError();
             return HETIS_ERR_ALLOC;
         }
+        w.ptr = static_cast<float *>(ptr);
         w.bytes = want;
     }
     *out = w.ptr;
@@ -234,9 +260,8 @@ int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *
     hipStream_t st = (hipStream_t)stream;
     if (p.max_chunks > 1) {
         const size_t rows = (size_t)shape->batch * n_sel_heads * c.group * p.max_chunks;
-        const size_t need = rows * (shape->head_dim + 1) * sizeof(float);
         float *ws = nullptr;
-        rc = workspace_for(need, &ws);
+        rc = workspace_for(rows * (shape->head_dim + 1) * sizeof(float), &ws);
         if (rc != HETIS_OK) return rc;
         p.o_partial = ws;
         p.lse_partial = ws + rows * shape->head_dim;
@@ -339,6 +364,14 @@ int hetis_attn_merge(const hetis_attn_shape *shape, const float *o_partial,
     p.lse_partial = const_cast<float *>(lse_partial);
     launch_merge(p, shape->head_dim, c.group, shape->batch, (hipStream_t)stream);
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
+
+int hetis_attn_profile_events(void *begin, void *end)
+{
+    if ((begin == nullptr) != (end == nullptr)) return HETIS_ERR_NULL;
+    t_prof_begin = (hipEvent_t)begin;
+    t_prof_end = (hipEvent_t)end;
+    return HETIS_OK;
 }
 
 int hetis_attn_validate(const hetis_attn_shape *shape, const int32_t *block_table,
