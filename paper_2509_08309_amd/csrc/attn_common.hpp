@@ -54,6 +54,26 @@ __device__ __forceinline__ float group_sum(float x)
     return x;
 }
 
+// Buffer descriptor covering exactly one (block, head) tile, or nothing.  With valid == false
+// the descriptor spans 0 bytes: the hardware range check then makes every lane of a load
+// return zeros without touching memory, while the instruction still takes its place in the
+// in-order load counter.  This lets the tile ring issue every refill unconditionally, which
+// keeps the compiler's wait counts exact (a load that is issued only on some paths forces
+// full drains).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const __half *tile, int tile_bytes,
+                                                            bool valid)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(tile), 0,
+                                             valid ? tile_bytes : 0, 0x00020000);
+}
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 buffer_load_u4(__amdgpu_buffer_rsrc_t r, int byte_offset)
+{
+    const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 0);
+    return make_uint4(x.x, x.y, x.z, x.w);
+}
+
 union Pack16 {
     uint4 u;
     __half2 h2[4];

@@ -7,6 +7,7 @@
 #include <mutex>
 #include <vector>
 
+#include "attn_mfma.hpp"
 #include "attn_vec.hpp"
 
 namespace hetis {
@@ -81,34 +82,33 @@ static int device_cu_count()
     return cus[dev];
 }
 
-template <int D, int R>
-static int launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
+// Resident workgroups per compute unit of a persistent-kernel instantiation (cached per
+// instantiation and LDS size).
+template <class Kernel>
+static int resident_per_cu(Kernel kernel, int threads, size_t lds)
 {
-    constexpr int NW = kVecWaves;
-    const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
-    if (batch > kMaxPersistBatch || p.n_sel > kMaxPersistHeads || max_items >= (int64_t)1 << 31) {
-        dim3 grid(p.max_chunks, p.n_sel, batch);
-        attn_chunk_vec_kernel<D, R, NW><<<grid, NW * 64, 0, st>>>(p);
-        return HETIS_OK;
-    }
-    auto kernel = attn_chunk_vec_persistent_kernel<D, R, NW>;
-    const size_t lds = persist_table_bytes<D, R, NW>(batch, p.n_sel) + 2 * sizeof(WaveMergeLds<D, R, NW>);
-    // resident workgroups per compute unit for this instantiation and LDS size
     static std::mutex mu;
     static size_t cached_lds = (size_t)-1;
     static int cached_occ = 0;
-    int occ = 0;
-    {
-        std::lock_guard<std::mutex> lock(mu);
-        if (cached_lds != lds) {
-            int n = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, (NW + 1) * 64, lds) != hipSuccess || n < 1)
-                return HETIS_ERR_LAUNCH;
-            cached_occ = n;
-            cached_lds = lds;
-        }
-        occ = cached_occ;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached_lds != lds) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds) != hipSuccess || n < 1)
+            return 0;
+        cached_occ = n;
+        cached_lds = lds;
     }
+    return cached_occ;
+}
+
+template <class Policy>
+static int launch_persistent(const AttnParams &p, int batch, hipStream_t st)
+{
+    constexpr int NW = kVecWaves;
+    auto kernel = attn_chunk_persistent_kernel<Policy, NW>;
+    const size_t lds = persist_lds_bytes<Policy, NW>(batch, p.n_sel);
+    int occ = resident_per_cu(kernel, (NW + 1) * 64, lds);
+    if (occ < 1) return HETIS_ERR_LAUNCH;
     const int cus = device_cu_count();
     if (cus <= 0) return HETIS_ERR_LAUNCH;
     // HETIS_ATTN_WGS_PER_CU (optional, read once): cap on resident workgroups per compute unit.
@@ -119,6 +119,7 @@ static int launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
         return v > 0 ? v : 0;
     }();
     if (env_cap > 0 && occ > env_cap) occ = env_cap;
+    const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
     int64_t G = (int64_t)cus * occ;
     if (G > max_items) G = max_items;
     // a multiple of the head count keeps the heads of one chunk on neighbouring workgroups
@@ -127,10 +128,28 @@ static int launch_chunk_vec(const AttnParams &p, int batch, hipStream_t st)
     return HETIS_OK;
 }
 
+// Kernel choice depends on the shape only (never on the head subset): vector arithmetic for
+// query groups of 1 or 2, MFMA for groups of 4 or 8; batches too large for the persistent
+// kernel's LDS tables take the simple one-workgroup-per-chunk-slot kernel.
+template <int D, int R>
+static int launch_chunk(const AttnParams &p, int batch, hipStream_t st)
+{
+    const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
+    if (batch > kMaxPersistBatch || p.n_sel > kMaxPersistHeads || max_items >= (int64_t)1 << 31) {
+        dim3 grid(p.max_chunks, p.n_sel, batch);
+        attn_chunk_vec_kernel<D, R, kVecWaves><<<grid, kVecWaves * 64, 0, st>>>(p);
+        return HETIS_OK;
+    }
+    if constexpr (R >= 4)
+        return launch_persistent<MfmaPolicy<D, R>>(p, batch, st);
+    else
+        return launch_persistent<VecPolicy<D, R>>(p, batch, st);
+}
+
 static int dispatch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
 {
 #define HETIS_CASE(DD, RR) \
-    if (D == DD && r == RR) return launch_chunk_vec<DD, RR>(p, batch, st);
+    if (D == DD && r == RR) return launch_chunk<DD, RR>(p, batch, st);
     HETIS_CASE(128, 1) HETIS_CASE(128, 2) HETIS_CASE(128, 4) HETIS_CASE(128, 8)
     HETIS_CASE(64, 1) HETIS_CASE(64, 2) HETIS_CASE(64, 4) HETIS_CASE(64, 8)
 #undef HETIS_CASE

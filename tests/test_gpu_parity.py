@@ -15,7 +15,12 @@ from gpu_harness import (SENTINEL, TOL, Dev, as_f64, bits, selected_rows, unsele
 
 pytestmark = pytest.mark.gpu
 
-PARTIAL_TOL = 1e-4   # fp32 partials are not rounded to fp16
+# fp32 partials are not rounded to fp16 on output.  Vector path (query groups of 1 or 2): all
+# arithmetic is fp32, errors stay near 1e-5.  MFMA path (groups of 4 or 8): the softmax
+# weights enter the second product as fp16 (relative rounding 2^-11 per weight), which shows up
+# as a few 1e-4 on outputs of magnitude ~1.
+def partial_tol(group_size):
+    return 1e-4 if group_size < 4 else 1e-3
 
 
 def oracle_of(w, head_ids=None, batch_idx=None):
@@ -144,8 +149,8 @@ def test_split_partials_and_merge(chunk, Hq, Hkv, D):
     assert np.array_equal(np.isnan(gl), np.isnan(rl)), "written chunk set differs"
     assert np.array_equal(np.isnan(go), np.isnan(ro))
     m = ~np.isnan(rl)
-    assert np.abs(gl[m] - rl[m]).max() <= PARTIAL_TOL
-    assert np.abs(go[~np.isnan(ro)] - ro[~np.isnan(ro)]).max() <= PARTIAL_TOL
+    assert np.abs(gl[m] - rl[m]).max() <= 1e-4
+    assert np.abs(go[~np.isnan(ro)] - ro[~np.isnan(ro)]).max() <= partial_tol(Hq // Hkv)
     out = d.merge(o_p, lse_p, hid, chunk, msl)
     ref = oracle_of(w, hid)
     check_against_oracle(out, ref, w.spec, hid)
