@@ -60,11 +60,18 @@ __device__ __forceinline__ float group_sum(float x)
 // in-order load counter.  This lets the tile ring issue every refill unconditionally, which
 // keeps the compiler's wait counts exact (a load that is issued only on some paths forces
 // full drains).
+// The tile address and the validity flag are the same in every lane; they are passed through
+// readfirstlane so that the descriptor provably sits in scalar registers (a descriptor the
+// compiler believes to be lane-dependent is handled with a loop around every load).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const __half *tile, int tile_bytes,
                                                             bool valid)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(tile), 0,
-                                             valid ? tile_bytes : 0, 0x00020000);
+    const uint64_t a = reinterpret_cast<uint64_t>(tile);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    const int nbytes = __builtin_amdgcn_readfirstlane(valid ? tile_bytes : 0);
+    return __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void *>(((uint64_t)hi << 32) | lo), 0, nbytes, 0x00020000);
 }
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));

@@ -5,8 +5,12 @@
 // lane for lane, the B operand of the second:
 //
 //   S^T = K . Q^T      v_mfma_f32_16x16x32_f16, D/32 steps
-//         A = K tile : lane l holds K[token l%16][dims (l/16)*8 + 32*step .. +8]  (a 16-byte
-//                      load straight from the cache tile, no staging)
+//         A = K tile : lane l holds K[token l%16][dims (l/16)*8 + 32*step .. +8].  Loading
+//                      this straight from the cache would make every 16-lane quarter of a
+//                      load touch 16 different rows (64 cache lines per instruction instead
+//                      of 8), so the tile is fetched with the same coalesced 128-bit loads as
+//                      V, staged in a wave-private LDS area and read back in operand layout
+//                      with ds_read_b128.
 //         B = Q^T    : lane l holds Q[head l%16][same dims]; heads >= r are zero columns
 //         C          : lane l, reg i = score of token (l/16)*4 + i for head l%16
 //   O^T += V^T . P     v_mfma_f32_16x16x16_f16, D/16 row blocks
@@ -45,13 +49,17 @@ struct MfmaPolicy {
     static constexpr int KS = D / 32;                 // contraction steps of S^T = K.Q^T
     static constexpr int MB = D / 16;                 // 16-dim row blocks of O^T
     static constexpr int NV = kBlockTokens * D * 2 / 1024;   // 1 KB slices of a V tile
-    // LDS staging of one V tile per wave; rows padded by 32 bytes so that the 16 rows a
-    // transposing read touches fall into different banks.
-    static constexpr int kRowBytes = 2 * D + 32;
-    static constexpr int kWaveLdsBytes = kBlockTokens * kRowBytes;
+    // Wave-private LDS staging of one K tile and one V tile, token-major rows.  Row pitches
+    // are padded so that the rows touched together fall into different banks: K is read 16
+    // rows x 16 bytes at a time (pitch + 16), V 4 rows x 32 bytes per 16 lanes (pitch + 32).
+    static constexpr int kPitchK = 2 * D + 16;
+    static constexpr int kPitchV = 2 * D + 32;
+    static constexpr int kStageK = kBlockTokens * kPitchK;
+    static constexpr int kWaveLdsBytes = kStageK + kBlockTokens * kPitchV;
+    static constexpr int kWavesPerEu = 2;             // register budget: 512 / 2 per lane
 
     struct Tile {
-        uint4 k[KS];
+        uint4 k[NV];
         uint4 v[NV];
     };
     struct Query {
@@ -63,13 +71,13 @@ struct MfmaPolicy {
         f32x4 acc[MB];
     };
 
+    // K and V: lane l takes bytes [16 l, 16 l + 16) of every 1 KB slice of the tile
     __device__ static __forceinline__ void issue(Tile &t, __amdgpu_buffer_rsrc_t rk,
                                                  __amdgpu_buffer_rsrc_t rv, int lane)
     {
-        const int koff = (lane & 15) * (2 * D) + (lane >> 4) * 16;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) t.k[s] = buffer_load_u4(rk, koff + s * 64);
         const int voff = lane * 16;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) t.k[i] = buffer_load_u4(rk, voff + i * 1024);
 #pragma unroll
         for (int i = 0; i < NV; ++i) t.v[i] = buffer_load_u4(rv, voff + i * 1024);
     }
@@ -98,36 +106,42 @@ struct MfmaPolicy {
         for (int mb = 0; mb < MB; ++mb) st.acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    template <bool MASKED>
+    // One code path for full and ragged tiles (n_valid = 16 makes every select a no-op):
+    // two copies of this body would leave the accumulators in different registers on the two
+    // sides of a branch and cost 32 register moves per tile to reconcile.
     __device__ static __forceinline__ void update(State &st, const Tile &t, const Query &q,
                                                   float scale_log2, int lane, int n_valid,
                                                   unsigned char *stage)
     {
         const int grp = lane >> 4;
-        // ---- V tile -> wave-private LDS, token-major rows of kRowBytes
+        unsigned char *kstage = stage;
+        unsigned char *vstage = stage + kStageK;
+        // ---- K and V tiles -> wave-private LDS, token-major rows
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int pos = i * 1024 + lane * 16;
             const int row = pos / (2 * D), colb = pos % (2 * D);
+            *reinterpret_cast<uint4 *>(kstage + row * kPitchK + colb) = t.k[i];
             uint4 v = t.v[i];
-            if (MASKED && row >= n_valid) v = make_uint4(0u, 0u, 0u, 0u);   // may hold NaN
-            *reinterpret_cast<uint4 *>(stage + row * kRowBytes + colb) = v;
+            if (row >= n_valid) v = make_uint4(0u, 0u, 0u, 0u);   // slots past the end may hold NaN
+            *reinterpret_cast<uint4 *>(vstage + row * kPitchV + colb) = v;
         }
         // ---- scores of 16 tokens x 16 (padded) heads
+        const unsigned char *ksrc = kstage + (lane & 15) * kPitchK + grp * 16;
+        union {
+            uint4 u;
+            f16x8 h;
+        } a[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s].u = *reinterpret_cast<const uint4 *>(ksrc + s * 64);
         f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            union {
-                uint4 u;
-                f16x8 h;
-            } a;
-            a.u = t.k[s];
-            c = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, q.b[s], c, 0, 0, 0);
-        }
+        for (int s = 0; s < KS; ++s)
+            c = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s].h, q.b[s], c, 0, 0, 0);
         float s4[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const bool valid = !MASKED || (grp * 4 + i < n_valid);
+            const bool valid = grp * 4 + i < n_valid;
             s4[i] = valid ? c[i] * scale_log2 : -INFINITY;
         }
         float mt = fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
@@ -144,25 +158,24 @@ struct MfmaPolicy {
             ps += p4[i];
         }
         st.l = st.l * alpha + ps;
-        // the maximum settles after a few tiles: skip the rescale when no lane needs it
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) st.acc[mb] *= alpha;
-        }
+        for (int mb = 0; mb < MB; ++mb) st.acc[mb] *= alpha;
         const f16x4 pb = {(_Float16)p4[0], (_Float16)p4[1], (_Float16)p4[2], (_Float16)p4[3]};
-        // ---- O^T += V^T . P, V^T through the transposing LDS read
+        // ---- O^T += V^T . P, V^T through the transposing LDS read (all reads first, so
+        // that their latencies overlap)
         const int srow = grp * 4 + ((lane & 15) >> 2);
-        const unsigned char *vsrc = stage + srow * kRowBytes + (lane & 3) * 8;
+        const unsigned char *vsrc = vstage + srow * kPitchV + (lane & 3) * 8;
+        union {
+            i16x4 i;
+            f16x4 h;
+        } vt[MB];
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            union {
-                i16x4 i;
-                f16x4 h;
-            } vt;
-            vt.i = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        for (int mb = 0; mb < MB; ++mb)
+            vt[mb].i = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (__attribute__((address_space(3))) i16x4 *)(vsrc + mb * 32));
-            st.acc[mb] = __builtin_amdgcn_mfma_f32_16x16x16f16(vt.h, pb, st.acc[mb], 0, 0, 0);
-        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            st.acc[mb] = __builtin_amdgcn_mfma_f32_16x16x16f16(vt[mb].h, pb, st.acc[mb], 0, 0, 0);
     }
 
     template <int NW>

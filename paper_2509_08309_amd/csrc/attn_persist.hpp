@@ -16,10 +16,18 @@
 //     known exactly at every wait.  These waves never store to global memory: on
 //     gfx9-class hardware loads and stores share one counter that is in order only among
 //     loads, so a single pending store would force every later wait to drain all loads.
-//   - Writer wave: after the barrier that ends an item it combines the NW wave results
-//     from LDS (ascending wave order) and stores the fp16 row or the fp32 partial.
+//     After the barrier that ends an item the streaming waves also combine the NW wave
+//     results (ascending wave order), a quarter of the rows each, into an LDS result area.
+//     They also keep the query rows flowing: each wave loads its share of the rows of item
+//     n + 2 while item n streams and puts them into LDS one item later, from where all
+//     waves take their query operand.
+//   - Writer wave: one item behind, it copies the finished result area to global memory
+//     (fp16 row or fp32 partial).  It never loads from global memory, so it never has to
+//     wait for its stores.
+// Every item ends with exactly one workgroup barrier; one more follows the last item.
 // Dynamic LDS: int lens[batch], int first[batch + 1], int hids[n_sel]; two WaveMergeLds
-// areas used alternately; NW per-wave staging areas of Policy::kWaveLdsBytes.
+// areas, two result areas and two query areas used alternately; NW per-wave staging areas
+// of Policy::kWaveLdsBytes.
 // Nothing depends on how many heads were selected or on the grid size: the result for one
 // (sequence, head) is a function of that sequence's length alone.
 #pragma once
@@ -35,12 +43,20 @@ struct WaveMergeLds {
     float l[NW][R];
 };
 
-// After a barrier: final result of the chunk, to `out` (fp16) or to the partial buffers.
+// Finished rows of one item, before they leave for global memory.
+template <int D, int R>
+struct ResultLds {
+    float o[R][D];      // normalised output rows
+    float lse[R];       // natural-log log-sum-exp of each row (used by partial results only)
+};
+
+// After the barrier that ends an item: combine the NW wave results into the result area.
+// Called by the NTHREADS streaming threads; thread `tid` takes elements tid, tid + NTHREADS, ...
 template <int D, int R, int NW, int NTHREADS>
-__device__ __forceinline__ void lds_finish(const WaveMergeLds<D, R, NW> &sm, const AttnParams &p,
-                                           int tid, int b, int g, int si, int c, bool to_out)
+__device__ __forceinline__ void lds_combine(const WaveMergeLds<D, R, NW> &sm, ResultLds<D, R> &res,
+                                            int tid)
 {
-    const int rows = p.n_sel * R;
+#pragma unroll
     for (int idx = tid; idx < R * D; idx += NTHREADS) {
         const int r = idx / D, d = idx % D;
         float M = sm.m[0][r];
@@ -53,13 +69,33 @@ __device__ __forceinline__ void lds_finish(const WaveMergeLds<D, R, NW> &sm, con
             acc += sm.o[w][r][d] * a;
             lsum += sm.l[w][r] * a;
         }
-        const float res = acc / lsum;
+        res.o[r][d] = acc * __builtin_amdgcn_rcpf(lsum);
+        if (d == 0) res.lse[r] = (M + fast_log2(lsum)) * kLn2;
+    }
+}
+
+// Result area -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
+template <int D, int R>
+__device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const AttnParams &p,
+                                             int lane, int b, int g, int si, int c, bool to_out)
+{
+    const int rows = p.n_sel * R;
+#pragma unroll
+    for (int idx = lane * 4; idx < R * D; idx += 256) {
+        const int r = idx / D, d = idx % D;
+        const float4 v = *reinterpret_cast<const float4 *>(&res.o[r][d]);
         if (to_out) {
-            p.out[((int64_t)b * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(res);
+            union {
+                __half2 h[2];
+                uint2 u;
+            } pk;
+            pk.h[0] = __floats2half2_rn(v.x, v.y);
+            pk.h[1] = __floats2half2_rn(v.z, v.w);
+            *reinterpret_cast<uint2 *>(p.out + ((int64_t)b * p.n_q_heads + g * R + r) * D + d) = pk.u;
         } else {
             const int64_t row = ((int64_t)b * rows + si * R + r) * p.max_chunks + c;
-            p.o_partial[row * D + d] = res;
-            if (d == 0) p.lse_partial[row] = (M + fast_log2(lsum)) * kLn2;
+            *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
+            if (d == 0) p.lse_partial[row] = res.lse[r];
         }
     }
 }
@@ -89,6 +125,8 @@ __host__ __device__ constexpr size_t persist_lds_bytes(int batch, int n_sel)
 {
     return align16((size_t)(2 * batch + 1 + n_sel) * sizeof(int)) +
            2 * sizeof(WaveMergeLds<Policy::D, Policy::R, NW>) +
+           2 * sizeof(ResultLds<Policy::D, Policy::R>) +
+           2 * (size_t)Policy::R * Policy::D * sizeof(__half) +
            (size_t)NW * Policy::kWaveLdsBytes;
 }
 
@@ -100,7 +138,7 @@ __device__ __forceinline__ void workgroup_barrier()
 }
 
 template <class Policy, int NW>
-__global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(const AttnParams p,
+__global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(Policy::kWavesPerEu))) void attn_chunk_persistent_kernel(const AttnParams p,
                                                                               const int batch)
 {
     constexpr int D = Policy::D;
@@ -115,7 +153,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(co
     int *hids = first + batch + 1;
     unsigned char *after_tables = smem + align16((size_t)(2 * batch + 1 + p.n_sel) * sizeof(int));
     Lds *sm = reinterpret_cast<Lds *>(after_tables);
-    unsigned char *staging = after_tables + 2 * sizeof(Lds);
+    using Res = ResultLds<D, R>;
+    Res *res = reinterpret_cast<Res *>(after_tables + 2 * sizeof(Lds));
+    constexpr int kQBytes = R * D * (int)sizeof(__half);      // query rows of one item
+    unsigned char *q_stage = after_tables + 2 * sizeof(Lds) + 2 * sizeof(Res);
+    unsigned char *staging = q_stage + 2 * kQBytes;
     __shared__ int scan[NT];
 
     const int tid = threadIdx.x;
@@ -157,13 +199,13 @@ __global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(co
     const int total = first[batch] * p.n_sel;
     const int G = gridDim.x;
 
-    int b_scan = 0;   // sequences are visited in ascending order: resume the search where it ended
-    auto decode = [&](int w, ItemHdr &h) {
+    // sequences are visited in ascending order: `cursor` resumes the search where it ended
+    auto decode = [&](int w, ItemHdr &h, int &cursor) {
         const int cg = w / p.n_sel;
         h.si = w - cg * p.n_sel;
-        while (first[b_scan + 1] <= cg) ++b_scan;
-        b_scan = __builtin_amdgcn_readfirstlane(b_scan);
-        h.b = b_scan;
+        while (first[cursor + 1] <= cg) ++cursor;
+        cursor = __builtin_amdgcn_readfirstlane(cursor);
+        h.b = cursor;
         h.c = __builtin_amdgcn_readfirstlane(cg - first[h.b]);
         const int L = __builtin_amdgcn_readfirstlane(lens[h.b]);
         h.g = __builtin_amdgcn_readfirstlane(hids[h.si]);
@@ -179,20 +221,53 @@ __global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(co
     int w = blockIdx.x;
     if (w >= total) return;
 
+    // ---- query rows: global -> registers -> LDS, a share per streaming wave
+    static_assert(kQBytes % (NW * 16) == 0, "query rows split evenly over the streaming waves");
+    constexpr int kQShare = kQBytes / NW;                     // bytes per wave
+    constexpr int kQVec = (kQShare / 16 + 63) / 64;           // uint4 per lane
+    int cursor_q = 0;
+    auto q_fetch = [&](int wi, uint4 (&qv)[kQVec]) {          // unconditional, indices clamped
+        ItemHdr h;
+        decode(min(wi, total - 1), h, cursor_q);
+        const uint4 *src = reinterpret_cast<const uint4 *>(
+            p.q + ((int64_t)h.b * p.n_q_heads + h.g * R) * D) + wave * (kQShare / 16);
+#pragma unroll
+        for (int i = 0; i < kQVec; ++i) qv[i] = src[min(lane + 64 * i, kQShare / 16 - 1)];
+    };
+    auto q_store = [&](const uint4 (&qv)[kQVec], int par) {
+        uint4 *dst = reinterpret_cast<uint4 *>(q_stage + par * kQBytes) + wave * (kQShare / 16);
+#pragma unroll
+        for (int i = 0; i < kQVec; ++i)
+            if (lane + 64 * i < kQShare / 16) dst[lane + 64 * i] = qv[i];
+    };
+    uint4 qv[kQVec];
+    if (wave < NW) {
+        q_fetch(w, qv);
+        q_store(qv, 0);
+        q_fetch(w + G, qv);           // stays in registers until the first item's barrier
+    }
+    __syncthreads();
+
     if (wave == NW) {
         // ------------------------------------------------------------ writer wave
-        int parity = 0;
-        for (; w < total; w += G) {
+        int n = 0, cursor = 0;
+        ItemHdr prev;
+        bool have_prev = false;
+        for (; w < total; w += G, ++n) {
             ItemHdr h;
-            decode(w, h);
-            if (h.zero) {
-                write_zero_rows<D, R, 64>(p, lane, h.b, h.g);
-                continue;
-            }
-            workgroup_barrier();
-            lds_finish<D, R, NW, 64>(sm[parity], p, lane, h.b, h.g, h.si, h.c, h.to_out);
-            parity ^= 1;
+            decode(w, h, cursor);
+            workgroup_barrier();                  // ends item n; item n - 1 is now combined
+            if (have_prev)
+                flush_result<D, R>(res[(n - 1) & 1], p, lane, prev.b, prev.g, prev.si, prev.c,
+                                   prev.to_out);
+            have_prev = !h.zero;
+            prev = h;
+            if (h.zero) write_zero_rows<D, R, 64>(p, lane, h.b, h.g);
         }
+        workgroup_barrier();                      // the last item is combined
+        if (have_prev)
+            flush_result<D, R>(res[(n - 1) & 1], p, lane, prev.b, prev.g, prev.si, prev.c,
+                               prev.to_out);
         return;
     }
 
@@ -204,17 +279,15 @@ __global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(co
         int64_t head_off;
         bool exists;
     };
+    int cursor = 0;
     auto fill = [&](int wi, Slot &s) {
         s.exists = wi < total;
-        decode(min(wi, total - 1), s.h);
+        decode(min(wi, total - 1), s.h, cursor);
         s.n_my = (s.exists && s.h.nblk > wave) ? (s.h.nblk - wave + NW - 1) / NW : 0;
         s.head_off = (int64_t)s.h.g * p.stride_head;
         const int32_t *bt =
             p.block_table + (int64_t)s.h.b * p.max_blocks_per_seq + s.h.t0 / kBlockTokens;
         s.ids = bt[min(wave + NW * lane, max(s.h.nblk - 1, 0))];
-    };
-    auto load_q = [&](const Slot &s, typename Policy::Query &q) {
-        Policy::load_q(q, p.q + ((int64_t)s.h.b * p.n_q_heads + s.h.g * R) * D, lane);
     };
     auto issue = [&](Tile &t, int ids, int idx, int64_t head_off, bool valid) {
         const int blk = __builtin_amdgcn_readlane(ids, idx & 63);
@@ -224,18 +297,19 @@ __global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(co
     };
 
     Slot cur, nxt, nn;
-    typename Policy::Query q, q_nxt;
+    typename Policy::Query q;
     Tile A, B;
     unsigned char *my_staging = staging + (size_t)wave * Policy::kWaveLdsBytes;
     fill(w, cur);
     fill(w + G, nxt);
-    load_q(cur, q);
     issue(A, cur.ids, 0, cur.head_off, 0 < cur.n_my);
     issue(B, cur.ids, 1, cur.head_off, 1 < cur.n_my);
-    int parity = 0;
-    for (;;) {
+    int n = 0;
+    for (;; ++n) {
         fill(w + 2 * G, nn);        // header and block ids two items ahead
-        load_q(nxt, q_nxt);         // query rows one item ahead
+        Policy::load_q(q, reinterpret_cast<const __half *>(q_stage + (n & 1) * kQBytes), lane);
+        q_store(qv, (n + 1) & 1);   // rows of item n + 1, loaded one item ago
+        q_fetch(w + 2 * G, qv);     // rows of item n + 2
 
         typename Policy::State st;
         Policy::reset(st);
@@ -250,10 +324,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(co
         // the ragged block, if any, is the chunk's last block: the last tile of one wave
         const bool mine_ragged = cur.h.rem != 0 && ((cur.h.nblk - 1) % NW) == wave;
         auto consume = [&](const Tile &t, int i) {
-            if (mine_ragged && i == n_my - 1)
-                Policy::template update<true>(st, t, q, p.scale_log2, lane, cur.h.rem, my_staging);
-            else
-                Policy::template update<false>(st, t, q, p.scale_log2, lane, kBlockTokens, my_staging);
+            const int n_valid = (mine_ragged && i == n_my - 1) ? cur.h.rem : kBlockTokens;
+            Policy::update(st, t, q, p.scale_log2, lane, n_valid, my_staging);
         };
         // The scheduling fences keep "consume a slot, refill it at once" in program order;
         // without them the compiler batches both tiles' arithmetic ahead of both refills
@@ -268,17 +340,15 @@ __global__ __launch_bounds__((NW + 1) * 64) void attn_chunk_persistent_kernel(co
             refill(B, i + 3);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (cur.exists && !cur.h.zero) {
-            Policy::template put<NW>(st, sm[parity], wave, lane);
-            workgroup_barrier();
-            parity ^= 1;
-        }
+        if (!cur.h.zero) Policy::template put<NW>(st, sm[n & 1], wave, lane);
+        workgroup_barrier();                      // ends item n
+        if (!cur.h.zero) lds_combine<D, R, NW, NW * 64>(sm[n & 1], res[n & 1], tid);
         if (!nxt.exists) break;
         cur = nxt;
         nxt = nn;
-        q = q_nxt;
         w += G;
     }
+    workgroup_barrier();                          // lets the writer see the last combined item
 }
 
 }  // namespace hetis

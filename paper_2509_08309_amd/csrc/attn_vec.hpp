@@ -227,7 +227,10 @@ __global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParam
     __shared__ WaveMergeLds<D, R, NW> sm;
     vec_lds_put<D, R, NW>(sm, st, wave, gid, sub);
     __syncthreads();
-    lds_finish<D, R, NW, NW * 64>(sm, p, tid, b, g, si, c, to_out);
+    __shared__ ResultLds<D, R> res;
+    lds_combine<D, R, NW, NW * 64>(sm, res, tid);
+    __syncthreads();
+    if (wave == 0) flush_result<D, R>(res, p, lane, b, g, si, c, to_out);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -238,6 +241,7 @@ struct VecPolicy {
     static constexpr int D = D_;
     static constexpr int R = R_;
     static constexpr int kWaveLdsBytes = 0;      // no per-wave staging area
+    static constexpr int kWavesPerEu = R == 1 ? 4 : 3;   // register budget: 512 / this per lane
     using Tile = TileRegs<D>;
     using State = VecState<D, R>;
     struct Query {
@@ -266,12 +270,13 @@ struct VecPolicy {
         }
     }
     __device__ static __forceinline__ void reset(State &st) { st.reset(); }
-    template <bool MASKED>
+    // n_valid < 16 only for the ragged last block of a sequence: a separate masked copy of
+    // the arithmetic keeps the common case free of compares and selects
     __device__ static __forceinline__ void update(State &st, const Tile &t, const Query &q,
                                                   float scale_log2, int lane, int n_valid,
                                                   unsigned char *)
     {
-        vec_tile_update<D, R, MASKED>(st, t, q.h, scale_log2, lane / (D / 8), n_valid);
+        vec_tile_update_any<D, R>(st, t, q.h, scale_log2, lane / (D / 8), n_valid);
     }
     template <int NW>
     __device__ static __forceinline__ void put(State &st, WaveMergeLds<D, R, NW> &sm, int wave,
