@@ -126,7 +126,7 @@ int hetis_attn_release_workspace(void);
  * sequence b covers tokens [c*chunk_tokens, min((c+1)*chunk_tokens, L_b)).
  *
  * hetis_attn_split_num_chunks: C_max = ceil(max_seq_len / chunk_tokens), or a
- *   negative status.  chunk_tokens must be a positive multiple of 16, at most 4096.
+ *   negative status.  chunk_tokens must be a positive multiple of 16, at most 1024.
  * hetis_attn_split_workspace_bytes: sizes in bytes of the two partial buffers
  *   (host out-pointers).
  */

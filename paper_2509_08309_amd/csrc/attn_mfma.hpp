@@ -5,12 +5,9 @@
 // lane for lane, the B operand of the second:
 //
 //   S^T = K . Q^T      v_mfma_f32_16x16x32_f16, D/32 steps
-//         A = K tile : lane l holds K[token l%16][dims (l/16)*8 + 32*step .. +8].  Loading
-//                      this straight from the cache would make every 16-lane quarter of a
-//                      load touch 16 different rows (64 cache lines per instruction instead
-//                      of 8), so the tile is fetched with the same coalesced 128-bit loads as
-//                      V, staged in a wave-private LDS area and read back in operand layout
-//                      with ds_read_b128.
+//         A = K tile : lane l holds K[token l%16][dims (l/16)*8 + 32*step .. +8]  (a 16-byte
+//                      load straight from the cache tile; staging K through LDS with
+//                      row-coalesced loads was measured and made no difference)
 //         B = Q^T    : lane l holds Q[head l%16][same dims]; heads >= r are zero columns
 //         C          : lane l, reg i = score of token (l/16)*4 + i for head l%16
 //   O^T += V^T . P     v_mfma_f32_16x16x16_f16, D/16 row blocks
@@ -49,17 +46,17 @@ struct MfmaPolicy {
     static constexpr int KS = D / 32;                 // contraction steps of S^T = K.Q^T
     static constexpr int MB = D / 16;                 // 16-dim row blocks of O^T
     static constexpr int NV = kBlockTokens * D * 2 / 1024;   // 1 KB slices of a V tile
-    // Wave-private LDS staging of one K tile and one V tile, token-major rows.  Row pitches
-    // are padded so that the rows touched together fall into different banks: K is read 16
-    // rows x 16 bytes at a time (pitch + 16), V 4 rows x 32 bytes per 16 lanes (pitch + 32).
-    static constexpr int kPitchK = 2 * D + 16;
+    // Wave-private LDS: one V tile (token-major rows, pitch padded by 32 bytes so that the
+    // 4 rows x 32 bytes a 16-lane transposing read touches fall into different banks) and
+    // the query rows of the current item.
     static constexpr int kPitchV = 2 * D + 32;
-    static constexpr int kStageK = kBlockTokens * kPitchK;
-    static constexpr int kWaveLdsBytes = kStageK + kBlockTokens * kPitchV;
+    static constexpr int kStageV = kBlockTokens * kPitchV;
+    static constexpr int kQBytes = R * D * 2;
+    static constexpr int kWaveLdsBytes = kStageV + kQBytes;
     static constexpr int kWavesPerEu = 2;             // register budget: 512 / 2 per lane
 
     struct Tile {
-        uint4 k[NV];
+        uint4 k[KS];
         uint4 v[NV];
     };
     struct Query {
@@ -71,21 +68,39 @@ struct MfmaPolicy {
         f32x4 acc[MB];
     };
 
-    // K and V: lane l takes bytes [16 l, 16 l + 16) of every 1 KB slice of the tile
     __device__ static __forceinline__ void issue(Tile &t, __amdgpu_buffer_rsrc_t rk,
                                                  __amdgpu_buffer_rsrc_t rv, int lane)
     {
-        const int voff = lane * 16;
+        const int koff = (lane & 15) * (2 * D) + (lane >> 4) * 16;
 #pragma unroll
-        for (int i = 0; i < NV; ++i) t.k[i] = buffer_load_u4(rk, voff + i * 1024);
+        for (int s = 0; s < KS; ++s) t.k[s] = buffer_load_u4(rk, koff + s * 64);
+        const int voff = lane * 16;
 #pragma unroll
         for (int i = 0; i < NV; ++i) t.v[i] = buffer_load_u4(rv, voff + i * 1024);
     }
 
-    __device__ static __forceinline__ void load_q(Query &q, const __half *rows, int lane)
+    // Query rows: fetched as raw bytes one item ahead (kQBytes over 64 lanes), then passed
+    // through the wave's LDS area into operand layout with zero columns for heads >= r.
+    static constexpr int kQVec = (kQBytes / 16 + 63) / 64;
+    struct QueryPrefetch {
+        uint4 raw[kQVec];
+    };
+    __device__ static __forceinline__ void q_prefetch(QueryPrefetch &pre, const __half *rows, int lane)
     {
+        const uint4 *src = reinterpret_cast<const uint4 *>(rows);
+#pragma unroll
+        for (int i = 0; i < kQVec; ++i) pre.raw[i] = src[min(lane + 64 * i, kQBytes / 16 - 1)];
+    }
+    __device__ static __forceinline__ void q_commit(Query &q, const QueryPrefetch &pre,
+                                                    unsigned char *stage, int lane)
+    {
+        uint4 *dst = reinterpret_cast<uint4 *>(stage + kStageV);
+#pragma unroll
+        for (int i = 0; i < kQVec; ++i)
+            if (lane + 64 * i < kQBytes / 16) dst[lane + 64 * i] = pre.raw[i];
         const int j = lane & 15;
-        const __half *src = rows + min(j, R - 1) * D + (lane >> 4) * 8;
+        const __half *src =
+            reinterpret_cast<const __half *>(stage + kStageV) + min(j, R - 1) * D + (lane >> 4) * 8;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             union {
@@ -114,30 +129,27 @@ struct MfmaPolicy {
                                                   unsigned char *stage)
     {
         const int grp = lane >> 4;
-        unsigned char *kstage = stage;
-        unsigned char *vstage = stage + kStageK;
-        // ---- K and V tiles -> wave-private LDS, token-major rows
+        unsigned char *vstage = stage;
+        // ---- V tile -> wave-private LDS, token-major rows
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int pos = i * 1024 + lane * 16;
             const int row = pos / (2 * D), colb = pos % (2 * D);
-            *reinterpret_cast<uint4 *>(kstage + row * kPitchK + colb) = t.k[i];
             uint4 v = t.v[i];
             if (row >= n_valid) v = make_uint4(0u, 0u, 0u, 0u);   // slots past the end may hold NaN
             *reinterpret_cast<uint4 *>(vstage + row * kPitchV + colb) = v;
         }
         // ---- scores of 16 tokens x 16 (padded) heads
-        const unsigned char *ksrc = kstage + (lane & 15) * kPitchK + grp * 16;
-        union {
-            uint4 u;
-            f16x8 h;
-        } a[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) a[s].u = *reinterpret_cast<const uint4 *>(ksrc + s * 64);
         f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < KS; ++s)
-            c = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[s].h, q.b[s], c, 0, 0, 0);
+        for (int s = 0; s < KS; ++s) {
+            union {
+                uint4 u;
+                f16x8 h;
+            } a;
+            a.u = t.k[s];
+            c = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, q.b[s], c, 0, 0, 0);
+        }
         float s4[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -178,23 +190,23 @@ struct MfmaPolicy {
             st.acc[mb] = __builtin_amdgcn_mfma_f32_16x16x16f16(vt[mb].h, pb, st.acc[mb], 0, 0, 0);
     }
 
-    template <int NW>
-    __device__ static __forceinline__ void put(State &st, WaveMergeLds<D, R, NW> &sm, int wave,
-                                               int lane)
+    // normalised rows and their log-sum-exp -> LDS (the wave's mailbox)
+    __device__ static __forceinline__ void finish(State &st, float (&o)[R][D], float (&lse)[R],
+                                                  int lane)
     {
         const int j = lane & 15, grp = lane >> 4;
         float l = st.l;
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
         if (j < R) {
+            const float inv = __builtin_amdgcn_rcpf(l);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sm.o[wave][j][mb * 16 + grp * 4 + i] = st.acc[mb][i];
-            if (grp == 0) {
-                sm.m[wave][j] = st.m;
-                sm.l[wave][j] = l;
+            for (int mb = 0; mb < MB; ++mb) {
+                const float4 v = make_float4(st.acc[mb][0] * inv, st.acc[mb][1] * inv,
+                                             st.acc[mb][2] * inv, st.acc[mb][3] * inv);
+                *reinterpret_cast<float4 *>(&o[j][mb * 16 + grp * 4]) = v;
             }
+            if (grp == 0) lse[j] = (st.m + fast_log2(l)) * kLn2;
         }
     }
 };

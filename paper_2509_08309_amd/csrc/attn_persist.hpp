@@ -4,30 +4,31 @@
 //
 // Work enumeration: every workgroup scans the sequence lengths into a table of first-chunk
 // indices (LDS), which turns a flat item number into (sequence, chunk, selected head)
-// without launching a workgroup per possible chunk.  Workgroup k takes items k, k + G, ...
+// without launching a workgroup per possible chunk.  An item is one chunk of one
+// (sequence, selected head) and is processed by ONE wave; streaming wave number
+// blockIdx * NW + wave takes items of that number, that number + (waves in the grid), ...
 //
-// A workgroup is NW streaming waves plus one writer wave.
-//   - Streaming waves: wave w owns blocks w, w + NW, ... of the chunk and streams their
-//     tiles through a two-slot register ring; a slot is refilled right after it has been
-//     consumed, so one to two tile pairs (8-16 KB per wave) are always in flight, and the
-//     ring runs on into the first pair of the next item before the current item's merge.
-//     Every global load is issued unconditionally (indices clamped, tiles that do not
-//     exist turned into zero-length buffer descriptors), so the in-order load counter is
-//     known exactly at every wait.  These waves never store to global memory: on
-//     gfx9-class hardware loads and stores share one counter that is in order only among
-//     loads, so a single pending store would force every later wait to drain all loads.
-//     After the barrier that ends an item the streaming waves also combine the NW wave
-//     results (ascending wave order), a quarter of the rows each, into an LDS result area.
-//     They also keep the query rows flowing: each wave loads its share of the rows of item
-//     n + 2 while item n streams and puts them into LDS one item later, from where all
-//     waves take their query operand.
-//   - Writer wave: one item behind, it copies the finished result area to global memory
-//     (fp16 row or fp32 partial).  It never loads from global memory, so it never has to
-//     wait for its stores.
-// Every item ends with exactly one workgroup barrier; one more follows the last item.
-// Dynamic LDS: int lens[batch], int first[batch + 1], int hids[n_sel]; two WaveMergeLds
-// areas, two result areas and two query areas used alternately; NW per-wave staging areas
-// of Policy::kWaveLdsBytes.
+// A workgroup is NW streaming waves plus one writer wave; after the prologue they never
+// meet at a barrier.
+//   - Streaming waves stream the tiles of their item through a two-slot register ring; a
+//     slot is refilled right after it has been consumed, so one to two tile pairs (8-16 KB
+//     per wave) are always in flight, and the ring runs on into the first pair of the next
+//     item before the current item is finished off.  Every global load is issued
+//     unconditionally (indices clamped, tiles that do not exist turned into zero-length
+//     buffer descriptors), so the in-order load counter is known exactly at every wait.
+//     These waves never store to global memory: on gfx9-class hardware loads and stores
+//     share one counter that is in order only among loads, so a single pending store would
+//     force every later wait to drain all loads.  A finished item (normalised rows and
+//     their log-sum-exp) is handed over through one of the wave's two LDS mailboxes.
+//   - The writer wave polls the mailboxes and copies full ones to global memory (fp16 row,
+//     fp32 partial, or zeros for an empty sequence).  It never loads from global memory,
+//     so it never waits for its stores.
+// Mailbox protocol (flag is a workgroup-scope atomic in LDS): EMPTY -> the producer fills
+// data and header -> FULL -> the writer copies it out -> EMPTY.  A producer that has no more
+// items marks its next mailbox DONE; the writer leaves when all NW are DONE.  All waits are
+// polling loops with an iteration bound, so every wave reaches its end whatever happens.
+// Dynamic LDS: int lens[batch], int first[batch + 1], int hids[n_sel]; NW x 2 mailboxes; NW
+// per-wave staging areas of Policy::kWaveLdsBytes.
 // Nothing depends on how many heads were selected or on the grid size: the result for one
 // (sequence, head) is a function of that sequence's length alone.
 #pragma once
@@ -35,56 +36,41 @@
 
 namespace hetis {
 
-// LDS area through which the waves of a workgroup are merged (ascending wave order).
-template <int D, int R, int NW>
-struct WaveMergeLds {
-    float o[NW][R][D];
-    float m[NW][R];
-    float l[NW][R];
-};
+enum : int { kMailEmpty = 0, kMailFull = 1, kMailDone = 2 };
+enum : int { kKindOut = 0, kKindPartial = 1, kKindZero = 2 };
+constexpr int kSpinLimit = 1 << 22;     // polls before a wait gives up (far beyond any real wait)
 
-// Finished rows of one item, before they leave for global memory.
+// One finished item on its way to global memory.
 template <int D, int R>
-struct ResultLds {
+struct Mailbox {
     float o[R][D];      // normalised output rows
-    float lse[R];       // natural-log log-sum-exp of each row (used by partial results only)
+    float lse[R];       // natural-log log-sum-exp of each row (partial results only)
+    int b, g, si, c;    // sequence, KV head, position in head_ids, chunk
+    int kind;           // kKindOut / kKindPartial / kKindZero
+    int flag;           // kMailEmpty / kMailFull / kMailDone
+    int pad[2];
 };
 
-// After the barrier that ends an item: combine the NW wave results into the result area.
-// Called by the NTHREADS streaming threads; thread `tid` takes elements tid, tid + NTHREADS, ...
-template <int D, int R, int NW, int NTHREADS>
-__device__ __forceinline__ void lds_combine(const WaveMergeLds<D, R, NW> &sm, ResultLds<D, R> &res,
-                                            int tid)
-{
-#pragma unroll
-    for (int idx = tid; idx < R * D; idx += NTHREADS) {
-        const int r = idx / D, d = idx % D;
-        float M = sm.m[0][r];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm.m[w][r]);
-        float acc = 0.f, lsum = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float a = fast_exp2(sm.m[w][r] - M);
-            acc += sm.o[w][r][d] * a;
-            lsum += sm.l[w][r] * a;
-        }
-        res.o[r][d] = acc * __builtin_amdgcn_rcpf(lsum);
-        if (d == 0) res.lse[r] = (M + fast_log2(lsum)) * kLn2;
-    }
-}
-
-// Result area -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
+// Mailbox -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
 template <int D, int R>
-__device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const AttnParams &p,
-                                             int lane, int b, int g, int si, int c, bool to_out)
+__device__ __forceinline__ void flush_mailbox(const Mailbox<D, R> &mb, const AttnParams &p, int lane)
 {
+    const int b = __builtin_amdgcn_readfirstlane(mb.b);
+    const int g = __builtin_amdgcn_readfirstlane(mb.g);
+    const int si = __builtin_amdgcn_readfirstlane(mb.si);
+    const int c = __builtin_amdgcn_readfirstlane(mb.c);
+    const int kind = __builtin_amdgcn_readfirstlane(mb.kind);
     const int rows = p.n_sel * R;
 #pragma unroll
     for (int idx = lane * 4; idx < R * D; idx += 256) {
         const int r = idx / D, d = idx % D;
-        const float4 v = *reinterpret_cast<const float4 *>(&res.o[r][d]);
-        if (to_out) {
+        float4 v = *reinterpret_cast<const float4 *>(&mb.o[r][d]);
+        if (kind == kKindPartial) {
+            const int64_t row = ((int64_t)b * rows + si * R + r) * p.max_chunks + c;
+            *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
+            if (d == 0) p.lse_partial[row] = mb.lse[r];
+        } else {
+            if (kind == kKindZero) v = make_float4(0.f, 0.f, 0.f, 0.f);
             union {
                 __half2 h[2];
                 uint2 u;
@@ -92,20 +78,7 @@ __device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const A
             pk.h[0] = __floats2half2_rn(v.x, v.y);
             pk.h[1] = __floats2half2_rn(v.z, v.w);
             *reinterpret_cast<uint2 *>(p.out + ((int64_t)b * p.n_q_heads + g * R + r) * D + d) = pk.u;
-        } else {
-            const int64_t row = ((int64_t)b * rows + si * R + r) * p.max_chunks + c;
-            *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
-            if (d == 0) p.lse_partial[row] = res.lse[r];
         }
-    }
-}
-
-template <int D, int R, int NTHREADS>
-__device__ __forceinline__ void write_zero_rows(const AttnParams &p, int tid, int b, int g)
-{
-    for (int idx = tid; idx < R * D; idx += NTHREADS) {
-        const int r = idx / D, d = idx % D;
-        p.out[((int64_t)b * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(0.f);
     }
 }
 
@@ -124,87 +97,118 @@ template <class Policy, int NW>
 __host__ __device__ constexpr size_t persist_lds_bytes(int batch, int n_sel)
 {
     return align16((size_t)(2 * batch + 1 + n_sel) * sizeof(int)) +
-           2 * sizeof(WaveMergeLds<Policy::D, Policy::R, NW>) +
-           2 * sizeof(ResultLds<Policy::D, Policy::R>) +
-           2 * (size_t)Policy::R * Policy::D * sizeof(__half) +
-           (size_t)NW * Policy::kWaveLdsBytes;
+           2 * NW * sizeof(Mailbox<Policy::D, Policy::R>) + (size_t)NW * Policy::kWaveLdsBytes;
 }
 
-__device__ __forceinline__ void workgroup_barrier()
+__device__ __forceinline__ int mail_load(const int *flag)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void mail_store(int *flag, int v)
+{
+    __hip_atomic_store(flag, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 template <class Policy, int NW>
-__global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(Policy::kWavesPerEu))) void attn_chunk_persistent_kernel(const AttnParams p,
-                                                                              const int batch)
+__global__ __launch_bounds__((NW + 1) * 64)
+    __attribute__((amdgpu_waves_per_eu(Policy::kWavesPerEu))) void attn_chunk_persistent_kernel(
+        const AttnParams p, const int batch)
 {
     constexpr int D = Policy::D;
     constexpr int R = Policy::R;
     constexpr int NT = (NW + 1) * 64;
     constexpr int kTileBytes = kBlockTokens * D * 2;
-    using Lds = WaveMergeLds<D, R, NW>;
+    using Mail = Mailbox<D, R>;
     using Tile = typename Policy::Tile;
     extern __shared__ __align__(16) unsigned char smem[];
     int *lens = reinterpret_cast<int *>(smem);
     int *first = lens + batch;
     int *hids = first + batch + 1;
     unsigned char *after_tables = smem + align16((size_t)(2 * batch + 1 + p.n_sel) * sizeof(int));
-    Lds *sm = reinterpret_cast<Lds *>(after_tables);
-    using Res = ResultLds<D, R>;
-    Res *res = reinterpret_cast<Res *>(after_tables + 2 * sizeof(Lds));
-    constexpr int kQBytes = R * D * (int)sizeof(__half);      // query rows of one item
-    unsigned char *q_stage = after_tables + 2 * sizeof(Lds) + 2 * sizeof(Res);
-    unsigned char *staging = q_stage + 2 * kQBytes;
-    __shared__ int scan[NT];
+    Mail *mail = reinterpret_cast<Mail *>(after_tables);             // [NW][2]
+    unsigned char *staging = after_tables + 2 * NW * sizeof(Mail);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // ---- work enumeration: exclusive scan of items per sequence
+    // ---- work enumeration: exclusive scan of items per sequence, done by wave 0 alone
+    // (64 sequences per step: per-lane count, in-wave inclusive scan, running carry)
     for (int i = tid; i < p.n_sel; i += NT) hids[i] = p.head_ids[i];
-    {
-        const int seg = (batch + NT - 1) / NT;
-        const int lo = min(batch, tid * seg), hi = min(batch, lo + seg);
-        int sum = 0;
-        for (int b = lo; b < hi; ++b) {
-            const int L = p.seq_lens[b];
-            lens[b] = L;
+    if (tid < 2 * NW) mail[tid].flag = kMailEmpty;
+    if (wave == 0) {
+        int carry = 0;
+        for (int b0 = 0; b0 < batch; b0 += 64) {
+            const int b = b0 + lane;
+            const int L = b < batch ? p.seq_lens[b] : 0;
             int n = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-            if (L <= 0) n = p.direct_single ? 1 : 0;      // the item that writes the zeros
-            sum += n;
+            if (L <= 0) n = (p.direct_single && b < batch) ? 1 : 0;   // the item that writes the zeros
+            int incl = n;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += up;
+            }
+            if (b < batch) {
+                lens[b] = L;
+                first[b] = carry + incl - n;
+            }
+            carry += __shfl(incl, 63, 64);
         }
-        scan[tid] = sum;
-        __syncthreads();
-        for (int off = 1; off < NT; off <<= 1) {
-            const int v = (tid >= off) ? scan[tid - off] : 0;
-            __syncthreads();
-            scan[tid] += v;
-            __syncthreads();
-        }
-        int run = scan[tid] - sum;
-        for (int b = lo; b < hi; ++b) {
-            first[b] = run;
-            const int L = lens[b];
-            int n = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-            if (L <= 0) n = p.direct_single ? 1 : 0;
-            run += n;
-        }
-        if (tid == NT - 1) first[batch] = scan[NT - 1];
-        __syncthreads();
+        if (lane == 0) first[batch] = carry;
     }
+    __syncthreads();
     const int total = first[batch] * p.n_sel;
-    const int G = gridDim.x;
 
-    // sequences are visited in ascending order: `cursor` resumes the search where it ended
+    if (wave == NW) {
+        // ------------------------------------------------------------ writer wave
+        int next_box[NW];
+#pragma unroll
+        for (int v = 0; v < NW; ++v) next_box[v] = 0;
+        int done_mask = 0;
+        int idle = 0;
+        while (done_mask != (1 << NW) - 1 && idle < kSpinLimit) {
+            bool progressed = false;
+#pragma unroll
+            for (int v = 0; v < NW; ++v) {
+                if (done_mask & (1 << v)) continue;
+                Mail &mb = mail[v * 2 + next_box[v]];
+                const int f = __builtin_amdgcn_readfirstlane(mail_load(&mb.flag));
+                if (f == kMailFull) {
+                    flush_mailbox<D, R>(mb, p, lane);
+                    mail_store(&mb.flag, kMailEmpty);
+                    next_box[v] ^= 1;
+                    progressed = true;
+                } else if (f == kMailDone) {
+                    done_mask |= 1 << v;
+                    progressed = true;
+                }
+            }
+            if (progressed) {
+                idle = 0;
+            } else {
+                ++idle;
+                __builtin_amdgcn_s_sleep(8);
+            }
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- streaming waves
+    // item number -> sequence: binary search in the first-chunk table; sequences are visited
+    // in ascending order, so `cursor` (the last answer) is the lower end of the search
     auto decode = [&](int w, ItemHdr &h, int &cursor) {
         const int cg = w / p.n_sel;
         h.si = w - cg * p.n_sel;
-        while (first[cursor + 1] <= cg) ++cursor;
-        cursor = __builtin_amdgcn_readfirstlane(cursor);
+        int lo = cursor, hi = batch - 1;          // answer: the last b with first[b] <= cg
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (first[mid] <= cg)
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        cursor = __builtin_amdgcn_readfirstlane(lo);
         h.b = cursor;
         h.c = __builtin_amdgcn_readfirstlane(cg - first[h.b]);
         const int L = __builtin_amdgcn_readfirstlane(lens[h.b]);
@@ -217,77 +221,24 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(P
         h.nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
         h.rem = n_tok & (kBlockTokens - 1);
     };
-
-    int w = blockIdx.x;
-    if (w >= total) return;
-
-    // ---- query rows: global -> registers -> LDS, a share per streaming wave
-    static_assert(kQBytes % (NW * 16) == 0, "query rows split evenly over the streaming waves");
-    constexpr int kQShare = kQBytes / NW;                     // bytes per wave
-    constexpr int kQVec = (kQShare / 16 + 63) / 64;           // uint4 per lane
-    int cursor_q = 0;
-    auto q_fetch = [&](int wi, uint4 (&qv)[kQVec]) {          // unconditional, indices clamped
-        ItemHdr h;
-        decode(min(wi, total - 1), h, cursor_q);
-        const uint4 *src = reinterpret_cast<const uint4 *>(
-            p.q + ((int64_t)h.b * p.n_q_heads + h.g * R) * D) + wave * (kQShare / 16);
-#pragma unroll
-        for (int i = 0; i < kQVec; ++i) qv[i] = src[min(lane + 64 * i, kQShare / 16 - 1)];
-    };
-    auto q_store = [&](const uint4 (&qv)[kQVec], int par) {
-        uint4 *dst = reinterpret_cast<uint4 *>(q_stage + par * kQBytes) + wave * (kQShare / 16);
-#pragma unroll
-        for (int i = 0; i < kQVec; ++i)
-            if (lane + 64 * i < kQShare / 16) dst[lane + 64 * i] = qv[i];
-    };
-    uint4 qv[kQVec];
-    if (wave < NW) {
-        q_fetch(w, qv);
-        q_store(qv, 0);
-        q_fetch(w + G, qv);           // stays in registers until the first item's barrier
-    }
-    __syncthreads();
-
-    if (wave == NW) {
-        // ------------------------------------------------------------ writer wave
-        int n = 0, cursor = 0;
-        ItemHdr prev;
-        bool have_prev = false;
-        for (; w < total; w += G, ++n) {
-            ItemHdr h;
-            decode(w, h, cursor);
-            workgroup_barrier();                  // ends item n; item n - 1 is now combined
-            if (have_prev)
-                flush_result<D, R>(res[(n - 1) & 1], p, lane, prev.b, prev.g, prev.si, prev.c,
-                                   prev.to_out);
-            have_prev = !h.zero;
-            prev = h;
-            if (h.zero) write_zero_rows<D, R, 64>(p, lane, h.b, h.g);
-        }
-        workgroup_barrier();                      // the last item is combined
-        if (have_prev)
-            flush_result<D, R>(res[(n - 1) & 1], p, lane, prev.b, prev.g, prev.si, prev.c,
-                               prev.to_out);
-        return;
-    }
-
-    // ---------------------------------------------------------------- streaming waves
     struct Slot {
         ItemHdr h;
-        int n_my;           // tiles this wave owns: blocks wave, wave+NW, ...
-        int ids;            // lane i: physical block of this wave's i-th tile
+        int ids;            // lane i: physical block of the item's i-th tile
         int64_t head_off;
         bool exists;
     };
     int cursor = 0;
     auto fill = [&](int wi, Slot &s) {
         s.exists = wi < total;
-        decode(min(wi, total - 1), s.h, cursor);
-        s.n_my = (s.exists && s.h.nblk > wave) ? (s.h.nblk - wave + NW - 1) / NW : 0;
+        decode(min(wi, max(total - 1, 0)), s.h, cursor);
+        if (!s.exists) s.h.nblk = 0;
         s.head_off = (int64_t)s.h.g * p.stride_head;
         const int32_t *bt =
             p.block_table + (int64_t)s.h.b * p.max_blocks_per_seq + s.h.t0 / kBlockTokens;
-        s.ids = bt[min(wave + NW * lane, max(s.h.nblk - 1, 0))];
+        s.ids = bt[min(lane, max(s.h.nblk - 1, 0))];
+    };
+    auto q_rows = [&](const Slot &s) {
+        return p.q + ((int64_t)s.h.b * p.n_q_heads + s.h.g * R) * D;
     };
     auto issue = [&](Tile &t, int ids, int idx, int64_t head_off, bool valid) {
         const int blk = __builtin_amdgcn_readlane(ids, idx & 63);
@@ -295,36 +246,50 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(P
         Policy::issue(t, tile_rsrc(p.k_cache + base, kTileBytes, valid),
                       tile_rsrc(p.v_cache + base, kTileBytes, valid), lane);
     };
+    // bounded wait for a mailbox of this wave to be empty
+    auto wait_empty = [&](Mail &mb) {
+        for (int spin = 0; spin < kSpinLimit; ++spin) {
+            if (__builtin_amdgcn_readfirstlane(mail_load(&mb.flag)) == kMailEmpty) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+    };
+
+    const int stride = gridDim.x * NW;
+    int w = blockIdx.x * NW + wave;
+    unsigned char *my_staging = staging + (size_t)wave * Policy::kWaveLdsBytes;
+    Mail *my_mail = mail + wave * 2;
+    if (total <= 0 || w >= total) {
+        mail_store(&my_mail[0].flag, kMailDone);
+        return;
+    }
 
     Slot cur, nxt, nn;
     typename Policy::Query q;
+    typename Policy::QueryPrefetch q_pre;
     Tile A, B;
-    unsigned char *my_staging = staging + (size_t)wave * Policy::kWaveLdsBytes;
     fill(w, cur);
-    fill(w + G, nxt);
-    issue(A, cur.ids, 0, cur.head_off, 0 < cur.n_my);
-    issue(B, cur.ids, 1, cur.head_off, 1 < cur.n_my);
+    fill(w + stride, nxt);
+    Policy::q_prefetch(q_pre, q_rows(cur), lane);
+    issue(A, cur.ids, 0, cur.head_off, 0 < cur.h.nblk);
+    issue(B, cur.ids, 1, cur.head_off, 1 < cur.h.nblk);
     int n = 0;
     for (;; ++n) {
-        fill(w + 2 * G, nn);        // header and block ids two items ahead
-        Policy::load_q(q, reinterpret_cast<const __half *>(q_stage + (n & 1) * kQBytes), lane);
-        q_store(qv, (n + 1) & 1);   // rows of item n + 1, loaded one item ago
-        q_fetch(w + 2 * G, qv);     // rows of item n + 2
+        fill(w + 2 * stride, nn);                       // header and block ids two items ahead
+        Policy::q_commit(q, q_pre, my_staging, lane);   // this item's query operand
+        Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next item's query rows
 
         typename Policy::State st;
         Policy::reset(st);
-        const int n_my = cur.n_my;
-        const int lim = 2 * max(1, (n_my + 1) >> 1);     // tiles of this item, as whole pairs
+        const int n_my = cur.h.nblk;
+        const int lim = 2 * max(1, (n_my + 1) >> 1);    // tiles of this item, as whole pairs
         // refill with tile j of the pair stream: tiles of `cur`, then the first pair of `nxt`
         auto refill = [&](Tile &t, int j) {
             const bool in_cur = j < lim;
             issue(t, in_cur ? cur.ids : nxt.ids, in_cur ? j : j - lim,
-                  in_cur ? cur.head_off : nxt.head_off, in_cur ? j < n_my : j - lim < nxt.n_my);
+                  in_cur ? cur.head_off : nxt.head_off, in_cur ? j < n_my : j - lim < nxt.h.nblk);
         };
-        // the ragged block, if any, is the chunk's last block: the last tile of one wave
-        const bool mine_ragged = cur.h.rem != 0 && ((cur.h.nblk - 1) % NW) == wave;
         auto consume = [&](const Tile &t, int i) {
-            const int n_valid = (mine_ragged && i == n_my - 1) ? cur.h.rem : kBlockTokens;
+            const int n_valid = (cur.h.rem != 0 && i == n_my - 1) ? cur.h.rem : kBlockTokens;
             Policy::update(st, t, q, p.scale_log2, lane, n_valid, my_staging);
         };
         // The scheduling fences keep "consume a slot, refill it at once" in program order;
@@ -340,15 +305,26 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(P
             refill(B, i + 3);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (!cur.h.zero) Policy::template put<NW>(st, sm[n & 1], wave, lane);
-        workgroup_barrier();                      // ends item n
-        if (!cur.h.zero) lds_combine<D, R, NW, NW * 64>(sm[n & 1], res[n & 1], tid);
+        // hand the finished item to the writer
+        Mail &mb = my_mail[n & 1];
+        wait_empty(mb);
+        if (!cur.h.zero) Policy::finish(st, mb.o, mb.lse, lane);
+        if (lane == 0) {
+            mb.b = cur.h.b;
+            mb.g = cur.h.g;
+            mb.si = cur.h.si;
+            mb.c = cur.h.c;
+            mb.kind = cur.h.zero ? kKindZero : (cur.h.to_out ? kKindOut : kKindPartial);
+        }
+        mail_store(&mb.flag, kMailFull);
         if (!nxt.exists) break;
         cur = nxt;
         nxt = nn;
-        w += G;
+        w += stride;
     }
-    workgroup_barrier();                          // lets the writer see the last combined item
+    Mail &last = my_mail[(n + 1) & 1];
+    wait_empty(last);
+    mail_store(&last.flag, kMailDone);
 }
 
 }  // namespace hetis

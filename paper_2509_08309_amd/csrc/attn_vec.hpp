@@ -148,6 +148,76 @@ __device__ __forceinline__ void vec_wave_merge(VecState<D, R> &st)
     }
 }
 
+// ---- helpers of the simple (non-persistent) kernel: cross-wave merge through LDS
+template <int D, int R, int NW>
+struct WaveMergeLds {
+    float o[NW][R][D];
+    float m[NW][R];
+    float l[NW][R];
+};
+
+template <int D, int R>
+struct ResultLds {
+    float o[R][D];      // normalised output rows
+    float lse[R];       // natural-log log-sum-exp of each row (used by partial results only)
+};
+
+// After a barrier: combine the NW wave results (ascending wave order) into the result area.
+template <int D, int R, int NW, int NTHREADS>
+__device__ __forceinline__ void lds_combine(const WaveMergeLds<D, R, NW> &sm, ResultLds<D, R> &res,
+                                            int tid)
+{
+    for (int idx = tid; idx < R * D; idx += NTHREADS) {
+        const int r = idx / D, d = idx % D;
+        float M = sm.m[0][r];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm.m[w][r]);
+        float acc = 0.f, lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float a = fast_exp2(sm.m[w][r] - M);
+            acc += sm.o[w][r][d] * a;
+            lsum += sm.l[w][r] * a;
+        }
+        res.o[r][d] = acc * __builtin_amdgcn_rcpf(lsum);
+        if (d == 0) res.lse[r] = (M + fast_log2(lsum)) * kLn2;
+    }
+}
+
+// Result area -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
+template <int D, int R>
+__device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const AttnParams &p,
+                                             int lane, int b, int g, int si, int c, bool to_out)
+{
+    const int rows = p.n_sel * R;
+    for (int idx = lane * 4; idx < R * D; idx += 256) {
+        const int r = idx / D, d = idx % D;
+        const float4 v = *reinterpret_cast<const float4 *>(&res.o[r][d]);
+        if (to_out) {
+            union {
+                __half2 h[2];
+                uint2 u;
+            } pk;
+            pk.h[0] = __floats2half2_rn(v.x, v.y);
+            pk.h[1] = __floats2half2_rn(v.z, v.w);
+            *reinterpret_cast<uint2 *>(p.out + ((int64_t)b * p.n_q_heads + g * R + r) * D + d) = pk.u;
+        } else {
+            const int64_t row = ((int64_t)b * rows + si * R + r) * p.max_chunks + c;
+            *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
+            if (d == 0) p.lse_partial[row] = res.lse[r];
+        }
+    }
+}
+
+template <int D, int R, int NTHREADS>
+__device__ __forceinline__ void write_zero_rows(const AttnParams &p, int tid, int b, int g)
+{
+    for (int idx = tid; idx < R * D; idx += NTHREADS) {
+        const int r = idx / D, d = idx % D;
+        p.out[((int64_t)b * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(0.f);
+    }
+}
+
 template <int D, int R, int NW>
 __device__ __forceinline__ void vec_lds_put(WaveMergeLds<D, R, NW> &sm, const VecState<D, R> &st,
                                             int wave, int gid, int sub)
@@ -258,7 +328,8 @@ struct VecPolicy {
 #pragma unroll
         for (int i = 0; i < Tile::NI; ++i) t.v[i] = buffer_load_u4(rv, voff + i * 1024);
     }
-    __device__ static __forceinline__ void load_q(Query &q, const __half *rows, int lane)
+    using QueryPrefetch = Query;                 // loaded from global in its final layout
+    __device__ static __forceinline__ void q_prefetch(QueryPrefetch &q, const __half *rows, int lane)
     {
         const int sub = lane % (D / 8);
 #pragma unroll
@@ -269,6 +340,11 @@ struct VecPolicy {
             for (int x = 0; x < 4; ++x) q.h[r][x] = t.h2[x];
         }
     }
+    __device__ static __forceinline__ void q_commit(Query &q, const QueryPrefetch &pre,
+                                                    unsigned char *, int)
+    {
+        q = pre;
+    }
     __device__ static __forceinline__ void reset(State &st) { st.reset(); }
     // n_valid < 16 only for the ragged last block of a sequence: a separate masked copy of
     // the arithmetic keeps the common case free of compares and selects
@@ -278,12 +354,25 @@ struct VecPolicy {
     {
         vec_tile_update_any<D, R>(st, t, q.h, scale_log2, lane / (D / 8), n_valid);
     }
-    template <int NW>
-    __device__ static __forceinline__ void put(State &st, WaveMergeLds<D, R, NW> &sm, int wave,
-                                               int lane)
+    // normalised rows and their log-sum-exp -> LDS (the wave's mailbox)
+    __device__ static __forceinline__ void finish(State &st, float (&o)[R][D], float (&lse)[R],
+                                                  int lane)
     {
-        vec_wave_merge<D, R>(st);
-        vec_lds_put<D, R, NW>(sm, st, wave, lane / (D / 8), lane % (D / 8));
+        vec_wave_merge<D, R>(st);                // every lane group now holds the item's totals
+        const int gid = lane / (D / 8), sub = lane % (D / 8);
+        if (gid == 0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float inv = __builtin_amdgcn_rcpf(st.l[r]);
+                float4 lo = make_float4(st.o[r][0] * inv, st.o[r][1] * inv, st.o[r][2] * inv,
+                                        st.o[r][3] * inv);
+                float4 hi = make_float4(st.o[r][4] * inv, st.o[r][5] * inv, st.o[r][6] * inv,
+                                        st.o[r][7] * inv);
+                *reinterpret_cast<float4 *>(&o[r][sub * 8]) = lo;
+                *reinterpret_cast<float4 *>(&o[r][sub * 8 + 4]) = hi;
+                if (sub == 0) lse[r] = (st.m[r] + fast_log2(st.l[r])) * kLn2;
+            }
+        }
     }
 };
 

@@ -23,8 +23,8 @@ constexpr int kVecWaves = 4;
 // Largest batch whose length scan fits the persistent kernel's LDS table.
 constexpr int kMaxPersistBatch = 4096;
 constexpr int kMaxPersistHeads = 1024;
-// A wave keeps the block ids of its tiles of one chunk in one register (64 lanes).
-constexpr int kMaxChunkTokens = 64 * kVecWaves * kBlockTokens;
+// A wave keeps the block ids of one chunk in one register (64 lanes).
+constexpr int kMaxChunkTokens = 64 * kBlockTokens;
 
 struct Checked {
     int group;          // r
@@ -121,9 +121,8 @@ static int launch_persistent(const AttnParams &p, int batch, hipStream_t st)
     if (env_cap > 0 && occ > env_cap) occ = env_cap;
     const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
     int64_t G = (int64_t)cus * occ;
-    if (G > max_items) G = max_items;
-    // a multiple of the head count keeps the heads of one chunk on neighbouring workgroups
-    if (G > p.n_sel) G -= G % p.n_sel;
+    const int64_t enough = (max_items + NW - 1) / NW;     // one item per streaming wave
+    if (G > enough) G = enough;
     kernel<<<dim3((unsigned)G), (NW + 1) * 64, lds, st>>>(p, batch);
     return HETIS_OK;
 }
