@@ -30,6 +30,8 @@ struct AttnParams {
     int32_t chunk_tokens;       // multiple of 16
     int32_t max_chunks;
     int32_t direct_single;      // 1: a sequence of <= 1 chunk is written to `out` by the partial pass
+    unsigned int *tickets;      // [2] device words, zero between launches: item tickets drawn,
+                                // workgroups finished
     float scale_log2;           // scale * log2(e): scores are kept in the base-2 domain
 };
 

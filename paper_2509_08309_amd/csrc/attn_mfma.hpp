@@ -124,6 +124,7 @@ struct MfmaPolicy {
     // One code path for full and ragged tiles (n_valid = 16 makes every select a no-op):
     // two copies of this body would leave the accumulators in different registers on the two
     // sides of a branch and cost 32 register moves per tile to reconcile.
+    template <bool MAYBE_RAGGED>
     __device__ static __forceinline__ void update(State &st, const Tile &t, const Query &q,
                                                   float scale_log2, int lane, int n_valid,
                                                   unsigned char *stage)

@@ -2,11 +2,19 @@
 // independent of how a tile is turned into scores and sums (that is the Policy: vector ALU
 // arithmetic for small query groups, MFMA for grouped-query attention).
 //
-// Work enumeration: every workgroup scans the sequence lengths into a table of first-chunk
-// indices (LDS), which turns a flat item number into (sequence, chunk, selected head)
-// without launching a workgroup per possible chunk.  An item is one chunk of one
-// (sequence, selected head) and is processed by ONE wave; streaming wave number
-// blockIdx * NW + wave takes items of that number, that number + (waves in the grid), ...
+// Work enumeration: every workgroup scans the sequence lengths into two tables of running
+// counts (LDS): whole chunks per sequence and ragged last chunks per sequence.  A flat item
+// number then decodes into (sequence, chunk, selected head) by binary search, whole chunks
+// first and ragged ones last, without launching a workgroup per possible chunk.  An item is
+// one chunk of one (sequence, selected head) and is processed by ONE wave.
+// Work distribution: the first two items of a streaming wave are fixed by its number; the
+// rest come from a global ticket counter, so that waves which drew short chunks simply take
+// more of them.  Tickets are drawn by the workgroup's writer wave, eight per device atomic
+// while plenty of work is left and fewer towards the end, into a small LDS pool from which
+// the streaming waves take them with an LDS atomic shortly before they finish an item.  Which wave computes an item has no
+// influence on the item's arithmetic.  The ticket counter and a counter of finished
+// workgroups live in a small device buffer (AttnParams::tickets); the workgroup that
+// finishes last sets both back to zero for the next launch.
 //
 // A workgroup is NW streaming waves plus one writer wave; after the prologue they never
 // meet at a barrier.
@@ -21,14 +29,13 @@
 //     force every later wait to drain all loads.  A finished item (normalised rows and
 //     their log-sum-exp) is handed over through one of the wave's two LDS mailboxes.
 //   - The writer wave polls the mailboxes and copies full ones to global memory (fp16 row,
-//     fp32 partial, or zeros for an empty sequence).  It never loads from global memory,
-//     so it never waits for its stores.
+//     fp32 partial, or zeros for an empty sequence), and keeps the ticket pool filled.
 // Mailbox protocol (flag is a workgroup-scope atomic in LDS): EMPTY -> the producer fills
 // data and header -> FULL -> the writer copies it out -> EMPTY.  A producer that has no more
 // items marks its next mailbox DONE; the writer leaves when all NW are DONE.  All waits are
 // polling loops with an iteration bound, so every wave reaches its end whatever happens.
-// Dynamic LDS: int lens[batch], int first[batch + 1], int hids[n_sel]; NW x 2 mailboxes; NW
-// per-wave staging areas of Policy::kWaveLdsBytes.
+// Dynamic LDS: int lens[batch], int firstF[batch + 1], int firstT[batch + 1], int
+// hids[n_sel]; NW x 2 mailboxes; NW per-wave staging areas of Policy::kWaveLdsBytes.
 // Nothing depends on how many heads were selected or on the grid size: the result for one
 // (sequence, head) is a function of that sequence's length alone.
 #pragma once
@@ -39,6 +46,15 @@ namespace hetis {
 enum : int { kMailEmpty = 0, kMailFull = 1, kMailDone = 2 };
 enum : int { kKindOut = 0, kKindPartial = 1, kKindZero = 2 };
 constexpr int kSpinLimit = 1 << 22;     // polls before a wait gives up (far beyond any real wait)
+constexpr int kPoolSize = 32;           // item numbers the LDS ticket pool can hold
+constexpr int kTicketBatch = 8;         // tickets per device atomic
+
+// Item numbers waiting to be taken by the streaming waves of one workgroup.
+struct TicketPool {
+    int next;               // entries taken so far  (LDS atomic, streaming waves)
+    int end;                // entries published so far (written by the writer wave)
+    int items[kPoolSize];   // ring: entry i lives in items[i % kPoolSize]
+};
 
 // One finished item on its way to global memory.
 template <int D, int R>
@@ -96,7 +112,7 @@ __host__ __device__ constexpr size_t align16(size_t x) { return (x + 15) & ~(siz
 template <class Policy, int NW>
 __host__ __device__ constexpr size_t persist_lds_bytes(int batch, int n_sel)
 {
-    return align16((size_t)(2 * batch + 1 + n_sel) * sizeof(int)) +
+    return align16((size_t)(3 * batch + 2 + n_sel) * sizeof(int)) +
            2 * NW * sizeof(Mailbox<Policy::D, Policy::R>) + (size_t)NW * Policy::kWaveLdsBytes;
 }
 
@@ -122,9 +138,11 @@ __global__ __launch_bounds__((NW + 1) * 64)
     using Tile = typename Policy::Tile;
     extern __shared__ __align__(16) unsigned char smem[];
     int *lens = reinterpret_cast<int *>(smem);
-    int *first = lens + batch;
-    int *hids = first + batch + 1;
-    unsigned char *after_tables = smem + align16((size_t)(2 * batch + 1 + p.n_sel) * sizeof(int));
+    int *firstF = lens + batch;               // whole chunks before sequence b
+    int *firstT = firstF + batch + 1;         // ragged last chunks (and zero items) before b
+    int *hids = firstT + batch + 1;
+    unsigned char *after_tables = smem + align16((size_t)(3 * batch + 2 + p.n_sel) * sizeof(int));
+    __shared__ TicketPool pool;
     Mail *mail = reinterpret_cast<Mail *>(after_tables);             // [NW][2]
     unsigned char *staging = after_tables + 2 * NW * sizeof(Mail);
 
@@ -136,29 +154,45 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // (64 sequences per step: per-lane count, in-wave inclusive scan, running carry)
     for (int i = tid; i < p.n_sel; i += NT) hids[i] = p.head_ids[i];
     if (tid < 2 * NW) mail[tid].flag = kMailEmpty;
+    if (tid == 0) {
+        pool.next = 0;
+        pool.end = 0;
+    }
     if (wave == 0) {
-        int carry = 0;
+        int carryF = 0, carryT = 0;
         for (int b0 = 0; b0 < batch; b0 += 64) {
             const int b = b0 + lane;
             const int L = b < batch ? p.seq_lens[b] : 0;
-            int n = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-            if (L <= 0) n = (p.direct_single && b < batch) ? 1 : 0;   // the item that writes the zeros
-            int incl = n;
+            const int nF = L > 0 ? L / p.chunk_tokens : 0;
+            int nT = (L > 0 && L % p.chunk_tokens != 0) ? 1 : 0;
+            if (L <= 0 && b < batch && p.direct_single) nT = 1;       // the item that writes the zeros
+            int inclF = nF, inclT = nT;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(incl, off, 64);
-                if (lane >= off) incl += up;
+                const int upF = __shfl_up(inclF, off, 64);
+                const int upT = __shfl_up(inclT, off, 64);
+                if (lane >= off) {
+                    inclF += upF;
+                    inclT += upT;
+                }
             }
             if (b < batch) {
                 lens[b] = L;
-                first[b] = carry + incl - n;
+                firstF[b] = carryF + inclF - nF;
+                firstT[b] = carryT + inclT - nT;
             }
-            carry += __shfl(incl, 63, 64);
+            carryF += __shfl(inclF, 63, 64);
+            carryT += __shfl(inclT, 63, 64);
         }
-        if (lane == 0) first[batch] = carry;
+        if (lane == 0) {
+            firstF[batch] = carryF;
+            firstT[batch] = carryT;
+        }
     }
     __syncthreads();
-    const int total = first[batch] * p.n_sel;
+    const int totalF = firstF[batch];                         // whole chunks of all sequences
+    const int total = (totalF + firstT[batch]) * p.n_sel;
+    const int stride = gridDim.x * NW;                        // streaming waves in the grid
 
     if (wave == NW) {
         // ------------------------------------------------------------ writer wave
@@ -167,8 +201,35 @@ __global__ __launch_bounds__((NW + 1) * 64)
         for (int v = 0; v < NW; ++v) next_box[v] = 0;
         int done_mask = 0;
         int idle = 0;
+        int pool_end = 0;                 // entries published so far
+        long long last_base = 2ll * stride;   // item number of the last ticket drawn here
+        bool exhausted = total <= 2 * stride;    // no item left beyond the fixed ones
         while (done_mask != (1 << NW) - 1 && idle < kSpinLimit) {
             bool progressed = false;
+            // keep the ticket pool ahead of the streaming waves
+            const int taken = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load(&pool.next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+            // batch size shrinks as the work runs out (judged by the last ticket seen), so
+            // that the last items are not parked in one workgroup's pool
+            const long long left = (long long)total - last_base;
+            const int batch = left > 16ll * stride ? kTicketBatch : (left > 4ll * stride ? 2 : 1);
+            if (pool_end - taken < batch) {
+                long long base = total;   // past the last item: "no more work"
+                if (!exhausted) {
+                    unsigned t = 0;
+                    if (lane == 0)
+                        t = __hip_atomic_fetch_add(p.tickets, (unsigned)batch, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                    base = 2ll * stride + __builtin_amdgcn_readfirstlane(t);
+                    last_base = base;
+                    if (base + batch >= total) exhausted = true;
+                }
+                if (lane < batch)
+                    pool.items[(pool_end + lane) % kPoolSize] = (int)min(base + lane, (long long)total);
+                pool_end += batch;
+                __hip_atomic_store(&pool.end, pool_end, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                progressed = true;
+            }
 #pragma unroll
             for (int v = 0; v < NW; ++v) {
                 if (done_mask & (1 << v)) continue;
@@ -188,36 +249,60 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 idle = 0;
             } else {
                 ++idle;
-                __builtin_amdgcn_s_sleep(8);
+                __builtin_amdgcn_s_sleep(4);
+            }
+        }
+        // every streaming wave of this workgroup is done, so no more tickets will be drawn
+        // here: count the workgroup out; the last one to leave rearms both counters
+        if (lane == 0) {
+            const unsigned gone = __hip_atomic_fetch_add(p.tickets + 1, 1u, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            if (gone == gridDim.x - 1) {
+                __hip_atomic_store(p.tickets + 0, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(p.tickets + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         return;
     }
 
     // ---------------------------------------------------------------- streaming waves
-    // item number -> sequence: binary search in the first-chunk table; sequences are visited
-    // in ascending order, so `cursor` (the last answer) is the lower end of the search
-    auto decode = [&](int w, ItemHdr &h, int &cursor) {
-        const int cg = w / p.n_sel;
-        h.si = w - cg * p.n_sel;
-        int lo = cursor, hi = batch - 1;          // answer: the last b with first[b] <= cg
+    // item number -> (sequence, chunk, head): whole chunks come first, ragged last chunks
+    // after them; binary search in the matching running-count table.  Item numbers of a wave
+    // only grow, so the last answer of each table is the lower end of the next search.
+    int cursorF = 0, cursorT = 0;
+    auto upper = [&](const int *tab, int key, int lo) {       // last b with tab[b] <= key
+        int hi = batch - 1;
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
-            if (first[mid] <= cg)
+            if (tab[mid] <= key)
                 lo = mid;
             else
                 hi = mid - 1;
         }
-        cursor = __builtin_amdgcn_readfirstlane(lo);
-        h.b = cursor;
-        h.c = __builtin_amdgcn_readfirstlane(cg - first[h.b]);
-        const int L = __builtin_amdgcn_readfirstlane(lens[h.b]);
+        return __builtin_amdgcn_readfirstlane(lo);
+    };
+    auto decode = [&](int w, ItemHdr &h) {
+        const int cg = w / p.n_sel;
+        h.si = w - cg * p.n_sel;
         h.g = __builtin_amdgcn_readfirstlane(hids[h.si]);
+        int L, n_tok;
+        if (cg < totalF) {
+            cursorF = upper(firstF, cg, cursorF);
+            h.b = cursorF;
+            h.c = __builtin_amdgcn_readfirstlane(cg - firstF[h.b]);
+            L = __builtin_amdgcn_readfirstlane(lens[h.b]);
+            n_tok = p.chunk_tokens;
+        } else {
+            cursorT = upper(firstT, cg - totalF, cursorT);
+            h.b = cursorT;
+            L = __builtin_amdgcn_readfirstlane(lens[h.b]);
+            h.c = L > 0 ? L / p.chunk_tokens : 0;
+            n_tok = L > 0 ? L - h.c * p.chunk_tokens : 0;
+        }
         const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
         h.to_out = p.direct_single && n_chunks <= 1;
         h.zero = L <= 0;
         h.t0 = h.c * p.chunk_tokens;
-        const int n_tok = h.zero ? 0 : min(L, h.t0 + p.chunk_tokens) - h.t0;
         h.nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
         h.rem = n_tok & (kBlockTokens - 1);
     };
@@ -227,10 +312,9 @@ __global__ __launch_bounds__((NW + 1) * 64)
         int64_t head_off;
         bool exists;
     };
-    int cursor = 0;
     auto fill = [&](int wi, Slot &s) {
         s.exists = wi < total;
-        decode(min(wi, max(total - 1, 0)), s.h, cursor);
+        decode(min(wi, max(total - 1, 0)), s.h);
         if (!s.exists) s.h.nblk = 0;
         s.head_off = (int64_t)s.h.g * p.stride_head;
         const int32_t *bt =
@@ -253,9 +337,22 @@ __global__ __launch_bounds__((NW + 1) * 64)
             __builtin_amdgcn_s_sleep(2);
         }
     };
+    // next item number from the workgroup's ticket pool (`total` = none left)
+    auto take_ticket = [&]() {
+        int i = 0;
+        if (lane == 0)
+            i = __hip_atomic_fetch_add(&pool.next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        i = __builtin_amdgcn_readfirstlane(i);
+        for (int spin = 0; spin < kSpinLimit; ++spin) {
+            const int end = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load(&pool.end, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+            if (end > i) return __builtin_amdgcn_readfirstlane(pool.items[i % kPoolSize]);
+            __builtin_amdgcn_s_sleep(2);
+        }
+        return total;
+    };
 
-    const int stride = gridDim.x * NW;
-    int w = blockIdx.x * NW + wave;
+    const int w = blockIdx.x * NW + wave;
     unsigned char *my_staging = staging + (size_t)wave * Policy::kWaveLdsBytes;
     Mail *my_mail = mail + wave * 2;
     if (total <= 0 || w >= total) {
@@ -263,48 +360,59 @@ __global__ __launch_bounds__((NW + 1) * 64)
         return;
     }
 
-    Slot cur, nxt, nn;
+    Slot cur, nxt;
     typename Policy::Query q;
     typename Policy::QueryPrefetch q_pre;
     Tile A, B;
-    fill(w, cur);
-    fill(w + stride, nxt);
+    fill(w, cur);                   // items w and w + stride are this wave's without a ticket
+    nxt = cur;
     Policy::q_prefetch(q_pre, q_rows(cur), lane);
     issue(A, cur.ids, 0, cur.head_off, 0 < cur.h.nblk);
     issue(B, cur.ids, 1, cur.head_off, 1 < cur.h.nblk);
     int n = 0;
     for (;; ++n) {
-        fill(w + 2 * stride, nn);                       // header and block ids two items ahead
         Policy::q_commit(q, q_pre, my_staging, lane);   // this item's query operand
-        Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next item's query rows
 
         typename Policy::State st;
         Policy::reset(st);
         const int n_my = cur.h.nblk;
         const int lim = 2 * max(1, (n_my + 1) >> 1);    // tiles of this item, as whole pairs
-        // refill with tile j of the pair stream: tiles of `cur`, then the first pair of `nxt`
-        auto refill = [&](Tile &t, int j) {
-            const bool in_cur = j < lim;
-            issue(t, in_cur ? cur.ids : nxt.ids, in_cur ? j : j - lim,
-                  in_cur ? cur.head_off : nxt.head_off, in_cur ? j < n_my : j - lim < nxt.h.nblk);
-        };
-        auto consume = [&](const Tile &t, int i) {
-            const int n_valid = (cur.h.rem != 0 && i == n_my - 1) ? cur.h.rem : kBlockTokens;
-            Policy::update(st, t, q, p.scale_log2, lane, n_valid, my_staging);
-        };
         // The scheduling fences keep "consume a slot, refill it at once" in program order;
         // without them the compiler batches both tiles' arithmetic ahead of both refills
         // and the wave ends up waiting with nothing in flight.
-        for (int i = 0; i < lim; i += 2) {
-            if (i < n_my) consume(A, i);
+        auto steady_pair = [&](int i) {                 // whole tiles; refills stay in this item
+            Policy::template update<false>(st, A, q, p.scale_log2, lane, kBlockTokens, my_staging);
             __builtin_amdgcn_sched_barrier(0);
-            refill(A, i + 2);
+            issue(A, cur.ids, i + 2, cur.head_off, i + 2 < n_my);
             __builtin_amdgcn_sched_barrier(0);
-            if (i + 1 < n_my) consume(B, i + 1);
+            Policy::template update<false>(st, B, q, p.scale_log2, lane, kBlockTokens, my_staging);
             __builtin_amdgcn_sched_barrier(0);
-            refill(B, i + 3);
+            issue(B, cur.ids, i + 3, cur.head_off, i + 3 < n_my);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+        // The next item is chosen as late as its block ids allow (three pairs before the end
+        // of this one), so that little undone work is held back when the tickets run out.
+        int i = 0;
+        for (; i + 8 < lim; i += 2) steady_pair(i);
+        fill(n == 0 ? w + stride : take_ticket(), nxt);
+        Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next item's query rows
+        for (; i + 2 < lim; i += 2) steady_pair(i);
+        // last pair of this item (the only place a ragged block can be): its refills are the
+        // first pair of the next item, whose block ids are first touched here, a whole item
+        // after they were loaded
+        auto consume_last = [&](const Tile &t, int j) {
+            const int n_valid = (cur.h.rem != 0 && j == n_my - 1) ? cur.h.rem : kBlockTokens;
+            Policy::template update<true>(st, t, q, p.scale_log2, lane, n_valid, my_staging);
+        };
+        if (i < n_my) consume_last(A, i);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(A, nxt.ids, 0, nxt.head_off, 0 < nxt.h.nblk);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + 1 < n_my) consume_last(B, i + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(B, nxt.ids, 1, nxt.head_off, 1 < nxt.h.nblk);
+        __builtin_amdgcn_sched_barrier(0);
+
         // hand the finished item to the writer
         Mail &mb = my_mail[n & 1];
         wait_empty(mb);
@@ -319,8 +427,6 @@ __global__ __launch_bounds__((NW + 1) * 64)
         mail_store(&mb.flag, kMailFull);
         if (!nxt.exists) break;
         cur = nxt;
-        nxt = nn;
-        w += stride;
     }
     Mail &last = my_mail[(n + 1) & 1];
     wait_empty(last);

@@ -346,13 +346,17 @@ struct VecPolicy {
         q = pre;
     }
     __device__ static __forceinline__ void reset(State &st) { st.reset(); }
-    // n_valid < 16 only for the ragged last block of a sequence: a separate masked copy of
-    // the arithmetic keeps the common case free of compares and selects
+    // MAYBE_RAGGED: the tile may be the ragged last block of a sequence (n_valid < 16); a
+    // separate masked copy of the arithmetic keeps whole tiles free of compares and selects
+    template <bool MAYBE_RAGGED>
     __device__ static __forceinline__ void update(State &st, const Tile &t, const Query &q,
                                                   float scale_log2, int lane, int n_valid,
                                                   unsigned char *)
     {
-        vec_tile_update_any<D, R>(st, t, q.h, scale_log2, lane / (D / 8), n_valid);
+        if (MAYBE_RAGGED)
+            vec_tile_update_any<D, R>(st, t, q.h, scale_log2, lane / (D / 8), n_valid);
+        else
+            vec_tile_update<D, R, false>(st, t, q.h, scale_log2, lane / (D / 8), kBlockTokens);
     }
     // normalised rows and their log-sum-exp -> LDS (the wave's mailbox)
     __device__ static __forceinline__ void finish(State &st, float (&o)[R][D], float (&lse)[R],

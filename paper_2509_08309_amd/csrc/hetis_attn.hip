@@ -19,7 +19,10 @@ namespace hetis {
 #define HETIS_DECODE_CHUNK_TOKENS 256
 #endif
 constexpr int kDecodeChunkTokens = HETIS_DECODE_CHUNK_TOKENS;
-constexpr int kVecWaves = 4;
+#ifndef HETIS_STREAM_WAVES
+#define HETIS_STREAM_WAVES 4
+#endif
+constexpr int kVecWaves = HETIS_STREAM_WAVES;
 // Largest batch whose length scan fits the persistent kernel's LDS table.
 constexpr int kMaxPersistBatch = 4096;
 constexpr int kMaxPersistHeads = 1024;
@@ -101,8 +104,45 @@ static int resident_per_cu(Kernel kernel, int threads, size_t lds)
     return cached_occ;
 }
 
+// Ticket counters of the persistent kernel: kTicketSlots pairs of device words per device,
+// zeroed when allocated and left at zero by every launch that uses them.  Successive
+// launches rotate through the slots, so launches that overlap on different streams do not
+// share a pair unless more than kTicketSlots of them are in flight at once.
+constexpr int kTicketSlots = 64;
+struct TicketBuf {
+    unsigned int *ptr = nullptr;
+    unsigned int next = 0;
+};
+static std::mutex g_ticket_mutex;
+static std::vector<TicketBuf> g_tickets;
+
+static int tickets_for(unsigned int **out)
+{
+    std::lock_guard<std::mutex> lock(g_ticket_mutex);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return HETIS_ERR_ALLOC;
+    if ((size_t)dev >= g_tickets.size()) g_tickets.resize(dev + 1);
+    TicketBuf &t = g_tickets[dev];
+    if (!t.ptr) {
+        void *ptr = nullptr;
+        const size_t bytes = kTicketSlots * 2 * sizeof(unsigned int);
+        if (hipMalloc(&ptr, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return HETIS_ERR_ALLOC;
+        }
+        if (hipMemset(ptr, 0, bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+            (void)hipFree(ptr);
+            (void)hipGetLastError();
+            return HETIS_ERR_ALLOC;
+        }
+        t.ptr = static_cast<unsigned int *>(ptr);
+    }
+    *out = t.ptr + 2 * (t.next++ % kTicketSlots);
+    return HETIS_OK;
+}
+
 template <class Policy>
-static int launch_persistent(const AttnParams &p, int batch, hipStream_t st)
+static int launch_persistent(AttnParams p, int batch, hipStream_t st)
 {
     constexpr int NW = kVecWaves;
     auto kernel = attn_chunk_persistent_kernel<Policy, NW>;
@@ -119,6 +159,8 @@ static int launch_persistent(const AttnParams &p, int batch, hipStream_t st)
         return v > 0 ? v : 0;
     }();
     if (env_cap > 0 && occ > env_cap) occ = env_cap;
+    const int rc = tickets_for(&p.tickets);
+    if (rc != HETIS_OK) return rc;
     const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
     int64_t G = (int64_t)cus * occ;
     const int64_t enough = (max_items + NW - 1) / NW;     // one item per streaming wave
@@ -297,6 +339,11 @@ int hetis_attn_release_workspace(void)
     bool any = false;
     for (size_t d = 0; d < g_ws.size(); ++d)
         if (g_ws[d].ptr) any = true;
+    {
+        std::lock_guard<std::mutex> tlock(g_ticket_mutex);
+        for (size_t d = 0; d < g_tickets.size(); ++d)
+            if (g_tickets[d].ptr) any = true;
+    }
     if (!any) return HETIS_OK;
     if (hipGetDevice(&cur) != hipSuccess) return HETIS_ERR_ALLOC;
     for (size_t d = 0; d < g_ws.size(); ++d) {
@@ -305,6 +352,16 @@ int hetis_attn_release_workspace(void)
         (void)hipDeviceSynchronize();
         (void)hipFree(g_ws[d].ptr);
         g_ws[d] = Workspace();
+    }
+    {
+        std::lock_guard<std::mutex> tlock(g_ticket_mutex);
+        for (size_t d = 0; d < g_tickets.size(); ++d) {
+            if (!g_tickets[d].ptr) continue;
+            (void)hipSetDevice((int)d);
+            (void)hipDeviceSynchronize();
+            (void)hipFree(g_tickets[d].ptr);
+            g_tickets[d] = TicketBuf();
+        }
     }
     (void)hipSetDevice(cur);
     return HETIS_OK;
