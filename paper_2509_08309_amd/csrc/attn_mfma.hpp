@@ -54,6 +54,7 @@ struct MfmaPolicy {
     static constexpr int kQBytes = R * D * 2;
     static constexpr int kWaveLdsBytes = kStageV + kQBytes;
     static constexpr int kWavesPerEu = 2;             // register budget: 512 / 2 per lane
+    static constexpr int kRing = 2;   // tile pairs in flight per wave
 
     struct Tile {
         uint4 k[KS];

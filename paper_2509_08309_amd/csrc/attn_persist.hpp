@@ -18,10 +18,10 @@
 //
 // A workgroup is NW streaming waves plus one writer wave; after the prologue they never
 // meet at a barrier.
-//   - Streaming waves stream the tiles of their item through a two-slot register ring; a
-//     slot is refilled right after it has been consumed, so one to two tile pairs (8-16 KB
-//     per wave) are always in flight, and the ring runs on into the first pair of the next
-//     item before the current item is finished off.  Every global load is issued
+//   - Streaming waves stream the tiles of their item through a register ring of
+//     Policy::kRing slots; a slot is refilled right after it has been consumed, so up to
+//     kRing tile pairs (8 KB each) per wave are in flight, and the ring runs on into the
+//     first tiles of the next item before the current item is finished off.  Every global load is issued
 //     unconditionally (indices clamped, tiles that do not exist turned into zero-length
 //     buffer descriptors), so the in-order load counter is known exactly at every wait.
 //     These waves never store to global memory: on gfx9-class hardware loads and stores
@@ -360,15 +360,16 @@ __global__ __launch_bounds__((NW + 1) * 64)
         return;
     }
 
+    constexpr int RING = Policy::kRing;             // tile pairs a wave keeps in flight, at most
     Slot cur, nxt;
     typename Policy::Query q;
     typename Policy::QueryPrefetch q_pre;
-    Tile A, B;
+    Tile ring[RING];
     fill(w, cur);                   // items w and w + stride are this wave's without a ticket
     nxt = cur;
     Policy::q_prefetch(q_pre, q_rows(cur), lane);
-    issue(A, cur.ids, 0, cur.head_off, 0 < cur.h.nblk);
-    issue(B, cur.ids, 1, cur.head_off, 1 < cur.h.nblk);
+#pragma unroll
+    for (int s = 0; s < RING; ++s) issue(ring[s], cur.ids, s, cur.head_off, s < cur.h.nblk);
     int n = 0;
     for (;; ++n) {
         Policy::q_commit(q, q_pre, my_staging, lane);   // this item's query operand
@@ -376,42 +377,40 @@ __global__ __launch_bounds__((NW + 1) * 64)
         typename Policy::State st;
         Policy::reset(st);
         const int n_my = cur.h.nblk;
-        const int lim = 2 * max(1, (n_my + 1) >> 1);    // tiles of this item, as whole pairs
+        const int lim = RING * max(1, (n_my + RING - 1) / RING);   // tiles, as whole ring turns
         // The scheduling fences keep "consume a slot, refill it at once" in program order;
-        // without them the compiler batches both tiles' arithmetic ahead of both refills
-        // and the wave ends up waiting with nothing in flight.
-        auto steady_pair = [&](int i) {                 // whole tiles; refills stay in this item
-            Policy::template update<false>(st, A, q, p.scale_log2, lane, kBlockTokens, my_staging);
-            __builtin_amdgcn_sched_barrier(0);
-            issue(A, cur.ids, i + 2, cur.head_off, i + 2 < n_my);
-            __builtin_amdgcn_sched_barrier(0);
-            Policy::template update<false>(st, B, q, p.scale_log2, lane, kBlockTokens, my_staging);
-            __builtin_amdgcn_sched_barrier(0);
-            issue(B, cur.ids, i + 3, cur.head_off, i + 3 < n_my);
-            __builtin_amdgcn_sched_barrier(0);
+        // without them the compiler batches the tiles' arithmetic ahead of the refills and
+        // the wave ends up waiting with nothing in flight.
+        auto steady_turn = [&](int i) {                 // whole tiles; refills stay in this item
+#pragma unroll
+            for (int s = 0; s < RING; ++s) {
+                Policy::template update<false>(st, ring[s], q, p.scale_log2, lane, kBlockTokens,
+                                               my_staging);
+                __builtin_amdgcn_sched_barrier(0);
+                issue(ring[s], cur.ids, i + RING + s, cur.head_off, i + RING + s < n_my);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         };
-        // The next item is chosen as late as its block ids allow (three pairs before the end
-        // of this one), so that little undone work is held back when the tickets run out.
+        // The next item is chosen as late as its block ids allow (three ring turns before
+        // the end of this one), so that little undone work is held back when the tickets run
+        // out.
         int i = 0;
-        for (; i + 8 < lim; i += 2) steady_pair(i);
+        for (; i + 4 * RING < lim; i += RING) steady_turn(i);
         fill(n == 0 ? w + stride : take_ticket(), nxt);
         Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next item's query rows
-        for (; i + 2 < lim; i += 2) steady_pair(i);
-        // last pair of this item (the only place a ragged block can be): its refills are the
-        // first pair of the next item, whose block ids are first touched here, a whole item
-        // after they were loaded
-        auto consume_last = [&](const Tile &t, int j) {
-            const int n_valid = (cur.h.rem != 0 && j == n_my - 1) ? cur.h.rem : kBlockTokens;
-            Policy::template update<true>(st, t, q, p.scale_log2, lane, n_valid, my_staging);
-        };
-        if (i < n_my) consume_last(A, i);
-        __builtin_amdgcn_sched_barrier(0);
-        issue(A, nxt.ids, 0, nxt.head_off, 0 < nxt.h.nblk);
-        __builtin_amdgcn_sched_barrier(0);
-        if (i + 1 < n_my) consume_last(B, i + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        issue(B, nxt.ids, 1, nxt.head_off, 1 < nxt.h.nblk);
-        __builtin_amdgcn_sched_barrier(0);
+        for (; i + RING < lim; i += RING) steady_turn(i);
+        // last turn of this item (the only place a ragged block can be): its refills are the
+        // first tiles of the next item
+#pragma unroll
+        for (int s = 0; s < RING; ++s) {
+            if (i + s < n_my) {
+                const int n_valid = (cur.h.rem != 0 && i + s == n_my - 1) ? cur.h.rem : kBlockTokens;
+                Policy::template update<true>(st, ring[s], q, p.scale_log2, lane, n_valid, my_staging);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue(ring[s], nxt.ids, s, nxt.head_off, s < nxt.h.nblk);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
         // hand the finished item to the writer
         Mail &mb = my_mail[n & 1];

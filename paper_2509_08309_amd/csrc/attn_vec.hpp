@@ -311,7 +311,8 @@ struct VecPolicy {
     static constexpr int D = D_;
     static constexpr int R = R_;
     static constexpr int kWaveLdsBytes = 0;      // no per-wave staging area
-    static constexpr int kWavesPerEu = R == 1 ? 4 : 3;   // register budget: 512 / this per lane
+    static constexpr int kWavesPerEu = 2;        // register budget: 512 / 2 per lane
+    static constexpr int kRing = 2;              // tile pairs in flight per wave
     using Tile = TileRegs<D>;
     using State = VecState<D, R>;
     struct Query {

@@ -23,6 +23,7 @@ constexpr int kDecodeChunkTokens = HETIS_DECODE_CHUNK_TOKENS;
 #define HETIS_STREAM_WAVES 4
 #endif
 constexpr int kVecWaves = HETIS_STREAM_WAVES;
+constexpr int kWgsPerCu = 1;    // persistent workgroups per compute unit
 // Largest batch whose length scan fits the persistent kernel's LDS table.
 constexpr int kMaxPersistBatch = 4096;
 constexpr int kMaxPersistHeads = 1024;
@@ -151,14 +152,16 @@ static int launch_persistent(AttnParams p, int batch, hipStream_t st)
     if (occ < 1) return HETIS_ERR_LAUNCH;
     const int cus = device_cu_count();
     if (cus <= 0) return HETIS_ERR_LAUNCH;
-    // HETIS_ATTN_WGS_PER_CU (optional, read once): cap on resident workgroups per compute unit.
-    // It changes how items are spread over workgroups, never the arithmetic of an item.
-    static const int env_cap = [] {
+    // One workgroup (NW streaming waves) per compute unit already keeps enough bytes in
+    // flight to saturate HBM; more only lengthens the tail.  HETIS_ATTN_WGS_PER_CU (optional,
+    // read once) overrides this, up to what fits.  It changes how items are spread over
+    // workgroups, never the arithmetic of an item.
+    static const int env_wgs = [] {
         const char *e = std::getenv("HETIS_ATTN_WGS_PER_CU");
         const int v = e ? std::atoi(e) : 0;
-        return v > 0 ? v : 0;
+        return v > 0 ? v : kWgsPerCu;
     }();
-    if (env_cap > 0 && occ > env_cap) occ = env_cap;
+    if (occ > env_wgs) occ = env_wgs;
     const int rc = tickets_for(&p.tickets);
     if (rc != HETIS_OK) return rc;
     const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
