@@ -153,10 +153,12 @@ def main():
     kern_ms = np.array([a.elapsed_time(b) for a, b in ev_kernel])
 
     if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        # a plain elementwise kernel of known traffic (1 GiB read, 1 GiB written) for scaling
+        # the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
 
     kv_bytes = w.kv_bytes()

@@ -242,3 +242,64 @@ def test_c4_long_split_512_and_decode():
     o_s, lse_s = d.split(sub_ids, spec.chunk_tokens, spec.max_seq_len)
     out_s = d.merge(o_s, lse_s, sub_ids, spec.chunk_tokens, spec.max_seq_len)
     assert np.array_equal(bits(out_s)[:, sub_ids], bits(out)[:, sub_ids])
+
+
+# ------------------------------------------------------------------ other entry points and paths
+def test_validate_reports_bad_content():
+    w = W.make_custom([20, 45], 4, 4, 64, [0, 1], seed=41, max_seq_len=64)
+    d = Dev(w)
+    hid, n = d.heads([0, 1])
+    assert H.hetis_attn_validate(d.shape, d.bt, d.sl, hid, n, w.num_blocks) == 0
+    bad_hid = torch.tensor([0, 4], dtype=torch.int32, device="cuda:0")          # head 4 of 4
+    assert H.hetis_attn_validate(d.shape, d.bt, d.sl, bad_hid, 2, w.num_blocks) == H.binding.HETIS_ERR_BAD_CONTENT
+    bad_len = torch.tensor([20, 65], dtype=torch.int32, device="cuda:0")        # beyond the table
+    assert H.hetis_attn_validate(d.shape, d.bt, bad_len, hid, n, w.num_blocks) == H.binding.HETIS_ERR_BAD_CONTENT
+    assert H.hetis_attn_validate(d.shape, d.bt, d.sl, hid, n, 2) == H.binding.HETIS_ERR_BAD_CONTENT  # block id >= 2
+
+
+def test_profile_events_bracket_the_chunk_kernel():
+    w = W.make_custom([300, 700, 64], 4, 4, 128, [0, 1, 2, 3], seed=42, max_seq_len=1024)
+    d = Dev(w)
+    ref = d.decode([0, 1, 2, 3])
+    st = torch.cuda.current_stream()
+    ev = []
+    for _ in range(2):
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(st)
+        ev.append(e)
+    torch.cuda.synchronize()
+    assert H.hetis_attn_profile_events(ev[0].cuda_event, None) == H.binding.HETIS_ERR_NULL
+    assert H.hetis_attn_profile_events(ev[0].cuda_event, ev[1].cuda_event) == 0
+    out = d.decode([0, 1, 2, 3])
+    assert H.hetis_attn_profile_events(None, None) == 0
+    assert 0.0 < ev[0].elapsed_time(ev[1]) < 50.0          # milliseconds
+    assert np.array_equal(bits(out), bits(ref))
+
+
+def test_batch_beyond_the_persistent_kernel_limit():
+    # more than 4096 sequences: the simple one-workgroup-per-chunk-slot kernel takes over
+    rng = np.random.default_rng(43)
+    lens = rng.integers(0, 300, size=4100).tolist()
+    w = W.make_custom(lens, 2, 2, 64, [1], seed=43, max_seq_len=304)
+    d = Dev(w)
+    out = d.decode([1])
+    idx = np.array([0, 1, 7, 2048, 4095, 4096, 4099])
+    ref = oracle_of(w, [1], idx)
+    got = as_f64(out)[idx][:, [1]]
+    assert np.abs(got - ref[:, [1]]).max() <= TOL
+    full = d.decode([0, 1])
+    assert np.array_equal(bits(full)[:, 1], bits(out)[:, 1])
+
+
+def test_many_short_sequences_and_repeat_calls():
+    # thousands of tiny items exercise the ticket pool; repeated calls must leave its counters
+    # ready (identical bits every time)
+    rng = np.random.default_rng(44)
+    lens = rng.integers(1, 40, size=1500).tolist()
+    w = W.make_custom(lens, 4, 4, 128, [0, 2, 3], seed=44, max_seq_len=48)
+    d = Dev(w)
+    first = d.decode([0, 2, 3])
+    ref = oracle_of(w, [0, 2, 3])
+    check_against_oracle(first, ref, w.spec, [0, 2, 3])
+    for _ in range(5):
+        assert np.array_equal(bits(d.decode([0, 2, 3])), bits(first))
