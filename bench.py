@@ -106,9 +106,9 @@ def main():
 
     if spec.chunk_tokens:
         C = H.hetis_attn_split_num_chunks(spec.max_seq_len, spec.chunk_tokens)
-        rows = n_sel * spec.group_size
-        o_p = torch.empty((spec.batch, rows, C, spec.head_dim), dtype=torch.float32, device=dev)
-        lse_p = torch.empty((spec.batch, rows, C), dtype=torch.float32, device=dev)
+        r = spec.group_size
+        o_p = torch.empty((spec.batch, n_sel, C, r, spec.head_dim), dtype=torch.float32, device=dev)
+        lse_p = torch.empty((spec.batch, n_sel, C, r), dtype=torch.float32, device=dev)
 
         def step():
             H.check(H.hetis_attn_decode_split(shape, w.q, w.k_cache, w.v_cache, bt, sl, hid, n_sel,

@@ -136,10 +136,11 @@ int hetis_attn_split_workspace_bytes(const hetis_attn_shape *shape, int32_t n_se
                                      size_t *o_partial_bytes, size_t *lse_partial_bytes);
 
 /*
- * Partial pass.  With row j = i*r + (h - head_ids[i]*r) for the i-th selected
- * KV head, and per chunk m_c = max_t s_t, Z_c = sum_t exp(s_t - m_c):
- *   o_partial   fp32 [B, n_sel_heads*r, C_max, D]  = sum_t exp(s_t - m_c) V_t / Z_c
- *   lse_partial fp32 [B, n_sel_heads*r, C_max]     = m_c + ln Z_c   (natural log)
+ * Partial pass.  For the i-th selected KV head, chunk c and query head j = 0..r-1 of the
+ * group (h = head_ids[i]*r + j), with m_c = max_t s_t, Z_c = sum_t exp(s_t - m_c):
+ *   o_partial   fp32 [B, n_sel_heads, C_max, r, D]  = sum_t exp(s_t - m_c) V_t / Z_c
+ *   lse_partial fp32 [B, n_sel_heads, C_max, r]     = m_c + ln Z_c   (natural log)
+ * (the r rows of one chunk are adjacent, so a chunk's result is one contiguous run).
  * Entries of chunks c >= ceil(L_b / chunk_tokens) are not written.
  * max_seq_len (host) bounds every seq_lens[b]; it fixes C_max and the grid.
  * Errors: as hetis_attn_decode, plus WORKSPACE when max_seq_len is not in

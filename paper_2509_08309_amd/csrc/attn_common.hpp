@@ -20,8 +20,8 @@ struct AttnParams {
     const int32_t *seq_lens;    // [B]
     const int32_t *head_ids;    // [n_sel]
     __half *out;                // [B, Hq, D]
-    float *o_partial;           // [B, n_sel*r, max_chunks, D]
-    float *lse_partial;         // [B, n_sel*r, max_chunks]
+    float *o_partial;           // [B, n_sel, max_chunks, r, D]
+    float *lse_partial;         // [B, n_sel, max_chunks, r]
     int64_t stride_block;       // elements
     int64_t stride_head;        // elements
     int32_t n_q_heads;

@@ -76,15 +76,15 @@ __device__ __forceinline__ void flush_mailbox(const Mailbox<D, R> &mb, const Att
     const int si = __builtin_amdgcn_readfirstlane(mb.si);
     const int c = __builtin_amdgcn_readfirstlane(mb.c);
     const int kind = __builtin_amdgcn_readfirstlane(mb.kind);
-    const int rows = p.n_sel * R;
+    // the r rows of one (sequence, head, chunk) are contiguous in the partial buffers, so an
+    // item leaves as one run of r*D floats plus one run of r floats
+    const int64_t item = ((int64_t)b * p.n_sel + si) * p.max_chunks + c;
 #pragma unroll
     for (int idx = lane * 4; idx < R * D; idx += 256) {
         const int r = idx / D, d = idx % D;
         float4 v = *reinterpret_cast<const float4 *>(&mb.o[r][d]);
         if (kind == kKindPartial) {
-            const int64_t row = ((int64_t)b * rows + si * R + r) * p.max_chunks + c;
-            *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
-            if (d == 0) p.lse_partial[row] = mb.lse[r];
+            *reinterpret_cast<float4 *>(p.o_partial + item * (R * D) + idx) = v;
         } else {
             if (kind == kKindZero) v = make_float4(0.f, 0.f, 0.f, 0.f);
             union {
@@ -96,6 +96,7 @@ __device__ __forceinline__ void flush_mailbox(const Mailbox<D, R> &mb, const Att
             *reinterpret_cast<uint2 *>(p.out + ((int64_t)b * p.n_q_heads + g * R + r) * D + d) = pk.u;
         }
     }
+    if (kind == kKindPartial && lane < R) p.lse_partial[item * R + lane] = mb.lse[lane];
 }
 
 struct ItemHdr {

@@ -189,7 +189,6 @@ template <int D, int R>
 __device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const AttnParams &p,
                                              int lane, int b, int g, int si, int c, bool to_out)
 {
-    const int rows = p.n_sel * R;
     for (int idx = lane * 4; idx < R * D; idx += 256) {
         const int r = idx / D, d = idx % D;
         const float4 v = *reinterpret_cast<const float4 *>(&res.o[r][d]);
@@ -202,7 +201,7 @@ __device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const A
             pk.h[1] = __floats2half2_rn(v.z, v.w);
             *reinterpret_cast<uint2 *>(p.out + ((int64_t)b * p.n_q_heads + g * R + r) * D + d) = pk.u;
         } else {
-            const int64_t row = ((int64_t)b * rows + si * R + r) * p.max_chunks + c;
+            const int64_t row = (((int64_t)b * p.n_sel + si) * p.max_chunks + c) * R + r;
             *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
             if (d == 0) p.lse_partial[row] = res.lse[r];
         }
@@ -397,18 +396,18 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(const AttnParams p, int g
         o[d] = __float2half_rn(0.f);
         return;
     }
-    const int rows = p.n_sel * group;
-    const int64_t base = ((int64_t)b * rows + j) * p.max_chunks;
+    // partial of chunk c of this row: index ((b*n_sel + i)*max_chunks + c)*group + rr
+    const int64_t base = ((int64_t)b * p.n_sel + j / group) * p.max_chunks * group + j % group;
     const float *lse = p.lse_partial + base;
     const float *op = p.o_partial + base * D + d;
     float M = lse[0];
-    for (int c = 1; c < n_chunks; ++c) M = fmaxf(M, lse[c]);
+    for (int c = 1; c < n_chunks; ++c) M = fmaxf(M, lse[(int64_t)c * group]);
     float W = 0.f, acc = 0.f;
 #pragma unroll 4
     for (int c = 0; c < n_chunks; ++c) {
-        const float w = fast_exp2((lse[c] - M) * kLog2e);
+        const float w = fast_exp2((lse[(int64_t)c * group] - M) * kLog2e);
         W += w;
-        acc = fmaf(w, op[(int64_t)c * D], acc);
+        acc = fmaf(w, op[(int64_t)c * group * D], acc);
     }
     o[d] = __float2half_rn(acc / W);
 }

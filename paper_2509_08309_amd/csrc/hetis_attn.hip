@@ -12,13 +12,20 @@
 
 namespace hetis {
 
-// Tokens per chunk of hetis_attn_decode.  A compile-time constant: the chunking of a
-// sequence must depend on its length only, or a head-subset call could not reproduce
-// the all-heads call bit for bit.
+// Tokens per chunk of hetis_attn_decode.  Compile-time constants chosen by the query-group
+// size only: the chunking of a sequence must depend on its length and the model shape alone,
+// or a head-subset call could not reproduce the all-heads call bit for bit.  Grouped-query
+// shapes write r rows of partials per chunk, so they take longer chunks.
 #ifndef HETIS_DECODE_CHUNK_TOKENS
 #define HETIS_DECODE_CHUNK_TOKENS 256
 #endif
-constexpr int kDecodeChunkTokens = HETIS_DECODE_CHUNK_TOKENS;
+#ifndef HETIS_DECODE_CHUNK_TOKENS_GQA
+#define HETIS_DECODE_CHUNK_TOKENS_GQA 512
+#endif
+constexpr int decode_chunk_tokens(int group)
+{
+    return group >= 4 ? HETIS_DECODE_CHUNK_TOKENS_GQA : HETIS_DECODE_CHUNK_TOKENS;
+}
 #ifndef HETIS_STREAM_WAVES
 #define HETIS_STREAM_WAVES 4
 #endif
@@ -316,9 +323,10 @@ int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *
 
     AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
                                n_sel_heads, scale, out);
-    p.chunk_tokens = kDecodeChunkTokens;
+    const int chunk = decode_chunk_tokens(c.group);
+    p.chunk_tokens = chunk;
     const int64_t max_tokens = (int64_t)shape->max_blocks_per_seq * kBlockTokens;
-    p.max_chunks = (int)((max_tokens + kDecodeChunkTokens - 1) / kDecodeChunkTokens);
+    p.max_chunks = (int)((max_tokens + chunk - 1) / chunk);
     p.direct_single = 1;
     hipStream_t st = (hipStream_t)stream;
     if (p.max_chunks > 1) {

@@ -59,9 +59,9 @@ class Dev:
         assert C > 0
         rc, ob, lb = H.hetis_attn_split_workspace_bytes(self.shape, n, max_seq_len, chunk_tokens)
         H.check(rc, "workspace_bytes")
-        rows = n * s.group_size
-        o_p = torch.full((s.batch, rows, C, s.head_dim), fill, dtype=torch.float32, device="cuda:0")
-        lse_p = torch.full((s.batch, rows, C), fill, dtype=torch.float32, device="cuda:0")
+        r = s.group_size
+        o_p = torch.full((s.batch, n, C, r, s.head_dim), fill, dtype=torch.float32, device="cuda:0")
+        lse_p = torch.full((s.batch, n, C, r), fill, dtype=torch.float32, device="cuda:0")
         assert o_p.numel() * 4 == ob and lse_p.numel() * 4 == lb
         H.check(H.hetis_attn_decode_split(self.shape, self.q, self.k, self.v, self.bt, self.sl,
                                           hid, n, self.scale, chunk_tokens, max_seq_len, o_p,
@@ -76,6 +76,23 @@ class Dev:
                                    max_seq_len, out), "hetis_attn_merge")
         torch.cuda.synchronize()
         return out
+
+
+def partials_as_rows(o_p: torch.Tensor, lse_p: torch.Tensor):
+    """Library layout [B, S, C, r, D] / [B, S, C, r] -> row-major [B, S*r, C, D] / [B, S*r, C] (fp64)."""
+    B, S, C, r, D = o_p.shape
+    o = as_f64(o_p).transpose(0, 1, 3, 2, 4).reshape(B, S * r, C, D)
+    lse = as_f64(lse_p).transpose(0, 1, 3, 2).reshape(B, S * r, C)
+    return o, lse
+
+
+def rows_as_partials(o_rows, lse_rows, r):
+    """Inverse of partials_as_rows for numpy arrays; returns float32 arrays in library layout."""
+    B, SR, C, D = o_rows.shape
+    S = SR // r
+    o = o_rows.reshape(B, S, r, C, D).transpose(0, 1, 3, 2, 4)
+    lse = lse_rows.reshape(B, S, r, C).transpose(0, 1, 3, 2)
+    return np.ascontiguousarray(o, dtype=np.float32), np.ascontiguousarray(lse, dtype=np.float32)
 
 
 def bits(t: torch.Tensor) -> np.ndarray:

@@ -11,7 +11,8 @@ import oracle
 import paper_2509_08309_amd as H
 from paper_2509_08309_amd import workloads as W
 
-from gpu_harness import (SENTINEL, TOL, Dev, as_f64, bits, selected_rows, unselected_rows)
+from gpu_harness import (SENTINEL, TOL, Dev, as_f64, bits, partials_as_rows, rows_as_partials,
+                         selected_rows, unselected_rows)
 
 pytestmark = pytest.mark.gpu
 
@@ -145,7 +146,7 @@ def test_split_partials_and_merge(chunk, Hq, Hkv, D):
     o_p, lse_p = d.split(hid, chunk, msl)
     ro, rl = oracle.attn_partial(w.q.numpy(), w.k_cache.numpy(), w.v_cache.numpy(), w.block_table,
                                  w.seq_lens, hid, w.spec.scale, chunk, C)
-    go, gl = as_f64(o_p), as_f64(lse_p)
+    go, gl = partials_as_rows(o_p, lse_p)
     assert np.array_equal(np.isnan(gl), np.isnan(rl)), "written chunk set differs"
     assert np.array_equal(np.isnan(go), np.isnan(ro))
     m = ~np.isnan(rl)
@@ -172,8 +173,9 @@ def test_merge_kernel_alone_on_checker_partials():
                                  w.seq_lens, hid, w.spec.scale, chunk, C, fill=np.nan)
     ref = oracle.attn_merge(ro, rl, w.seq_lens, hid, 4, 2, chunk)
     d = Dev(w)
-    o_p = torch.from_numpy(ro.astype(np.float32)).cuda()
-    lse_p = torch.from_numpy(rl.astype(np.float32)).cuda()
+    o_np, lse_np = rows_as_partials(ro, rl, 2)
+    o_p = torch.from_numpy(o_np).cuda()
+    lse_p = torch.from_numpy(lse_np).cuda()
     out = d.merge(o_p, lse_p, hid, chunk, msl)
     check_against_oracle(out, ref, w.spec, hid)
     assert (bits(out)[0] == 0).all()
