@@ -2,11 +2,13 @@
 // independent of how a tile is turned into scores and sums (that is the Policy: vector ALU
 // arithmetic for small query groups, MFMA for grouped-query attention).
 //
-// Work enumeration: every workgroup scans the sequence lengths into two tables of running
-// counts (LDS): whole chunks per sequence and ragged last chunks per sequence.  A flat item
-// number then decodes into (sequence, chunk, selected head) by binary search, whole chunks
-// first and ragged ones last, without launching a workgroup per possible chunk.  An item is
-// one chunk of one (sequence, selected head) and is processed by ONE wave.
+// Work enumeration: every workgroup scans the sequence lengths into tables of running counts
+// (LDS): whole chunks per sequence, and ragged last chunks per sequence in four classes by
+// size.  A flat item number then decodes into (sequence, chunk, selected head) by binary
+// search, whole chunks first, then the ragged ones from the longest class to the shortest,
+// without launching a workgroup per possible chunk; the items handed out last are the
+// shortest, which keeps the tail of the launch short.  An item is one chunk of one
+// (sequence, selected head) and is processed by ONE wave.
 // Work distribution: the first two items of a streaming wave are fixed by its number; the
 // rest come from a global ticket counter, so that waves which drew short chunks simply take
 // more of them.  Tickets are drawn by the workgroup's writer wave, eight per device atomic
@@ -34,7 +36,7 @@
 // data and header -> FULL -> the writer copies it out -> EMPTY.  A producer that has no more
 // items marks its next mailbox DONE; the writer leaves when all NW are DONE.  All waits are
 // polling loops with an iteration bound, so every wave reaches its end whatever happens.
-// Dynamic LDS: int lens[batch], int firstF[batch + 1], int firstT[batch + 1], int
+// Dynamic LDS: int lens[batch], int firstF[batch + 1], int firstT[4][batch + 1], int
 // hids[n_sel]; NW x 2 mailboxes; NW per-wave staging areas of Policy::kWaveLdsBytes.
 // Nothing depends on how many heads were selected or on the grid size: the result for one
 // (sequence, head) is a function of that sequence's length alone.
@@ -113,7 +115,7 @@ __host__ __device__ constexpr size_t align16(size_t x) { return (x + 15) & ~(siz
 template <class Policy, int NW>
 __host__ __device__ constexpr size_t persist_lds_bytes(int batch, int n_sel)
 {
-    return align16((size_t)(3 * batch + 2 + n_sel) * sizeof(int)) +
+    return align16((size_t)(6 * batch + 5 + n_sel) * sizeof(int)) +
            2 * NW * sizeof(Mailbox<Policy::D, Policy::R>) + (size_t)NW * Policy::kWaveLdsBytes;
 }
 
@@ -140,9 +142,11 @@ __global__ __launch_bounds__((NW + 1) * 64)
     extern __shared__ __align__(16) unsigned char smem[];
     int *lens = reinterpret_cast<int *>(smem);
     int *firstF = lens + batch;               // whole chunks before sequence b
-    int *firstT = firstF + batch + 1;         // ragged last chunks (and zero items) before b
-    int *hids = firstT + batch + 1;
-    unsigned char *after_tables = smem + align16((size_t)(3 * batch + 2 + p.n_sel) * sizeof(int));
+    int *firstT = firstF + batch + 1;         // [4][batch + 1]: ragged last chunks of size class
+                                              // k before sequence b (class 3 also holds the
+                                              // items that write zeros)
+    int *hids = firstT + 4 * (batch + 1);
+    unsigned char *after_tables = smem + align16((size_t)(6 * batch + 5 + p.n_sel) * sizeof(int));
     __shared__ TicketPool pool;
     Mail *mail = reinterpret_cast<Mail *>(after_tables);             // [NW][2]
     unsigned char *staging = after_tables + 2 * NW * sizeof(Mail);
@@ -159,40 +163,66 @@ __global__ __launch_bounds__((NW + 1) * 64)
         pool.next = 0;
         pool.end = 0;
     }
+    // size class of a ragged last chunk of `rt` tokens: 0 = longest quarter ... 3 = shortest
+    auto ragged_class = [&](int rt) { return 3 - min(3, (4 * rt - 1) / p.chunk_tokens); };
     if (wave == 0) {
-        int carryF = 0, carryT = 0;
+        // counts of classes 0,1 and 2,3 travel packed in 16-bit halves (batch < 65536)
+        int carryF = 0, carry01 = 0, carry23 = 0;
         for (int b0 = 0; b0 < batch; b0 += 64) {
             const int b = b0 + lane;
             const int L = b < batch ? p.seq_lens[b] : 0;
             const int nF = L > 0 ? L / p.chunk_tokens : 0;
-            int nT = (L > 0 && L % p.chunk_tokens != 0) ? 1 : 0;
-            if (L <= 0 && b < batch && p.direct_single) nT = 1;       // the item that writes the zeros
-            int inclF = nF, inclT = nT;
+            const int rt = L > 0 ? L % p.chunk_tokens : 0;
+            int cls = -1;
+            if (rt > 0) cls = ragged_class(rt);
+            if (L <= 0 && b < batch && p.direct_single) cls = 3;      // the item that writes the zeros
+            const int n01 = cls == 0 ? 1 : (cls == 1 ? 1 << 16 : 0);
+            const int n23 = cls == 2 ? 1 : (cls == 3 ? 1 << 16 : 0);
+            int inclF = nF, incl01 = n01, incl23 = n23;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const int upF = __shfl_up(inclF, off, 64);
-                const int upT = __shfl_up(inclT, off, 64);
+                const int up01 = __shfl_up(incl01, off, 64);
+                const int up23 = __shfl_up(incl23, off, 64);
                 if (lane >= off) {
                     inclF += upF;
-                    inclT += upT;
+                    incl01 += up01;
+                    incl23 += up23;
                 }
             }
             if (b < batch) {
                 lens[b] = L;
                 firstF[b] = carryF + inclF - nF;
-                firstT[b] = carryT + inclT - nT;
+                const int e01 = carry01 + incl01 - n01, e23 = carry23 + incl23 - n23;
+                firstT[0 * (batch + 1) + b] = e01 & 0xffff;
+                firstT[1 * (batch + 1) + b] = e01 >> 16;
+                firstT[2 * (batch + 1) + b] = e23 & 0xffff;
+                firstT[3 * (batch + 1) + b] = e23 >> 16;
             }
             carryF += __shfl(inclF, 63, 64);
-            carryT += __shfl(inclT, 63, 64);
+            carry01 += __shfl(incl01, 63, 64);
+            carry23 += __shfl(incl23, 63, 64);
         }
         if (lane == 0) {
             firstF[batch] = carryF;
-            firstT[batch] = carryT;
+            firstT[0 * (batch + 1) + batch] = carry01 & 0xffff;
+            firstT[1 * (batch + 1) + batch] = carry01 >> 16;
+            firstT[2 * (batch + 1) + batch] = carry23 & 0xffff;
+            firstT[3 * (batch + 1) + batch] = carry23 >> 16;
         }
     }
     __syncthreads();
     const int totalF = firstF[batch];                         // whole chunks of all sequences
-    const int total = (totalF + firstT[batch]) * p.n_sel;
+    int class_end[4];                                         // running ends of the ragged classes
+    {
+        int run = totalF;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            run += firstT[k * (batch + 1) + batch];
+            class_end[k] = run;
+        }
+    }
+    const int total = class_end[3] * p.n_sel;
     const int stride = gridDim.x * NW;                        // streaming waves in the grid
 
     if (wave == NW) {
@@ -270,7 +300,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // item number -> (sequence, chunk, head): whole chunks come first, ragged last chunks
     // after them; binary search in the matching running-count table.  Item numbers of a wave
     // only grow, so the last answer of each table is the lower end of the next search.
-    int cursorF = 0, cursorT = 0;
+    int cursorF = 0, cursorT[4] = {0, 0, 0, 0};
     auto upper = [&](const int *tab, int key, int lo) {       // last b with tab[b] <= key
         int hi = batch - 1;
         while (lo < hi) {
@@ -294,8 +324,20 @@ __global__ __launch_bounds__((NW + 1) * 64)
             L = __builtin_amdgcn_readfirstlane(lens[h.b]);
             n_tok = p.chunk_tokens;
         } else {
-            cursorT = upper(firstT, cg - totalF, cursorT);
-            h.b = cursorT;
+            int k = 0, begin = totalF;
+#pragma unroll
+            for (int j = 0; j < 3; ++j)
+                if (cg >= class_end[j]) {
+                    k = j + 1;
+                    begin = class_end[j];
+                }
+            // the four cursors live in registers: pick and update with selects, not indexing
+            int cur = k == 0 ? cursorT[0] : (k == 1 ? cursorT[1] : (k == 2 ? cursorT[2] : cursorT[3]));
+            cur = upper(firstT + k * (batch + 1), cg - begin, cur);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (j == k) cursorT[j] = cur;
+            h.b = cur;
             L = __builtin_amdgcn_readfirstlane(lens[h.b]);
             h.c = L > 0 ? L / p.chunk_tokens : 0;
             n_tok = L > 0 ? L - h.c * p.chunk_tokens : 0;

@@ -32,7 +32,7 @@ constexpr int decode_chunk_tokens(int group)
 constexpr int kVecWaves = HETIS_STREAM_WAVES;
 constexpr int kWgsPerCu = 1;    // persistent workgroups per compute unit
 // Largest batch whose length scan fits the persistent kernel's LDS table.
-constexpr int kMaxPersistBatch = 4096;
+constexpr int kMaxPersistBatch = 2048;
 constexpr int kMaxPersistHeads = 1024;
 // A wave keeps the block ids of one chunk in one register (64 lanes).
 constexpr int kMaxChunkTokens = 64 * kBlockTokens;
