@@ -1,7 +1,8 @@
 """Python face of the CPU checker (TEST INFRASTRUCTURE ONLY).
 
-Thin ctypes wrappers around oracle/hetis_oracle.c: numpy arrays in, fp64 numpy
-arrays out.  Only tests, the smoke check and the benchmark's cpu_baseline leg
+Thin ctypes wrappers around oracle/hetis_oracle.c (Attention: numpy arrays in,
+fp64 numpy arrays out) and oracle/hetis_kv_oracle.c (cache store / fetch / tile
+copy: 16-bit arrays in and out).  Only tests, the smoke check and the benchmark's cpu_baseline leg
 may import this package; the GPU library never does, and nothing here imports
 the GPU package.
 """
@@ -30,7 +31,8 @@ def lib():
         _lib.oracle_half_to_double.restype = C.c_double
         _lib.oracle_half_to_double.argtypes = [C.c_uint16]
         for name in ("oracle_attn_decode", "oracle_attn_partial", "oracle_attn_merge",
-                     "oracle_max_threads"):
+                     "oracle_max_threads", "oracle_kv_store", "oracle_kv_append",
+                     "oracle_kv_fetch", "oracle_kv_copy_tiles"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -114,3 +116,97 @@ def attn_merge(o_partial, lse_partial, seq_lens, head_ids, n_q_heads, n_kv_heads
     if rc != 0:
         raise RuntimeError(f"oracle_attn_merge failed: {rc}")
     return out
+
+
+# ---------------------------------------------------------------- cache management
+
+class _Pool(C.Structure):
+    _fields_ = [("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_size", C.c_int32),
+                ("num_blocks", C.c_int32),
+                ("kv_stride_block", C.c_int64), ("kv_stride_head", C.c_int64)]
+
+
+def _cache_geometry(cache, strides):
+    """(num_blocks, Hkv, block_size, D, stride_block, stride_head) of a [nb, Hkv, bs, D] pool,
+    or of a flat buffer described by strides = (nb, Hkv, bs, D, stride_block, stride_head)."""
+    if strides is not None:
+        return tuple(int(x) for x in strides)
+    nb, Hkv, bs, D = cache.shape
+    return nb, Hkv, bs, D, Hkv * bs * D, bs * D
+
+
+def _opt_i32(a):
+    return None if a is None else _i32(a)
+
+
+def _opt_ptr(a):
+    return None if a is None else _ptr(a)
+
+
+def kv_store(k_cache, v_cache, k_new, v_new, token_seq, token_pos, block_table, head_ids,
+             strides=None):
+    """Copies of the two caches with rows k_new[n, g], v_new[n, g] stored at
+    (token_seq[n], token_pos[n], g) for g in head_ids.  token_seq=None: entry n is sequence n."""
+    k, v = _u16(k_cache).copy(), _u16(v_cache).copy()
+    kn, vn = _u16(k_new), _u16(v_new)
+    nb, Hkv, bs, D, sb, sh = _cache_geometry(k, strides)
+    assert kn.shape[1:] == (Hkv, D) and vn.shape == kn.shape
+    bt, hid, pos, seq = _i32(block_table), _i32(head_ids), _i32(token_pos), _opt_i32(token_seq)
+    shp = _Shape(bt.shape[0], Hkv, Hkv, D, bs, bt.shape[1], sb, sh)
+    rc = lib().oracle_kv_store(C.byref(shp), _ptr(kn), _ptr(vn), _opt_ptr(seq), _ptr(pos),
+                               C.c_int32(len(pos)), _ptr(bt), _ptr(hid), C.c_int32(len(hid)),
+                               C.c_int32(nb), _ptr(k), _ptr(v))
+    if rc != 0:
+        raise RuntimeError(f"oracle_kv_store failed: {rc}")
+    return k, v
+
+
+def kv_append(k_cache, v_cache, k_new, v_new, block_table, seq_lens, head_ids, strides=None):
+    """Copies of the two caches with the new row of every sequence stored at seq_lens[b] - 1."""
+    k, v = _u16(k_cache).copy(), _u16(v_cache).copy()
+    kn, vn = _u16(k_new), _u16(v_new)
+    nb, Hkv, bs, D, sb, sh = _cache_geometry(k, strides)
+    bt, hid, sl = _i32(block_table), _i32(head_ids), _i32(seq_lens)
+    assert kn.shape == (bt.shape[0], Hkv, D) and vn.shape == kn.shape
+    shp = _Shape(bt.shape[0], Hkv, Hkv, D, bs, bt.shape[1], sb, sh)
+    rc = lib().oracle_kv_append(C.byref(shp), _ptr(kn), _ptr(vn), _ptr(bt), _ptr(sl), _ptr(hid),
+                                C.c_int32(len(hid)), C.c_int32(nb), _ptr(k), _ptr(v))
+    if rc != 0:
+        raise RuntimeError(f"oracle_kv_append failed: {rc}")
+    return k, v
+
+
+def kv_fetch(k_cache, v_cache, token_seq, token_pos, block_table, head_ids, fill=0xFFFF,
+             strides=None):
+    """(k_out, v_out) uint16 [n_tokens, Hkv, D]; rows not fetched keep `fill`."""
+    k, v = _u16(k_cache), _u16(v_cache)
+    nb, Hkv, bs, D, sb, sh = _cache_geometry(k, strides)
+    bt, hid, pos, seq = _i32(block_table), _i32(head_ids), _i32(token_pos), _opt_i32(token_seq)
+    ko = np.full((len(pos), Hkv, D), fill, dtype=np.uint16)
+    vo = np.full((len(pos), Hkv, D), fill, dtype=np.uint16)
+    shp = _Shape(bt.shape[0], Hkv, Hkv, D, bs, bt.shape[1], sb, sh)
+    rc = lib().oracle_kv_fetch(C.byref(shp), _ptr(k), _ptr(v), _opt_ptr(seq), _ptr(pos),
+                               C.c_int32(len(pos)), _ptr(bt), _ptr(hid), C.c_int32(len(hid)),
+                               C.c_int32(nb), _ptr(ko), _ptr(vo))
+    if rc != 0:
+        raise RuntimeError(f"oracle_kv_fetch failed: {rc}")
+    return ko, vo
+
+
+def kv_copy_tiles(src_k, src_v, dst_k, dst_v, src_blocks, dst_blocks, src_heads, dst_heads,
+                  src_strides=None, dst_strides=None):
+    """Copies of the destination caches with tile (src_blocks[i], src_heads[j]) of the source
+    written to (dst_blocks[i], dst_heads[j]) for every i, j."""
+    sk, sv = _u16(src_k), _u16(src_v)
+    dk, dv = _u16(dst_k).copy(), _u16(dst_v).copy()
+    snb, sH, sbs, sD, ssb, ssh = _cache_geometry(sk, src_strides)
+    dnb, dH, dbs, dD, dsb, dsh = _cache_geometry(dk, dst_strides)
+    sp, dp = _Pool(sH, sD, sbs, snb, ssb, ssh), _Pool(dH, dD, dbs, dnb, dsb, dsh)
+    sbk, dbk, sh_, dh_ = _i32(src_blocks), _i32(dst_blocks), _i32(src_heads), _i32(dst_heads)
+    assert len(sbk) == len(dbk) and len(sh_) == len(dh_)
+    rc = lib().oracle_kv_copy_tiles(C.byref(sp), _ptr(sk), _ptr(sv), C.byref(dp), _ptr(dk),
+                                    _ptr(dv), _ptr(sbk), _ptr(dbk), C.c_int32(len(sbk)),
+                                    _ptr(sh_), _ptr(dh_), C.c_int32(len(sh_)))
+    if rc != 0:
+        raise RuntimeError(f"oracle_kv_copy_tiles failed: {rc}")
+    return dk, dv

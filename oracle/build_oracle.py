@@ -3,15 +3,16 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "hetis_oracle.c")
+SRCS = [os.path.join(HERE, "hetis_oracle.c"), os.path.join(HERE, "hetis_kv_oracle.c")]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and all(
+            os.path.getmtime(LIB) >= os.path.getmtime(src) for src in SRCS):
         return LIB
     cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-o", LIB, SRC, "-lm"]
+           "-o", LIB, *SRCS, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 
