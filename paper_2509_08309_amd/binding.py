@@ -1,4 +1,4 @@
-"""ctypes binding of libhetis_attn.so: same names as include/hetis_attn.h.
+"""ctypes binding of libhetis_attn.so: same names as include/hetis_attn.h and include/hetis_kv.h.
 
 Argument marshalling only.  Tensors are torch tensors that already live on the
 GPU (PyTorch is used for device memory and streams, nothing else); every
@@ -31,6 +31,12 @@ class hetis_attn_shape(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("block_size", C.c_int32),
                 ("max_blocks_per_seq", C.c_int32),
+                ("kv_stride_block", C.c_int64), ("kv_stride_head", C.c_int64)]
+
+
+class hetis_kv_pool(C.Structure):
+    _fields_ = [("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_size", C.c_int32),
+                ("reserved", C.c_int32), ("num_blocks", C.c_int64),
                 ("kv_stride_block", C.c_int64), ("kv_stride_head", C.c_int64)]
 
 
@@ -81,6 +87,17 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_profile_events.argtypes = [vp, vp]
     lib.hetis_attn_validate.restype = C.c_int
     lib.hetis_attn_validate.argtypes = [shp, vp, vp, vp, i32, i64, vp]
+    pool = C.POINTER(hetis_kv_pool)
+    lib.hetis_kv_append.restype = C.c_int
+    lib.hetis_kv_append.argtypes = [shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    lib.hetis_kv_store.restype = C.c_int
+    lib.hetis_kv_store.argtypes = [shp, vp, vp, vp, vp, i32, vp, vp, i32, i64, vp, vp, vp]
+    lib.hetis_kv_fetch.restype = C.c_int
+    lib.hetis_kv_fetch.argtypes = [shp, vp, vp, vp, vp, i32, vp, vp, i32, i64, vp, vp, vp]
+    lib.hetis_kv_copy_tiles.restype = C.c_int
+    lib.hetis_kv_copy_tiles.argtypes = [pool, vp, vp, pool, vp, vp, vp, vp, i32, vp, vp, i32, vp]
+    lib.hetis_kv_profile_events.restype = C.c_int
+    lib.hetis_kv_profile_events.argtypes = [vp, vp]
     _lib = lib
     return lib
 
@@ -169,6 +186,49 @@ def hetis_attn_validate(shape, block_table, seq_lens, head_ids, n_sel_heads, num
     return load().hetis_attn_validate(C.byref(shape), _ptr(block_table), _ptr(seq_lens),
                                       _ptr(head_ids), int(n_sel_heads), int(num_blocks),
                                       _stream(stream))
+
+
+def make_pool(n_kv_heads, head_dim, num_blocks, block_size=16, kv_stride_block=0,
+              kv_stride_head=0) -> hetis_kv_pool:
+    return hetis_kv_pool(n_kv_heads, head_dim, block_size, 0, num_blocks, kv_stride_block,
+                         kv_stride_head)
+
+
+def hetis_kv_append(shape, k_new, v_new, block_table, seq_lens, head_ids, n_sel_heads,
+                    num_blocks, k_cache, v_cache, stream=None) -> int:
+    return load().hetis_kv_append(C.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(block_table),
+                                  _ptr(seq_lens), _ptr(head_ids), int(n_sel_heads),
+                                  int(num_blocks), _ptr(k_cache), _ptr(v_cache), _stream(stream))
+
+
+def hetis_kv_store(shape, k_new, v_new, token_seq, token_pos, n_tokens, block_table, head_ids,
+                   n_sel_heads, num_blocks, k_cache, v_cache, stream=None) -> int:
+    return load().hetis_kv_store(C.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(token_seq),
+                                 _ptr(token_pos), int(n_tokens), _ptr(block_table),
+                                 _ptr(head_ids), int(n_sel_heads), int(num_blocks),
+                                 _ptr(k_cache), _ptr(v_cache), _stream(stream))
+
+
+def hetis_kv_fetch(shape, k_cache, v_cache, token_seq, token_pos, n_tokens, block_table,
+                   head_ids, n_sel_heads, num_blocks, k_out, v_out, stream=None) -> int:
+    return load().hetis_kv_fetch(C.byref(shape), _ptr(k_cache), _ptr(v_cache), _ptr(token_seq),
+                                 _ptr(token_pos), int(n_tokens), _ptr(block_table),
+                                 _ptr(head_ids), int(n_sel_heads), int(num_blocks), _ptr(k_out),
+                                 _ptr(v_out), _stream(stream))
+
+
+def hetis_kv_copy_tiles(src_pool, src_k, src_v, dst_pool, dst_k, dst_v, src_blocks, dst_blocks,
+                        n_pairs, src_heads, dst_heads, n_sel_heads, stream=None) -> int:
+    return load().hetis_kv_copy_tiles(
+        None if src_pool is None else C.byref(src_pool), _ptr(src_k), _ptr(src_v),
+        None if dst_pool is None else C.byref(dst_pool), _ptr(dst_k), _ptr(dst_v),
+        _ptr(src_blocks), _ptr(dst_blocks), int(n_pairs), _ptr(src_heads), _ptr(dst_heads),
+        int(n_sel_heads), _stream(stream))
+
+
+def hetis_kv_profile_events(begin, end) -> int:
+    """begin/end: raw hipEvent_t handles (ints) or None."""
+    return load().hetis_kv_profile_events(begin, end)
 
 
 def check(status: int, where: str = "hetis_attn") -> None:

@@ -206,3 +206,43 @@ def make_custom(batch_lens: Sequence[int], n_q_heads: int, n_kv_heads: int, head
         poison_unused_slots(v_cache, seq_lens, block_table, spec.block_size)
     return Workload(spec, seq_lens, block_table, num_blocks, q, k_cache, v_cache,
                     np.asarray(spec.head_ids, dtype=np.int32))
+
+
+# ---------------------------------------------------------------- cache-management inputs
+
+def new_token_rows(w: Workload, seed: Optional[int] = None):
+    """K and V rows of the token each sequence has just produced: fp16 [B, Hkv, D] each, on the
+    device of the workload."""
+    s = w.spec
+    gen = torch.Generator(device=w.q.device)
+    gen.manual_seed((s.seed if seed is None else seed) + 7919)
+    shape = (s.batch, s.n_kv_heads, s.head_dim)
+    return _randn_fp16(shape, gen, w.q.device), _randn_fp16(shape, gen, w.q.device)
+
+
+def token_entries(w: Workload, seed: int, n: Optional[int] = None):
+    """(token_seq, token_pos) int32 arrays naming cached tokens of the workload: all of them in
+    a seeded random order, or a seeded sample of n distinct ones."""
+    lens = w.seq_lens.astype(np.int64)
+    seq = np.repeat(np.arange(len(lens), dtype=np.int32), lens)
+    pos = (np.arange(int(lens.sum()), dtype=np.int64) - np.repeat(np.cumsum(lens) - lens, lens))
+    order = np.random.default_rng(seed).permutation(len(seq))
+    if n is not None:
+        order = order[:n]
+    return seq[order], pos[order].astype(np.int32)
+
+
+def migration_plan(w: Workload, seed: int, extra_blocks: int = 5):
+    """A move of every used block of the workload into another pool: (src_blocks, dst_blocks,
+    dst_num_blocks, dst_block_table).  Destination blocks are a seeded random choice among
+    dst_num_blocks = used + extra_blocks."""
+    used_mask = np.zeros_like(w.block_table, dtype=bool)
+    nblk = (w.seq_lens.astype(np.int64) + w.spec.block_size - 1) // w.spec.block_size
+    for b, n in enumerate(nblk):
+        used_mask[b, :n] = True
+    src = w.block_table[used_mask].astype(np.int32)
+    dst_num = len(src) + extra_blocks
+    dst = np.random.default_rng(seed).permutation(dst_num)[:len(src)].astype(np.int32)
+    table = np.full_like(w.block_table, -1)
+    table[used_mask] = dst
+    return src, dst, dst_num, table

@@ -22,13 +22,13 @@ def declared_functions():
         if fn.endswith(".h"):
             text = open(os.path.join(ROOT, "include", fn)).read()
             text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-            names += re.findall(r"\b(hetis_attn_\w+)\s*\(", text)
+            names += re.findall(r"\b(hetis_(?:attn|kv)_\w+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) >= 9
+    assert len(names) >= 14 and "hetis_kv_copy_tiles" in names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
         assert hasattr(binding, n), f"{n} has no Python binding of the same name"
@@ -148,3 +148,78 @@ def test_product_never_imports_the_checker():
                 text = open(os.path.join(root, fn)).read()
                 assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), fn
                 assert "hetis_oracle" not in text and "liboracle" not in text, fn
+
+
+# ---------------------------------------------------------------- cache management entry points
+
+def kv_append(shape, n_sel=4, num_blocks=10, **kw):
+    a = dict(kn=P, vn=P, bt=P, sl=P, hid=P, k=P, v=P)
+    a.update(kw)
+    return H.hetis_kv_append(shape, a["kn"], a["vn"], a["bt"], a["sl"], a["hid"], n_sel,
+                             num_blocks, a["k"], a["v"], 0)
+
+
+def kv_store(shape, n_sel=4, n_tokens=3, num_blocks=10, fetch=False, **kw):
+    a = dict(kn=P, vn=P, seq=P, pos=P, bt=P, hid=P, k=P, v=P)
+    a.update(kw)
+    if fetch:
+        return H.hetis_kv_fetch(shape, a["k"], a["v"], a["seq"], a["pos"], n_tokens, a["bt"],
+                                a["hid"], n_sel, num_blocks, a["kn"], a["vn"], 0)
+    return H.hetis_kv_store(shape, a["kn"], a["vn"], a["seq"], a["pos"], n_tokens, a["bt"],
+                            a["hid"], n_sel, num_blocks, a["k"], a["v"], 0)
+
+
+@pytest.mark.parametrize("arg", ["kn", "vn", "bt", "sl", "hid", "k", "v"])
+def test_kv_append_null_pointers(lib, arg):
+    assert kv_append(good(), **{arg: None}) == binding.HETIS_ERR_NULL
+
+
+@pytest.mark.parametrize("fetch", [False, True])
+@pytest.mark.parametrize("arg", ["kn", "vn", "pos", "bt", "hid", "k", "v"])
+def test_kv_store_fetch_null_pointers(lib, arg, fetch):
+    assert kv_store(good(), fetch=fetch, **{arg: None}) == binding.HETIS_ERR_NULL
+
+
+def test_kv_row_argument_errors(lib):
+    assert lib.hetis_kv_append(None, P, P, P, P, P, 4, 10, P, P, None) == binding.HETIS_ERR_NULL
+    assert kv_append(good(), n_sel=0) == binding.HETIS_ERR_BAD_HEADS
+    assert kv_append(good(), n_sel=9) == binding.HETIS_ERR_BAD_HEADS
+    assert kv_append(good(), num_blocks=0) == binding.HETIS_ERR_BAD_SHAPE
+    assert kv_append(H.make_shape(4, 8, 8, 96, 16)) == binding.HETIS_ERR_UNSUPPORTED
+    assert kv_append(H.make_shape(4, 8, 8, 64, 16, block_size=32)) == binding.HETIS_ERR_UNSUPPORTED
+    assert kv_append(H.make_shape(4, 8, 8, 64, 16, kv_stride_head=1028)) == binding.HETIS_ERR_BAD_SHAPE
+    for fetch in (False, True):
+        assert kv_store(good(), n_tokens=-1, fetch=fetch) == binding.HETIS_ERR_BAD_SHAPE
+        # implicit sequence ids need n_tokens <= batch
+        assert kv_store(good(), n_tokens=5, seq=None, fetch=fetch) == binding.HETIS_ERR_BAD_SHAPE
+        # nothing to do: returns before any HIP call
+        assert kv_store(good(), n_tokens=0, fetch=fetch) == binding.HETIS_OK
+
+
+def kv_copy(sp, dp, n_pairs=3, n_sel=2, **kw):
+    a = dict(sk=P, sv=P, dk=P, dv=P, sb=P, db=P, sh=P, dh=P)
+    a.update(kw)
+    return H.hetis_kv_copy_tiles(sp, a["sk"], a["sv"], dp, a["dk"], a["dv"], a["sb"], a["db"],
+                                 n_pairs, a["sh"], a["dh"], n_sel, 0)
+
+
+@pytest.mark.parametrize("arg", ["sk", "sv", "dk", "dv", "sb", "db", "sh", "dh"])
+def test_kv_copy_null_pointers(lib, arg):
+    sp, dp = H.make_pool(8, 64, 10), H.make_pool(2, 64, 6)
+    assert kv_copy(sp, dp, **{arg: None}) == binding.HETIS_ERR_NULL
+
+
+def test_kv_copy_argument_errors(lib):
+    sp, dp = H.make_pool(8, 64, 10), H.make_pool(2, 64, 6)
+    assert kv_copy(None, dp) == binding.HETIS_ERR_NULL
+    assert kv_copy(sp, None) == binding.HETIS_ERR_NULL
+    assert kv_copy(sp, H.make_pool(2, 128, 6)) == binding.HETIS_ERR_BAD_SHAPE
+    assert kv_copy(sp, H.make_pool(2, 64, 0)) == binding.HETIS_ERR_BAD_SHAPE
+    assert kv_copy(sp, H.make_pool(2, 80, 6)) == binding.HETIS_ERR_UNSUPPORTED
+    assert kv_copy(sp, H.make_pool(2, 64, 6, kv_stride_head=100)) == binding.HETIS_ERR_BAD_SHAPE
+    assert kv_copy(sp, dp, n_pairs=-1) == binding.HETIS_ERR_BAD_SHAPE
+    assert kv_copy(sp, dp, n_sel=0) == binding.HETIS_ERR_BAD_HEADS
+    assert kv_copy(sp, dp, n_sel=1025) == binding.HETIS_ERR_BAD_HEADS
+    assert kv_copy(sp, dp, n_pairs=0) == binding.HETIS_OK
+    assert H.hetis_kv_profile_events(P, None) == binding.HETIS_ERR_NULL
+    assert H.hetis_kv_profile_events(None, None) == binding.HETIS_OK
