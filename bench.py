@@ -1,6 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of head-subset paged decode Attention on one MI355X.
 
+Default (--op decode) is the headline measurement described below.  --op kv_append,
+kv_store and kv_copy time the cache-management kernels on the same workload shapes and
+print a line of the same form (value = bytes moved per second of step time).
+
 A step is one pass of the whole hot path (hetis_attn_decode through the C ABI:
 work enumeration, block-table gather, q.K^T, online softmax, p.V, chunk merge,
 fp16 store) over one batch of seeded synthetic input that is already resident
@@ -67,12 +71,170 @@ def cpu_baseline(w_host, budget_s: float):
     }
 
 
+def timed_steps(step, set_events, stream, steps, warmup):
+    """W untimed steps, then K timed ones between synchronisations.  Returns (wall seconds,
+    device ms per step from one event pair, per-step kernel ms from the pairs that the library
+    records around its main kernel launch)."""
+    import numpy as np
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+
+    def new_event():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(stream)                 # creates the underlying hipEvent_t
+        return e
+    ev_region = (new_event(), new_event())
+    ev_kernel = [(new_event(), new_event()) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev_region[0].record(stream)
+    for kb, ke in ev_kernel:
+        set_events(kb.cuda_event, ke.cuda_event)
+        step()
+    ev_region[1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    set_events(None, None)
+    dev_ms = ev_region[0].elapsed_time(ev_region[1]) / steps
+    return wall, dev_ms, np.array([a.elapsed_time(b) for a, b in ev_kernel])
+
+
+def bench_kv(args):
+    """Cache-management kernels on the workload's shapes: the decode-step store of the new
+    token (kv_append), a store of every cached token as after prefill (kv_store), and the move
+    of the selected heads' tiles into a compact pool (kv_copy)."""
+    import numpy as np
+    import torch
+    import paper_2509_08309_amd as H
+    from paper_2509_08309_amd import workloads as W
+
+    spec = W.SPECS[args.workload]
+    dev = torch.device("cuda:0")
+    w = W.make_workload(spec, device=dev)
+    stream = torch.cuda.current_stream()
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    bt, sl, hid = to_dev(w.block_table), to_dev(w.seq_lens), to_dev(w.head_ids)
+    n_sel, D, Hkv = len(w.head_ids), spec.head_dim, spec.n_kv_heads
+    shape = H.make_shape(spec.batch, spec.n_q_heads, Hkv, D, w.block_table.shape[1])
+    row_bytes = 2 * D * 2                                   # one K row + one V row
+    if args.op == "kv_append":
+        kn, vn = W.new_token_rows(w)
+        units, unit_name = spec.batch * n_sel, "rows"
+        moved = units * row_bytes                           # read once, written once
+        kernel = "kv_rows_kernel<D, false>"
+
+        def step():
+            H.check(H.hetis_kv_append(shape, kn, vn, bt, sl, hid, n_sel, w.num_blocks, w.k_cache,
+                                      w.v_cache, stream), "kv_append")
+
+    elif args.op == "kv_store":
+        seq, pos = W.token_entries(w, seed=spec.seed)
+        n = len(pos)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(spec.seed)
+        kn = torch.randn((n, Hkv, D), generator=gen, device=dev).half()
+        vn = torch.randn((n, Hkv, D), generator=gen, device=dev).half()
+        tseq, tpos = to_dev(seq), to_dev(pos)
+        units, unit_name = n * n_sel, "rows"
+        moved = units * row_bytes
+        kernel = "kv_rows_kernel<D, false>"
+
+        def step():
+            H.check(H.hetis_kv_store(shape, kn, vn, tseq, tpos, n, bt, hid, n_sel, w.num_blocks,
+                                     w.k_cache, w.v_cache, stream), "kv_store")
+    else:
+        src_b, dst_b, dnb, _ = W.migration_plan(w, seed=spec.seed)
+        dk = torch.empty((dnb, n_sel, 16, D), dtype=torch.float16, device=dev)
+        dv = torch.empty_like(dk)
+        spool, dpool = H.make_pool(Hkv, D, w.num_blocks), H.make_pool(n_sel, D, dnb)
+        tsb, tdb, dh = to_dev(src_b), to_dev(dst_b), to_dev(np.arange(n_sel))
+        units, unit_name = len(src_b) * n_sel, "(block, head) tile pairs"
+        moved = units * 16 * row_bytes
+        kernel = "kv_copy_tiles_kernel<D>"
+
+        def step():
+            H.check(H.hetis_kv_copy_tiles(spool, w.k_cache, w.v_cache, dpool, dk, dv, tsb, tdb,
+                                          len(src_b), hid, dh, n_sel, stream), "kv_copy_tiles")
+
+    wall, dev_ms, kern_ms = timed_steps(step, H.hetis_kv_profile_events, stream, args.steps,
+                                        args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    traffic_alg = 2 * moved                                  # every byte is read and written
+    achieved = traffic_alg / (float(kern_ms.mean()) * 1e-3) / 1e9
+    rec = {
+        "metric": f"{args.op}: HBM bytes moved per second (read + written), 1 GPU",
+        "value": traffic_alg / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8 (byte copy)", "data": "synthetic",
+        "config": {"workload": spec.name, "op": args.op, "units": units, "unit": unit_name,
+                   "selected_kv_heads": [int(x) for x in w.head_ids], "head_dim": D,
+                   "seed": spec.seed},
+        "device_us_per_step": dev_ms * 1e3,
+        "kernel_us": {"mean": float(kern_ms.mean() * 1e3), "median": float(np.median(kern_ms) * 1e3),
+                      "min": float(kern_ms.min() * 1e3)},
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": read_traffic(f"{args.op}_{spec.name}"),
+                     "algorithmic_bytes": traffic_alg},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = kv_cpu_baseline(args.op, w, spec)
+    print(json.dumps(rec))
+
+
+def kv_cpu_baseline(op, w, spec):
+    """The CPU checker's version of the same operation on the whole workload, timed."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2509_08309_amd import workloads as W
+    u16 = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+    k, v = u16(w.k_cache), u16(w.v_cache)
+    heads = w.head_ids
+    row_bytes = 2 * spec.head_dim * 2
+    if op == "kv_append":
+        kn, vn = W.new_token_rows(w)
+        kn, vn = u16(kn), u16(vn)
+        t0 = time.perf_counter()
+        oracle.kv_append(k, v, kn, vn, w.block_table, w.seq_lens, heads)
+        dt = time.perf_counter() - t0
+        moved = spec.batch * len(heads) * row_bytes
+        sample = (f"one append of {spec.batch} x {len(heads)} rows; the timed call includes the "
+                  f"checker's copy of both caches ({k.nbytes * 2 / 1e9:.2f} GB)")
+    elif op == "kv_store":
+        seq, pos = W.token_entries(w, seed=spec.seed)
+        n = min(len(pos), 20000)
+        rng = np.random.default_rng(spec.seed)
+        kn = rng.integers(0, 0x7000, size=(n, spec.n_kv_heads, spec.head_dim)).astype(np.uint16)
+        t0 = time.perf_counter()
+        oracle.kv_store(k, v, kn, kn, seq[:n], pos[:n], w.block_table, heads)
+        dt = time.perf_counter() - t0
+        moved = n * len(heads) * row_bytes
+        sample = (f"{n} of {len(pos)} entries x {len(heads)} heads; includes the checker's copy of "
+                  f"both caches ({k.nbytes * 2 / 1e9:.2f} GB)")
+    else:
+        src_b, dst_b, dnb, _ = W.migration_plan(w, seed=spec.seed)
+        d0 = np.zeros((dnb, len(heads), 16, spec.head_dim), dtype=np.uint16)
+        t0 = time.perf_counter()
+        oracle.kv_copy_tiles(k, v, d0, d0, src_b, dst_b, heads, np.arange(len(heads)))
+        dt = time.perf_counter() - t0
+        moved = len(src_b) * len(heads) * 16 * row_bytes
+        sample = (f"all {len(src_b)} blocks x {len(heads)} heads; includes the checker's copy of "
+                  f"the destination pools ({d0.nbytes * 2 / 1e9:.2f} GB)")
+    return {"value": 2 * moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": sample + f", {dt:.3f} s wall"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3_13b_subset")
+    ap.add_argument("--op", default="decode", choices=["decode", "kv_append", "kv_store", "kv_copy"])
     ap.add_argument("--cpu-seconds", type=float, default=1.5,
                     help="wall-clock budget of the CPU checker sample (x cores = CPU work)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -91,6 +253,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     H.binding.load()                       # the HIP library must be built; no fallback exists
+    if args.op != "decode":
+        return bench_kv(args)
     spec = W.SPECS[args.workload]
     dev = torch.device("cuda:0")
     w = W.make_workload(spec, device=dev)
@@ -123,34 +287,12 @@ def main():
                                         spec.scale, out, stream), "decode")
         path = "hetis_attn_decode"
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
     # Events: one pair brackets the whole timed region on the launch stream; one pair per
     # step is handed to the library, which records it around the launch of the chunk kernel
     # (the kernel that streams the KV cache) inside the call.
-    def new_event():
-        e = torch.cuda.Event(enable_timing=True)
-        e.record(stream)                 # creates the underlying hipEvent_t
-        return e
-    ev_region = (new_event(), new_event())
-    ev_kernel = [(new_event(), new_event()) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-
-    # timed region: exactly K steps, synchronised on both sides
-    t0 = time.perf_counter()
-    ev_region[0].record(stream)
-    for kb, ke in ev_kernel:
-        H.hetis_attn_profile_events(kb.cuda_event, ke.cuda_event)
-        step()
-    ev_region[1].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    H.hetis_attn_profile_events(None, None)
+    wall, dev_ms_per_step, kern_ms = timed_steps(step, H.hetis_attn_profile_events, stream,
+                                                 args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
-    dev_ms_per_step = ev_region[0].elapsed_time(ev_region[1]) / args.steps
-    kern_ms = np.array([a.elapsed_time(b) for a, b in ev_kernel])
 
     if args.calibrate_copy:
         # a plain elementwise kernel of known traffic (1 GiB read, 1 GiB written) for scaling

