@@ -31,7 +31,7 @@ def lib():
         _lib.oracle_half_to_double.restype = C.c_double
         _lib.oracle_half_to_double.argtypes = [C.c_uint16]
         for name in ("oracle_attn_decode", "oracle_attn_partial", "oracle_attn_merge",
-                     "oracle_max_threads", "oracle_kv_store", "oracle_kv_append",
+                     "oracle_attn_decode_pairs", "oracle_max_threads", "oracle_kv_store", "oracle_kv_append",
                      "oracle_kv_fetch", "oracle_kv_copy_tiles"):
             getattr(_lib, name).restype = C.c_int
     return _lib
@@ -80,6 +80,26 @@ def attn_decode(q, k_cache, v_cache, block_table, seq_lens, head_ids, scale,
                                   C.c_int32(n_threads))
     if rc != 0:
         raise RuntimeError(f"oracle_attn_decode failed: {rc}")
+    return out
+
+
+def attn_decode_pairs(q, k_tiles, v_tiles, block_table, seq_lens, pair_seq, pair_head, n_kv_heads,
+                      scale, fill=np.nan):
+    """fp64 [B, Hq, D] for a list of (sequence, KV head) pairs over a pool of single-head tiles
+    [num_tiles, 16, D] with one block-table row per pair; rows no pair names keep `fill`."""
+    q, k, v = _u16(q), _u16(k_tiles), _u16(v_tiles)
+    bt, sl = _i32(block_table), _i32(seq_lens)
+    ps, ph = _i32(pair_seq), _i32(pair_head)
+    B, Hq, D = q.shape
+    nt, bs, D2 = k.shape
+    assert D == D2 and bt.shape[0] == len(ps) == len(ph)
+    shp = _Shape(B, Hq, n_kv_heads, D, bs, bt.shape[1], bs * D, 0)
+    out = np.full(q.shape, fill, dtype=np.float64)
+    rc = lib().oracle_attn_decode_pairs(C.byref(shp), _ptr(q), _ptr(k), _ptr(v), _ptr(bt),
+                                        _ptr(sl), _ptr(ps), _ptr(ph), C.c_int32(len(ps)),
+                                        C.c_double(scale), _ptr(out))
+    if rc != 0:
+        raise RuntimeError(f"oracle_attn_decode_pairs failed: {rc}")
     return out
 
 

@@ -146,6 +146,54 @@ int oracle_attn_decode(const oracle_shape *s, const uint16_t *q, const uint16_t 
 }
 
 /*
+ * Per-request head subsets (Section 4.2: the heads h_j^i of request j on device i are chosen
+ * per request; Section 5.2.1 dispatches x_i^j heads of request j to device i).  The work is a
+ * list of (sequence, KV head) pairs; the cache is a pool of single-head tiles (Section 6:
+ * blocks split on the head dimension) and every pair has its own block-table row:
+ *   pair p = (b, g) = (pair_seq[p], pair_head[p]);
+ *   token t of the pair lives in tile block_table[p][t / block_size], row t % block_size,
+ *   at element tile * kv_stride_block + (t % block_size) * D   (kv_stride_head is not used).
+ * For every pair, the r query heads of group g of sequence b get Eq. (2b) over the L_b
+ * tokens; rows no pair names are not written.
+ */
+int oracle_attn_decode_pairs(const oracle_shape *s, const uint16_t *q, const uint16_t *k_tiles,
+                             const uint16_t *v_tiles, const int32_t *block_table,
+                             const int32_t *seq_lens, const int32_t *pair_seq,
+                             const int32_t *pair_head, int32_t n_pairs, double scale,
+                             double *out)
+{
+    int r = s->n_q_heads / s->n_kv_heads;
+    int D = s->head_dim;
+    int fail = 0;
+    oracle_shape tiles = *s;
+    tiles.kv_stride_head = 0;               /* a tile holds one head: no head term in the address */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t p = 0; p < n_pairs; ++p) {
+        int b = pair_seq[p];
+        int g = pair_head[p];
+        int L = seq_lens[b];
+        const int32_t *bt_row = block_table + p * s->max_blocks_per_seq;
+        double *score = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+        if (!score) {
+#pragma omp atomic write
+            fail = 1;
+            continue;
+        }
+        for (int h = g * r; h < g * r + r; ++h) {
+            double *o = out + ((int64_t)b * s->n_q_heads + h) * D;
+            if (L <= 0) {
+                for (int d = 0; d < D; ++d) o[d] = 0.0;
+                continue;
+            }
+            const uint16_t *qrow = q + ((int64_t)b * s->n_q_heads + h) * D;
+            attend_range(&tiles, qrow, k_tiles, v_tiles, bt_row, g, 0, L, scale, o, NULL, score);
+        }
+        free(score);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
  * Split-KV partials (an exact intra-device decomposition of Eq. (2b) along the
  * token axis; not part of the paper, which only splits on heads).  Chunk c of
  * sequence b covers tokens [c*chunk, min((c+1)*chunk, L_b)).  For every

@@ -246,3 +246,72 @@ def migration_plan(w: Workload, seed: int, extra_blocks: int = 5):
     table = np.full_like(w.block_table, -1)
     table[used_mask] = dst
     return src, dst, dst_num, table
+
+
+# ---------------------------------------------------------------- per-request head subsets
+
+@dataclass
+class PairsWorkload:
+    """A list of (sequence, KV head) pairs over a pool of single-head tiles, one block-table
+    row per pair (the form in which a device sees requests whose head subsets differ)."""
+    spec: WorkloadSpec
+    seq_lens: np.ndarray                # int32 [B]
+    pair_seq: np.ndarray                # int32 [P]
+    pair_head: np.ndarray               # int32 [P]
+    block_table: np.ndarray             # int32 [P, max_blocks_per_seq] tile ids, -1 past the end
+    num_tiles: int
+    q: torch.Tensor                     # fp16 [B, Hq, D]
+    k_tiles: torch.Tensor               # fp16 [num_tiles, 16, D]
+    v_tiles: torch.Tensor
+
+    @property
+    def n_pairs(self) -> int:
+        return len(self.pair_seq)
+
+    def kv_bytes(self) -> int:
+        lens = self.seq_lens.astype(np.int64)[self.pair_seq]
+        return int(lens.sum()) * 2 * self.spec.head_dim * 2
+
+
+def draw_head_subsets(batch: int, n_kv_heads: int, mean_heads: float, rng: np.random.Generator):
+    """Per request: a count drawn uniformly from [0, 2 * mean_heads] (clipped to the head count)
+    and that many distinct KV heads, ascending.  Returns a list of int arrays."""
+    hi = int(min(n_kv_heads, round(2 * mean_heads)))
+    counts = rng.integers(0, hi + 1, size=batch)
+    return [np.sort(rng.choice(n_kv_heads, size=int(c), replace=False)).astype(np.int32)
+            for c in counts]
+
+
+def make_pairs_workload(spec: WorkloadSpec, device="cpu", mean_heads: Optional[float] = None,
+                        subsets=None, seq_lens=None, poison: bool = True,
+                        extra_tiles: int = 3) -> PairsWorkload:
+    """Lengths as in `spec`; every request gets its own head subset (drawn around
+    mean_heads = len(spec.head_ids) unless `subsets` is given); tiles are handed out by one
+    seeded permutation of the pool, data ~ N(0,1) rounded to fp16."""
+    rng = np.random.default_rng(spec.seed)
+    lens = draw_lengths(spec, rng) if seq_lens is None else np.asarray(seq_lens, dtype=np.int32)
+    if subsets is None:
+        mh = len(spec.head_ids) if mean_heads is None else mean_heads
+        subsets = draw_head_subsets(spec.batch, spec.n_kv_heads, mh, rng)
+    pair_seq = np.concatenate([np.full(len(h), b, dtype=np.int32) for b, h in enumerate(subsets)]
+                              + [np.zeros(0, dtype=np.int32)])
+    pair_head = np.concatenate([np.asarray(h, dtype=np.int32) for h in subsets]
+                               + [np.zeros(0, dtype=np.int32)])
+    table, num_tiles = build_block_table(lens[pair_seq], spec.max_blocks_per_seq, spec.block_size,
+                                         rng, extra_blocks=extra_tiles)
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(spec.seed)
+    q = _randn_fp16((spec.batch, spec.n_q_heads, spec.head_dim), gen, dev)
+    tshape = (num_tiles, spec.block_size, spec.head_dim)
+    k_tiles = _randn_fp16(tshape, gen, dev)
+    v_tiles = _randn_fp16(tshape, gen, dev)
+    if poison:
+        for p, b in enumerate(pair_seq):
+            L = int(lens[b])
+            rem = L % spec.block_size
+            if L > 0 and rem:
+                t = int(table[p, (L - 1) // spec.block_size])
+                k_tiles[t, rem:, :] = float("nan")
+                v_tiles[t, rem:, :] = float("nan")
+    return PairsWorkload(spec, lens, pair_seq, pair_head, table, num_tiles, q, k_tiles, v_tiles)
