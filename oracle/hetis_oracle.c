@@ -173,7 +173,9 @@ int oracle_attn_decode_pairs(const oracle_shape *s, const uint16_t *q, const uin
         int g = pair_head[p];
         int L = seq_lens[b];
         const int32_t *bt_row = block_table + p * s->max_blocks_per_seq;
-        double *score = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+        /* scores, then one result row: a row is finished in private memory and copied out
+         * whole, so that a pair listed twice never exposes a half-written row */
+        double *score = (double *)malloc(sizeof(double) * (size_t)((L > 0 ? L : 1) + D));
         if (!score) {
 #pragma omp atomic write
             fail = 1;
@@ -181,12 +183,16 @@ int oracle_attn_decode_pairs(const oracle_shape *s, const uint16_t *q, const uin
         }
         for (int h = g * r; h < g * r + r; ++h) {
             double *o = out + ((int64_t)b * s->n_q_heads + h) * D;
+            double *row = score + (L > 0 ? L : 1);
             if (L <= 0) {
-                for (int d = 0; d < D; ++d) o[d] = 0.0;
-                continue;
+                for (int d = 0; d < D; ++d) row[d] = 0.0;
+            } else {
+                const uint16_t *qrow = q + ((int64_t)b * s->n_q_heads + h) * D;
+                attend_range(&tiles, qrow, k_tiles, v_tiles, bt_row, g, 0, L, scale, row, NULL,
+                             score);
             }
-            const uint16_t *qrow = q + ((int64_t)b * s->n_q_heads + h) * D;
-            attend_range(&tiles, qrow, k_tiles, v_tiles, bt_row, g, 0, L, scale, o, NULL, score);
+#pragma omp critical(oracle_pairs_row)
+            memcpy(o, row, sizeof(double) * (size_t)D);
         }
         free(score);
     }
