@@ -185,6 +185,39 @@ int hetis_attn_validate(const hetis_attn_shape *shape, const int32_t *block_tabl
                         const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
                         int64_t num_blocks, void *stream);
 
+/*
+ * Per-request head subsets (Section 4.2: the heads of request j that live on device i are
+ * chosen per request; Section 5.2.1 dispatches x_i^j heads of request j to device i).  The
+ * work is a list of (sequence, KV head) pairs, and the cache is a pool of single-head tiles
+ * (Section 6: cache blocks split on the head dimension) with one block-table row per pair:
+ *   pair_seq     int32 [n_pairs]  sequence of pair p, in [0, B)
+ *   pair_head    int32 [n_pairs]  KV head of pair p, in [0, Hkv)
+ *   block_table  int32 [n_pairs, max_blocks_per_seq]: entry j of row p is the tile that holds
+ *                tokens [16 j, 16 j + 16) of (pair_seq[p], pair_head[p])
+ *   k_tiles, v_tiles  fp16: tile t starts at element t * kv_stride_block (0 = 16 * D) and holds
+ *                16 rows of D contiguous fp16; shape->kv_stride_head must be 0
+ *   seq_lens     int32 [B]; q, out: fp16 [B, Hq, D] as in hetis_attn_decode
+ * For every pair the r query heads of its group get Eq. (2b) over the sequence's tokens; rows
+ * of `out` that no pair names are left untouched.  A (sequence, head) listed twice is computed
+ * twice (same bytes written).  n_pairs = 0 is a no-op; at most 65535 pairs per call.
+ * The arithmetic of a pair is that of hetis_attn_decode for the same sequence length: the
+ * rows agree bit for bit with an all-heads run over the same tile contents.  Uses the same
+ * library-owned workspace as hetis_attn_decode (same rules for overlapping calls).
+ * Errors: NULL, BAD_SHAPE, UNSUPPORTED, ALLOC, LAUNCH.
+ */
+int hetis_attn_decode_pairs(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
+                            const void *v_tiles, const int32_t *block_table,
+                            const int32_t *seq_lens, const int32_t *pair_seq,
+                            const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
+                            void *stream);
+
+/* Debug helper like hetis_attn_validate for the pairs form: sequence ids, head ids, lengths
+ * and every tile id a call would read (0 <= id < num_tiles). */
+int hetis_attn_validate_pairs(const hetis_attn_shape *shape, const int32_t *block_table,
+                              const int32_t *seq_lens, const int32_t *pair_seq,
+                              const int32_t *pair_head, int32_t n_pairs, int64_t num_tiles,
+                              void *stream);
+
 #ifdef __cplusplus
 }
 #endif

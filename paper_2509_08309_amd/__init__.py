@@ -8,7 +8,8 @@ its absence is an error, never a fallback.
 """
 from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
-    HetisError, check, hetis_attn_decode, hetis_attn_decode_split, hetis_attn_merge, hetis_attn_profile_events,
+    HetisError, check, hetis_attn_decode, hetis_attn_decode_pairs, hetis_attn_decode_split,
+    hetis_attn_validate_pairs, hetis_attn_merge, hetis_attn_profile_events,
     hetis_attn_release_workspace, hetis_attn_shape, hetis_attn_split_num_chunks,
     hetis_attn_split_workspace_bytes, hetis_attn_status_string, hetis_attn_validate,
     hetis_attn_version, hetis_kv_append, hetis_kv_copy_tiles, hetis_kv_fetch, hetis_kv_pool,

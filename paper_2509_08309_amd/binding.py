@@ -87,6 +87,10 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_profile_events.argtypes = [vp, vp]
     lib.hetis_attn_validate.restype = C.c_int
     lib.hetis_attn_validate.argtypes = [shp, vp, vp, vp, i32, i64, vp]
+    lib.hetis_attn_decode_pairs.restype = C.c_int
+    lib.hetis_attn_decode_pairs.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
+    lib.hetis_attn_validate_pairs.restype = C.c_int
+    lib.hetis_attn_validate_pairs.argtypes = [shp, vp, vp, vp, vp, i32, i64, vp]
     pool = C.POINTER(hetis_kv_pool)
     lib.hetis_kv_append.restype = C.c_int
     lib.hetis_kv_append.argtypes = [shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
@@ -186,6 +190,21 @@ def hetis_attn_validate(shape, block_table, seq_lens, head_ids, n_sel_heads, num
     return load().hetis_attn_validate(C.byref(shape), _ptr(block_table), _ptr(seq_lens),
                                       _ptr(head_ids), int(n_sel_heads), int(num_blocks),
                                       _stream(stream))
+
+
+def hetis_attn_decode_pairs(shape, q, k_tiles, v_tiles, block_table, seq_lens, pair_seq, pair_head,
+                            n_pairs, scale, out, stream=None) -> int:
+    return load().hetis_attn_decode_pairs(C.byref(shape), _ptr(q), _ptr(k_tiles), _ptr(v_tiles),
+                                          _ptr(block_table), _ptr(seq_lens), _ptr(pair_seq),
+                                          _ptr(pair_head), int(n_pairs), float(scale), _ptr(out),
+                                          _stream(stream))
+
+
+def hetis_attn_validate_pairs(shape, block_table, seq_lens, pair_seq, pair_head, n_pairs,
+                              num_tiles, stream=None) -> int:
+    return load().hetis_attn_validate_pairs(C.byref(shape), _ptr(block_table), _ptr(seq_lens),
+                                            _ptr(pair_seq), _ptr(pair_head), int(n_pairs),
+                                            int(num_tiles), _stream(stream))
 
 
 def make_pool(n_kv_heads, head_dim, num_blocks, block_size=16, kv_stride_block=0,

@@ -19,6 +19,11 @@ struct AttnParams {
     const int32_t *block_table; // [B, max_blocks_per_seq]
     const int32_t *seq_lens;    // [B]
     const int32_t *head_ids;    // [n_sel]
+    // Per-request head subsets: row b of the enumeration is the pair (pair_seq[b], pair_head[b])
+    // with its own block-table row b over a pool of single-head tiles; n_sel is 1 and head_ids
+    // is unused.  Both null: every sequence uses the common head_ids.
+    const int32_t *pair_seq;    // [batch] or nullptr
+    const int32_t *pair_head;   // [batch] or nullptr
     __half *out;                // [B, Hq, D]
     float *o_partial;           // [B, n_sel, max_chunks, r, D]
     float *lse_partial;         // [B, n_sel, max_chunks, r]

@@ -37,7 +37,11 @@
 // items marks its next mailbox DONE; the writer leaves when all NW are DONE.  All waits are
 // polling loops with an iteration bound, so every wave reaches its end whatever happens.
 // Dynamic LDS: int lens[batch], int firstF[batch + 1], int firstT[4][batch + 1], int
-// hids[n_sel]; NW x 2 mailboxes; NW per-wave staging areas of Policy::kWaveLdsBytes.
+// hids[n_sel] (pairs mode: hids[batch], pseq[batch]); NW x 2 mailboxes; NW per-wave staging
+// areas of Policy::kWaveLdsBytes.
+// Pairs mode (per-request head subsets, Section 4.2 / 5.2.1): the rows of the enumeration are
+// (sequence, KV head) pairs instead of sequences, each with its own block-table row over a
+// pool of single-head tiles; everything else, the arithmetic of an item included, is shared.
 // Nothing depends on how many heads were selected or on the grid size: the result for one
 // (sequence, head) is a function of that sequence's length alone.
 #pragma once
@@ -63,24 +67,21 @@ template <int D, int R>
 struct Mailbox {
     float o[R][D];      // normalised output rows
     float lse[R];       // natural-log log-sum-exp of each row (partial results only)
-    int b, g, si, c;    // sequence, KV head, position in head_ids, chunk
+    int out_row;        // first of the item's R rows in `out`: sequence * n_q_heads + KV head * R
+    int item;           // index of the item's slot in the partial buffers
     int kind;           // kKindOut / kKindPartial / kKindZero
     int flag;           // kMailEmpty / kMailFull / kMailDone
-    int pad[2];
 };
 
 // Mailbox -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
 template <int D, int R>
 __device__ __forceinline__ void flush_mailbox(const Mailbox<D, R> &mb, const AttnParams &p, int lane)
 {
-    const int b = __builtin_amdgcn_readfirstlane(mb.b);
-    const int g = __builtin_amdgcn_readfirstlane(mb.g);
-    const int si = __builtin_amdgcn_readfirstlane(mb.si);
-    const int c = __builtin_amdgcn_readfirstlane(mb.c);
+    const int64_t out_row = __builtin_amdgcn_readfirstlane(mb.out_row);
     const int kind = __builtin_amdgcn_readfirstlane(mb.kind);
     // the r rows of one (sequence, head, chunk) are contiguous in the partial buffers, so an
     // item leaves as one run of r*D floats plus one run of r floats
-    const int64_t item = ((int64_t)b * p.n_sel + si) * p.max_chunks + c;
+    const int64_t item = __builtin_amdgcn_readfirstlane(mb.item);
 #pragma unroll
     for (int idx = lane * 4; idx < R * D; idx += 256) {
         const int r = idx / D, d = idx % D;
@@ -95,14 +96,15 @@ __device__ __forceinline__ void flush_mailbox(const Mailbox<D, R> &mb, const Att
             } pk;
             pk.h[0] = __floats2half2_rn(v.x, v.y);
             pk.h[1] = __floats2half2_rn(v.z, v.w);
-            *reinterpret_cast<uint2 *>(p.out + ((int64_t)b * p.n_q_heads + g * R + r) * D + d) = pk.u;
+            *reinterpret_cast<uint2 *>(p.out + (out_row + r) * D + d) = pk.u;
         }
     }
     if (kind == kKindPartial && lane < R) p.lse_partial[item * R + lane] = mb.lse[lane];
 }
 
 struct ItemHdr {
-    int b, si, c, g;
+    int b, si, c, g;    // enumeration row (sequence, or pair), position in head_ids, chunk, KV head
+    int seq;            // sequence whose query rows and output rows the item uses
     int nblk;       // blocks of this chunk
     int rem;        // tokens in the ragged last block (0: none)
     int t0;         // first token of the chunk
@@ -112,10 +114,17 @@ struct ItemHdr {
 
 __host__ __device__ constexpr size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
-template <class Policy, int NW>
-__host__ __device__ constexpr size_t persist_lds_bytes(int batch, int n_sel)
+// Table words after the six per-row tables: the selected heads, or in pairs mode the head and
+// the sequence of every pair.
+__host__ __device__ constexpr int persist_id_words(int batch, int n_sel, bool pairs)
 {
-    return align16((size_t)(6 * batch + 5 + n_sel) * sizeof(int)) +
+    return pairs ? 2 * batch : n_sel;
+}
+
+template <class Policy, int NW>
+__host__ __device__ constexpr size_t persist_lds_bytes(int batch, int n_sel, bool pairs)
+{
+    return align16((size_t)(6 * batch + 5 + persist_id_words(batch, n_sel, pairs)) * sizeof(int)) +
            2 * NW * sizeof(Mailbox<Policy::D, Policy::R>) + (size_t)NW * Policy::kWaveLdsBytes;
 }
 
@@ -128,7 +137,7 @@ __device__ __forceinline__ void mail_store(int *flag, int v)
     __hip_atomic_store(flag, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-template <class Policy, int NW>
+template <class Policy, int NW, bool PAIRS>
 __global__ __launch_bounds__((NW + 1) * 64)
     __attribute__((amdgpu_waves_per_eu(Policy::kWavesPerEu))) void attn_chunk_persistent_kernel(
         const AttnParams p, const int batch)
@@ -145,8 +154,12 @@ __global__ __launch_bounds__((NW + 1) * 64)
     int *firstT = firstF + batch + 1;         // [4][batch + 1]: ragged last chunks of size class
                                               // k before sequence b (class 3 also holds the
                                               // items that write zeros)
-    int *hids = firstT + 4 * (batch + 1);
-    unsigned char *after_tables = smem + align16((size_t)(6 * batch + 5 + p.n_sel) * sizeof(int));
+    int *hids = firstT + 4 * (batch + 1);     // KV head of position si in head_ids / of pair b
+    int *pseq = hids + batch;                 // pairs mode: sequence of pair b
+    const int n_sel = PAIRS ? 1 : p.n_sel;    // items per (row, chunk)
+    const int n_ids = PAIRS ? batch : p.n_sel;
+    unsigned char *after_tables =
+        smem + align16((size_t)(6 * batch + 5 + persist_id_words(batch, p.n_sel, PAIRS)) * sizeof(int));
     __shared__ TicketPool pool;
     Mail *mail = reinterpret_cast<Mail *>(after_tables);             // [NW][2]
     unsigned char *staging = after_tables + 2 * NW * sizeof(Mail);
@@ -157,7 +170,10 @@ __global__ __launch_bounds__((NW + 1) * 64)
 
     // ---- work enumeration: exclusive scan of items per sequence, done by wave 0 alone
     // (64 sequences per step: per-lane count, in-wave inclusive scan, running carry)
-    for (int i = tid; i < p.n_sel; i += NT) hids[i] = p.head_ids[i];
+    for (int i = tid; i < n_ids; i += NT) {
+        hids[i] = PAIRS ? p.pair_head[i] : p.head_ids[i];
+        if (PAIRS) pseq[i] = p.pair_seq[i];
+    }
     if (tid < 2 * NW) mail[tid].flag = kMailEmpty;
     if (tid == 0) {
         pool.next = 0;
@@ -170,7 +186,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         int carryF = 0, carry01 = 0, carry23 = 0;
         for (int b0 = 0; b0 < batch; b0 += 64) {
             const int b = b0 + lane;
-            const int L = b < batch ? p.seq_lens[b] : 0;
+            const int L = b < batch ? p.seq_lens[PAIRS ? p.pair_seq[b] : b] : 0;
             const int nF = L > 0 ? L / p.chunk_tokens : 0;
             const int rt = L > 0 ? L % p.chunk_tokens : 0;
             int cls = -1;
@@ -222,7 +238,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             class_end[k] = run;
         }
     }
-    const int total = class_end[3] * p.n_sel;
+    const int total = class_end[3] * n_sel;
     const int stride = gridDim.x * NW;                        // streaming waves in the grid
 
     if (wave == NW) {
@@ -313,9 +329,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
         return __builtin_amdgcn_readfirstlane(lo);
     };
     auto decode = [&](int w, ItemHdr &h) {
-        const int cg = w / p.n_sel;
-        h.si = w - cg * p.n_sel;
-        h.g = __builtin_amdgcn_readfirstlane(hids[h.si]);
+        const int cg = PAIRS ? w : w / n_sel;
+        h.si = PAIRS ? 0 : w - cg * n_sel;
         int L, n_tok;
         if (cg < totalF) {
             cursorF = upper(firstF, cg, cursorF);
@@ -342,6 +357,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
             h.c = L > 0 ? L / p.chunk_tokens : 0;
             n_tok = L > 0 ? L - h.c * p.chunk_tokens : 0;
         }
+        h.g = __builtin_amdgcn_readfirstlane(hids[PAIRS ? h.b : h.si]);
+        h.seq = PAIRS ? __builtin_amdgcn_readfirstlane(pseq[h.b]) : h.b;
         const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
         h.to_out = p.direct_single && n_chunks <= 1;
         h.zero = L <= 0;
@@ -359,13 +376,13 @@ __global__ __launch_bounds__((NW + 1) * 64)
         s.exists = wi < total;
         decode(min(wi, max(total - 1, 0)), s.h);
         if (!s.exists) s.h.nblk = 0;
-        s.head_off = (int64_t)s.h.g * p.stride_head;
+        s.head_off = PAIRS ? 0 : (int64_t)s.h.g * p.stride_head;   // pairs: single-head tiles
         const int32_t *bt =
             p.block_table + (int64_t)s.h.b * p.max_blocks_per_seq + s.h.t0 / kBlockTokens;
         s.ids = bt[min(lane, max(s.h.nblk - 1, 0))];
     };
     auto q_rows = [&](const Slot &s) {
-        return p.q + ((int64_t)s.h.b * p.n_q_heads + s.h.g * R) * D;
+        return p.q + ((int64_t)s.h.seq * p.n_q_heads + s.h.g * R) * D;
     };
     auto issue = [&](Tile &t, int ids, int idx, int64_t head_off, bool valid) {
         const int blk = __builtin_amdgcn_readlane(ids, idx & 63);
@@ -460,10 +477,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
         wait_empty(mb);
         if (!cur.h.zero) Policy::finish(st, mb.o, mb.lse, lane);
         if (lane == 0) {
-            mb.b = cur.h.b;
-            mb.g = cur.h.g;
-            mb.si = cur.h.si;
-            mb.c = cur.h.c;
+            mb.out_row = cur.h.seq * p.n_q_heads + cur.h.g * R;
+            mb.item = (cur.h.b * n_sel + cur.h.si) * p.max_chunks + cur.h.c;
             mb.kind = cur.h.zero ? kKindZero : (cur.h.to_out ? kKindOut : kKindPartial);
         }
         mail_store(&mb.flag, kMailFull);

@@ -187,8 +187,10 @@ __device__ __forceinline__ void lds_combine(const WaveMergeLds<D, R, NW> &sm, Re
 // Result area -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
 template <int D, int R>
 __device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const AttnParams &p,
-                                             int lane, int b, int g, int si, int c, bool to_out)
+                                             int lane, int seq, int b, int g, int si, int c,
+                                             bool to_out)
 {
+    const int n_sel = p.pair_seq ? 1 : p.n_sel;
     for (int idx = lane * 4; idx < R * D; idx += 256) {
         const int r = idx / D, d = idx % D;
         const float4 v = *reinterpret_cast<const float4 *>(&res.o[r][d]);
@@ -199,9 +201,9 @@ __device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const A
             } pk;
             pk.h[0] = __floats2half2_rn(v.x, v.y);
             pk.h[1] = __floats2half2_rn(v.z, v.w);
-            *reinterpret_cast<uint2 *>(p.out + ((int64_t)b * p.n_q_heads + g * R + r) * D + d) = pk.u;
+            *reinterpret_cast<uint2 *>(p.out + ((int64_t)seq * p.n_q_heads + g * R + r) * D + d) = pk.u;
         } else {
-            const int64_t row = (((int64_t)b * p.n_sel + si) * p.max_chunks + c) * R + r;
+            const int64_t row = (((int64_t)b * n_sel + si) * p.max_chunks + c) * R + r;
             *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
             if (d == 0) p.lse_partial[row] = res.lse[r];
         }
@@ -209,11 +211,11 @@ __device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const A
 }
 
 template <int D, int R, int NTHREADS>
-__device__ __forceinline__ void write_zero_rows(const AttnParams &p, int tid, int b, int g)
+__device__ __forceinline__ void write_zero_rows(const AttnParams &p, int tid, int seq, int g)
 {
     for (int idx = tid; idx < R * D; idx += NTHREADS) {
         const int r = idx / D, d = idx % D;
-        p.out[((int64_t)b * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(0.f);
+        p.out[((int64_t)seq * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(0.f);
     }
 }
 
@@ -237,6 +239,7 @@ __device__ __forceinline__ void vec_lds_put(WaveMergeLds<D, R, NW> &sm, const Ve
 // ---------------------------------------------------------------------------------------
 // Simple form: one workgroup per (chunk slot, selected head, sequence); slots past the end
 // of a sequence exit at once.  Used when the batch is too large for the persistent form.
+// Pairs mode: blockIdx.z is the pair, blockIdx.y is 0.
 // ---------------------------------------------------------------------------------------
 template <int D, int R, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParams p)
@@ -251,13 +254,15 @@ __global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParam
     const int gid = lane / LPR;
     const int sub = lane % LPR;
 
-    const int L = p.seq_lens[b];
-    const int g = p.head_ids[si];
+    const bool pairs = p.pair_seq != nullptr;
+    const int seq = pairs ? p.pair_seq[b] : b;
+    const int L = p.seq_lens[seq];
+    const int g = pairs ? p.pair_head[b] : p.head_ids[si];
     const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
     const bool to_out = p.direct_single && n_chunks <= 1;
 
     if (L <= 0) {
-        if (to_out && c == 0) write_zero_rows<D, R, NW * 64>(p, tid, b, g);
+        if (to_out && c == 0) write_zero_rows<D, R, NW * 64>(p, tid, seq, g);
         return;
     }
     if (c >= n_chunks) return;
@@ -267,13 +272,13 @@ __global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParam
     const int nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
     const int rem = n_tok & (kBlockTokens - 1);
     const int32_t *bt = p.block_table + (int64_t)b * p.max_blocks_per_seq + t0 / kBlockTokens;
-    const int64_t head_off = (int64_t)g * p.stride_head;
+    const int64_t head_off = pairs ? 0 : (int64_t)g * p.stride_head;
 
     __half2 qh[R][4];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         Pack16 t;
-        t.u = *reinterpret_cast<const uint4 *>(p.q + ((int64_t)b * p.n_q_heads + g * R + r) * D + sub * 8);
+        t.u = *reinterpret_cast<const uint4 *>(p.q + ((int64_t)seq * p.n_q_heads + g * R + r) * D + sub * 8);
 #pragma unroll
         for (int x = 0; x < 4; ++x) qh[r][x] = t.h2[x];
     }
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParam
     __shared__ ResultLds<D, R> res;
     lds_combine<D, R, NW, NW * 64>(sm, res, tid);
     __syncthreads();
-    if (wave == 0) flush_result<D, R>(res, p, lane, b, g, si, c, to_out);
+    if (wave == 0) flush_result<D, R>(res, p, lane, seq, b, g, si, c, to_out);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -380,24 +385,28 @@ struct VecPolicy {
     }
 };
 
-// Log-sum-exp merge of chunk partials: one workgroup of D threads per (sequence, selected row).
+// Log-sum-exp merge of chunk partials: one workgroup of D threads per (sequence, selected row);
+// in pairs mode per (pair, row of the group).
 template <int D>
 __global__ __launch_bounds__(D) void attn_merge_kernel(const AttnParams p, int group)
 {
     const int j = blockIdx.x;            // selected row: i*group + rr
     const int b = blockIdx.y;
     const int d = threadIdx.x;
-    const int L = p.seq_lens[b];
+    const bool pairs = p.pair_seq != nullptr;
+    const int seq = pairs ? p.pair_seq[b] : b;
+    const int n_sel = pairs ? 1 : p.n_sel;
+    const int L = p.seq_lens[seq];
     const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
     if (p.direct_single && n_chunks <= 1) return;      // already written by the partial pass
-    const int h = p.head_ids[j / group] * group + j % group;
-    __half *o = p.out + ((int64_t)b * p.n_q_heads + h) * D;
+    const int h = (pairs ? p.pair_head[b] : p.head_ids[j / group]) * group + j % group;
+    __half *o = p.out + ((int64_t)seq * p.n_q_heads + h) * D;
     if (n_chunks <= 0) {
         o[d] = __float2half_rn(0.f);
         return;
     }
     // partial of chunk c of this row: index ((b*n_sel + i)*max_chunks + c)*group + rr
-    const int64_t base = ((int64_t)b * p.n_sel + j / group) * p.max_chunks * group + j % group;
+    const int64_t base = ((int64_t)b * n_sel + j / group) * p.max_chunks * group + j % group;
     const float *lse = p.lse_partial + base;
     const float *op = p.o_partial + base * D + d;
     float M = lse[0];

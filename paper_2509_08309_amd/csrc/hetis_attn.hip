@@ -149,12 +149,12 @@ static int tickets_for(unsigned int **out)
     return HETIS_OK;
 }
 
-template <class Policy>
+template <class Policy, bool PAIRS>
 static int launch_persistent(AttnParams p, int batch, hipStream_t st)
 {
     constexpr int NW = kVecWaves;
-    auto kernel = attn_chunk_persistent_kernel<Policy, NW>;
-    const size_t lds = persist_lds_bytes<Policy, NW>(batch, p.n_sel);
+    auto kernel = attn_chunk_persistent_kernel<Policy, NW, PAIRS>;
+    const size_t lds = persist_lds_bytes<Policy, NW>(batch, p.n_sel, PAIRS);
     int occ = resident_per_cu(kernel, (NW + 1) * 64, lds);
     if (occ < 1) return HETIS_ERR_LAUNCH;
     const int cus = device_cu_count();
@@ -181,20 +181,25 @@ static int launch_persistent(AttnParams p, int batch, hipStream_t st)
 
 // Kernel choice depends on the shape only (never on the head subset): vector arithmetic for
 // query groups of 1 or 2, MFMA for groups of 4 or 8; batches too large for the persistent
-// kernel's LDS tables take the simple one-workgroup-per-chunk-slot kernel.
+// kernel's LDS tables take the simple one-workgroup-per-chunk-slot kernel.  `batch` is the
+// number of rows of the enumeration: sequences, or (sequence, head) pairs in pairs mode.
 template <int D, int R>
 static int launch_chunk(const AttnParams &p, int batch, hipStream_t st)
 {
+    const bool pairs = p.pair_seq != nullptr;
     const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
     if (batch > kMaxPersistBatch || p.n_sel > kMaxPersistHeads || max_items >= (int64_t)1 << 31) {
+        if (batch > 65535 || p.n_sel > 65535) return HETIS_ERR_UNSUPPORTED;   // grid limits
         dim3 grid(p.max_chunks, p.n_sel, batch);
         attn_chunk_vec_kernel<D, R, kVecWaves><<<grid, kVecWaves * 64, 0, st>>>(p);
         return HETIS_OK;
     }
     if constexpr (R >= 4)
-        return launch_persistent<MfmaPolicy<D, R>>(p, batch, st);
+        return pairs ? launch_persistent<MfmaPolicy<D, R>, true>(p, batch, st)
+                     : launch_persistent<MfmaPolicy<D, R>, false>(p, batch, st);
     else
-        return launch_persistent<VecPolicy<D, R>>(p, batch, st);
+        return pairs ? launch_persistent<VecPolicy<D, R>, true>(p, batch, st)
+                     : launch_persistent<VecPolicy<D, R>, false>(p, batch, st);
 }
 
 static int dispatch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
@@ -220,6 +225,7 @@ static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream
     return HETIS_OK;
 }
 
+// `batch`: sequences, or pairs in pairs mode (p.n_sel is 1 there)
 static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream_t st)
 {
     dim3 grid(p.n_sel * r, batch);
@@ -340,6 +346,51 @@ int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *
     rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, st);
     if (rc != HETIS_OK) return rc;
     if (p.max_chunks > 1) launch_merge(p, shape->head_dim, c.group, shape->batch, st);
+    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
+
+int hetis_attn_decode_pairs(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
+                            const void *v_tiles, const int32_t *block_table,
+                            const int32_t *seq_lens, const int32_t *pair_seq,
+                            const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
+                            void *stream)
+{
+    Checked c;
+    if (!shape || !q || !k_tiles || !v_tiles || !block_table || !seq_lens || !pair_seq ||
+        !pair_head || !out)
+        return HETIS_ERR_NULL;
+    int rc = check_shape(shape, 1, &c);
+    if (rc != HETIS_OK) return rc;
+    if (n_pairs < 0) return HETIS_ERR_BAD_SHAPE;
+    if (n_pairs > 65535) return HETIS_ERR_UNSUPPORTED;
+    // the pool holds single-head tiles: one stride, no head term
+    const int64_t tile = (int64_t)shape->block_size * shape->head_dim;
+    c.stride_block = shape->kv_stride_block ? shape->kv_stride_block : tile;
+    if (c.stride_block % 8 != 0 || c.stride_block < tile) return HETIS_ERR_BAD_SHAPE;
+    c.stride_head = 0;
+    if (n_pairs == 0) return HETIS_OK;
+
+    AttnParams p = make_params(shape, c, q, k_tiles, v_tiles, block_table, seq_lens, nullptr, 1,
+                               scale, out);
+    p.pair_seq = pair_seq;
+    p.pair_head = pair_head;
+    const int chunk = decode_chunk_tokens(c.group);
+    p.chunk_tokens = chunk;
+    const int64_t max_tokens = (int64_t)shape->max_blocks_per_seq * kBlockTokens;
+    p.max_chunks = (int)((max_tokens + chunk - 1) / chunk);
+    p.direct_single = 1;
+    hipStream_t st = (hipStream_t)stream;
+    if (p.max_chunks > 1) {
+        const size_t rows = (size_t)n_pairs * c.group * p.max_chunks;
+        float *ws = nullptr;
+        rc = workspace_for(rows * (shape->head_dim + 1) * sizeof(float), &ws);
+        if (rc != HETIS_OK) return rc;
+        p.o_partial = ws;
+        p.lse_partial = ws + rows * shape->head_dim;
+    }
+    rc = launch_chunks(p, shape->head_dim, c.group, n_pairs, st);
+    if (rc != HETIS_OK) return rc;
+    if (p.max_chunks > 1) launch_merge(p, shape->head_dim, c.group, n_pairs, st);
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
 
@@ -486,6 +537,41 @@ int hetis_attn_validate(const hetis_attn_shape *shape, const int32_t *block_tabl
         for (size_t j = 0; j < nb; ++j) {
             const int64_t blk = bt[b * MB + j];
             if (blk < 0 || blk >= num_blocks) return HETIS_ERR_BAD_CONTENT;
+        }
+    }
+    return HETIS_OK;
+}
+
+int hetis_attn_validate_pairs(const hetis_attn_shape *shape, const int32_t *block_table,
+                              const int32_t *seq_lens, const int32_t *pair_seq,
+                              const int32_t *pair_head, int32_t n_pairs, int64_t num_tiles,
+                              void *stream)
+{
+    Checked c;
+    if (!shape || !block_table || !seq_lens || !pair_seq || !pair_head) return HETIS_ERR_NULL;
+    int rc = check_shape(shape, 1, &c);
+    if (rc != HETIS_OK) return rc;
+    if (num_tiles <= 0 || n_pairs < 0) return HETIS_ERR_BAD_SHAPE;
+    if (n_pairs == 0) return HETIS_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t B = (size_t)shape->batch, MB = (size_t)shape->max_blocks_per_seq, P = (size_t)n_pairs;
+    std::vector<int32_t> sl(B), ps(P), ph(P), bt(P * MB);
+    if (hipStreamSynchronize(st) != hipSuccess) return HETIS_ERR_LAUNCH;
+    if (hipMemcpy(sl.data(), seq_lens, B * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(ps.data(), pair_seq, P * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(ph.data(), pair_head, P * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(bt.data(), block_table, bt.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return HETIS_ERR_LAUNCH;
+    for (size_t b = 0; b < B; ++b)
+        if (sl[b] < 0 || sl[b] > (int64_t)MB * kBlockTokens) return HETIS_ERR_BAD_CONTENT;
+    for (size_t i = 0; i < P; ++i) {
+        if (ps[i] < 0 || ps[i] >= shape->batch) return HETIS_ERR_BAD_CONTENT;
+        if (ph[i] < 0 || ph[i] >= shape->n_kv_heads) return HETIS_ERR_BAD_CONTENT;
+        const int64_t L = sl[(size_t)ps[i]];
+        const size_t nb = (size_t)((L + kBlockTokens - 1) / kBlockTokens);
+        for (size_t j = 0; j < nb; ++j) {
+            const int64_t t = bt[i * MB + j];
+            if (t < 0 || t >= num_tiles) return HETIS_ERR_BAD_CONTENT;
         }
     }
     return HETIS_OK;

@@ -223,3 +223,30 @@ def test_kv_copy_argument_errors(lib):
     assert kv_copy(sp, dp, n_pairs=0) == binding.HETIS_OK
     assert H.hetis_kv_profile_events(P, None) == binding.HETIS_ERR_NULL
     assert H.hetis_kv_profile_events(None, None) == binding.HETIS_OK
+
+
+# ---------------------------------------------------------------- per-request head subsets
+
+def decode_pairs(shape, n_pairs=5, **kw):
+    a = dict(q=P, k=P, v=P, bt=P, sl=P, ps=P, ph=P, out=P)
+    a.update(kw)
+    return H.hetis_attn_decode_pairs(shape, a["q"], a["k"], a["v"], a["bt"], a["sl"], a["ps"],
+                                     a["ph"], n_pairs, 0.125, a["out"], 0)
+
+
+@pytest.mark.parametrize("arg", ["q", "k", "v", "bt", "sl", "ps", "ph", "out"])
+def test_pairs_null_pointers(lib, arg):
+    assert decode_pairs(good(), **{arg: None}) == binding.HETIS_ERR_NULL
+
+
+def test_pairs_argument_errors(lib):
+    assert decode_pairs(good(), n_pairs=-1) == binding.HETIS_ERR_BAD_SHAPE
+    assert decode_pairs(good(), n_pairs=65536) == binding.HETIS_ERR_UNSUPPORTED
+    assert decode_pairs(H.make_shape(4, 8, 8, 96, 16)) == binding.HETIS_ERR_UNSUPPORTED
+    assert decode_pairs(H.make_shape(4, 8, 3, 64, 16)) == binding.HETIS_ERR_BAD_SHAPE
+    assert decode_pairs(H.make_shape(4, 8, 8, 64, 16, kv_stride_block=1000)) == binding.HETIS_ERR_BAD_SHAPE
+    assert decode_pairs(H.make_shape(4, 8, 8, 64, 16, kv_stride_block=1028)) == binding.HETIS_ERR_BAD_SHAPE
+    assert decode_pairs(good(), n_pairs=0) == binding.HETIS_OK        # nothing to do, no HIP call
+    assert H.hetis_attn_validate_pairs(good(), P, P, None, P, 3, 10, 0) == binding.HETIS_ERR_NULL
+    assert H.hetis_attn_validate_pairs(good(), P, P, P, P, 3, 0, 0) == binding.HETIS_ERR_BAD_SHAPE
+    assert H.hetis_attn_validate_pairs(good(), P, P, P, P, 0, 10, 0) == binding.HETIS_OK

@@ -1,0 +1,170 @@
+"""Parity of hetis_attn_decode_pairs (per-request head subsets over single-head tiles) against
+the CPU checker, and bit-identity with the common-subset entry point."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_08309_amd as H
+from paper_2509_08309_amd import workloads as W
+
+from gpu_harness import SENTINEL, TOL, Dev, as_f64, bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def i32(a):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, dtype=np.int32))).to(DEV)
+
+
+def spec_of(lens, Hq, Hkv, D, seed):
+    lens = tuple(int(x) for x in lens)
+    return W.WorkloadSpec("pairs", len(lens), Hq, Hkv, D, tuple(range(Hkv)), seed, "fixed", (lens,),
+                          max(max(lens), 1))
+
+
+def run_pairs(pw, order=None, out=None):
+    s = pw.spec
+    idx = np.arange(pw.n_pairs) if order is None else np.asarray(order)
+    shape = H.make_shape(s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim, pw.block_table.shape[1])
+    bt, sl = i32(pw.block_table[idx]), i32(pw.seq_lens)
+    ps, ph = i32(pw.pair_seq[idx]), i32(pw.pair_head[idx])
+    H.check(H.hetis_attn_validate_pairs(shape, bt, sl, ps, ph, len(idx), pw.num_tiles),
+            "validate_pairs")
+    if out is None:
+        out = torch.empty_like(pw.q)
+        out.view(torch.int16).fill_(np.int16(SENTINEL))
+    H.check(H.hetis_attn_decode_pairs(shape, pw.q, pw.k_tiles, pw.v_tiles, bt, sl, ps, ph,
+                                      len(idx), s.scale, out), "hetis_attn_decode_pairs")
+    torch.cuda.synchronize()
+    return out
+
+
+def named_rows(pw):
+    r = pw.spec.group_size
+    m = np.zeros((pw.spec.batch, pw.spec.n_q_heads), dtype=bool)
+    for b, g in zip(pw.pair_seq, pw.pair_head):
+        m[b, g * r:(g + 1) * r] = True
+    return m
+
+
+def oracle_pairs(pw, pick=None):
+    idx = np.arange(pw.n_pairs) if pick is None else np.asarray(pick)
+    return oracle.attn_decode_pairs(pw.q.cpu().numpy(), pw.k_tiles.cpu().numpy(),
+                                    pw.v_tiles.cpu().numpy(), pw.block_table[idx], pw.seq_lens,
+                                    pw.pair_seq[idx], pw.pair_head[idx], pw.spec.n_kv_heads,
+                                    pw.spec.scale)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 8, 64), (6, 6, 128), (16, 8, 128), (16, 4, 64),
+                                      (32, 4, 128)])
+def test_pairs_small(Hq, Hkv, D):
+    lens = [1, 15, 16, 17, 100, 255, 256, 257, 0, 600, 1025, 31]
+    rng = np.random.default_rng(61)
+    subsets = W.draw_head_subsets(len(lens), Hkv, Hkv / 2, rng)
+    subsets[0] = np.arange(Hkv, dtype=np.int32)          # one request with every head
+    subsets[3] = np.zeros(0, dtype=np.int32)             # one with none on this device
+    subsets[8] = np.array([Hkv - 1], dtype=np.int32)     # the empty sequence has a pair
+    pw = W.make_pairs_workload(spec_of(lens, Hq, Hkv, D, 62), device=DEV, subsets=subsets)
+    out = run_pairs(pw)
+    ref = oracle_pairs(pw)
+    m = named_rows(pw)
+    got = as_f64(out)
+    assert not np.isnan(got[m]).any()
+    err = np.abs(got[m] - ref[m]).max()
+    assert err <= TOL, f"max abs err {err:.3e}"
+    assert (bits(out)[~m] == SENTINEL).all(), "rows that no pair names were written"
+    # order of the pairs does not matter, bit for bit; run to run deterministic
+    order = rng.permutation(pw.n_pairs)
+    assert torch.equal(run_pairs(pw, order).view(torch.int16), out.view(torch.int16))
+    assert torch.equal(run_pairs(pw).view(torch.int16), out.view(torch.int16))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 8, 128), (16, 2, 128)])
+def test_pairs_rows_equal_the_common_subset_rows_bitwise(Hq, Hkv, D):
+    """A standard pool read as single-head tiles (tile = block * Hkv + head): every pair's rows
+    must be the rows hetis_attn_decode computes for all heads."""
+    lens = [40, 256, 257, 700, 1500, 16, 3]
+    w = W.make_custom(lens, Hq, Hkv, D, list(range(Hkv)), seed=63, device=DEV)
+    full = Dev(w).decode(list(range(Hkv)))
+    rng = np.random.default_rng(64)
+    subsets = W.draw_head_subsets(len(lens), Hkv, Hkv / 2, rng)
+    subsets[1] = np.arange(Hkv, dtype=np.int32)
+    pair_seq = np.concatenate([np.full(len(h), b, dtype=np.int32) for b, h in enumerate(subsets)])
+    pair_head = np.concatenate(subsets).astype(np.int32)
+    table = w.block_table[pair_seq] * Hkv + pair_head[:, None]
+    table[w.block_table[pair_seq] < 0] = -1
+    pw = W.PairsWorkload(w.spec, w.seq_lens, pair_seq, pair_head, table.astype(np.int32),
+                         w.num_blocks * Hkv, w.q, w.k_cache.view(-1, 16, D),
+                         w.v_cache.view(-1, 16, D))
+    out = run_pairs(pw)
+    m = named_rows(pw)
+    assert (bits(out)[m] == bits(full)[m]).all()
+    assert (bits(out)[~m] == SENTINEL).all()
+
+
+@pytest.mark.parametrize("name", ["c3_13b_subset", "c5_70b_gqa"])
+def test_pairs_full_size_sampled(name):
+    """The device's share when every request has its own head subset (13 of 40 heads on
+    average for the 13B shape; 3 of 8 groups for the grouped-query shape)."""
+    spec = W.SPECS[name]
+    pw = W.make_pairs_workload(spec, device=DEV)
+    out = run_pairs(pw)
+    rng = np.random.default_rng(65)
+    lens_p = pw.seq_lens[pw.pair_seq]
+    pick = np.unique(np.concatenate([[int(np.argmin(lens_p)), int(np.argmax(lens_p))],
+                                     rng.integers(0, pw.n_pairs, size=40)]))
+    ref = oracle_pairs(pw, pick)
+    r = spec.group_size
+    got = as_f64(out)
+    err = 0.0
+    for p in pick:
+        b, g = int(pw.pair_seq[p]), int(pw.pair_head[p])
+        err = max(err, np.abs(got[b, g * r:(g + 1) * r] - ref[b, g * r:(g + 1) * r]).max())
+    assert err <= TOL, f"max abs err {err:.3e}"
+    m = named_rows(pw)
+    assert not np.isnan(got[m]).any()
+    assert (bits(out)[~m] == SENTINEL).all()
+
+
+def test_more_pairs_than_the_persistent_kernel_holds():
+    """2500 pairs: the simple kernel takes over; same results as the checker."""
+    rng = np.random.default_rng(66)
+    B, Hkv, D = 250, 10, 64
+    lens = rng.integers(1, 400, size=B)
+    subsets = [np.arange(Hkv, dtype=np.int32) for _ in range(B)]
+    pw = W.make_pairs_workload(spec_of(lens, Hkv, Hkv, D, 67), device=DEV, subsets=subsets)
+    assert pw.n_pairs == 2500
+    out = run_pairs(pw)
+    pick = rng.integers(0, pw.n_pairs, size=60)
+    ref = oracle_pairs(pw, pick)
+    got = as_f64(out)
+    for p in pick:
+        b, g = int(pw.pair_seq[p]), int(pw.pair_head[p])
+        assert np.abs(got[b, g] - ref[b, g]).max() <= TOL
+    assert not np.isnan(got).any()
+
+
+def test_no_pairs_and_bad_content():
+    lens = [20, 7]
+    pw = W.make_pairs_workload(spec_of(lens, 4, 4, 64, 68), device=DEV, subsets=[[0, 2], [1]])
+    s = pw.spec
+    shape = H.make_shape(s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim, pw.block_table.shape[1])
+    out = torch.empty_like(pw.q)
+    out.view(torch.int16).fill_(np.int16(SENTINEL))
+    assert H.hetis_attn_decode_pairs(shape, pw.q, pw.k_tiles, pw.v_tiles, i32(pw.block_table),
+                                     i32(pw.seq_lens), i32(pw.pair_seq), i32(pw.pair_head), 0,
+                                     s.scale, out) == 0
+    torch.cuda.synchronize()
+    assert (bits(out) == SENTINEL).all()
+    bad = H.binding.HETIS_ERR_BAD_CONTENT
+    v = lambda bt, ps, ph, nt=pw.num_tiles: H.hetis_attn_validate_pairs(
+        shape, i32(bt), i32(pw.seq_lens), i32(ps), i32(ph), pw.n_pairs, nt)
+    assert v(pw.block_table, pw.pair_seq, pw.pair_head) == 0
+    assert v(pw.block_table, [0, 0, 2], pw.pair_head) == bad
+    assert v(pw.block_table, pw.pair_seq, [0, 4, 1]) == bad
+    assert v(pw.block_table, pw.pair_seq, pw.pair_head, nt=int(pw.block_table.max())) == bad
+    t = pw.block_table.copy()
+    t[2, 0] = -1
+    assert v(t, pw.pair_seq, pw.pair_head) == bad
