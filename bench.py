@@ -101,6 +101,75 @@ def timed_steps(step, set_events, stream, steps, warmup):
     return wall, dev_ms, np.array([a.elapsed_time(b) for a, b in ev_kernel])
 
 
+def bench_pairs(args):
+    """hetis_attn_decode_pairs on the workload's shape when every request has its own head
+    subset (drawn around the workload's number of selected heads) over single-head tiles."""
+    import numpy as np
+    import torch
+    import paper_2509_08309_amd as H
+    from paper_2509_08309_amd import workloads as W
+
+    spec = W.SPECS[args.workload]
+    dev = torch.device("cuda:0")
+    pw = W.make_pairs_workload(spec, device=dev)
+    stream = torch.cuda.current_stream()
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    bt, sl = to_dev(pw.block_table), to_dev(pw.seq_lens)
+    ps, ph = to_dev(pw.pair_seq), to_dev(pw.pair_head)
+    shape = H.make_shape(spec.batch, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
+                         pw.block_table.shape[1])
+    H.check(H.hetis_attn_validate_pairs(shape, bt, sl, ps, ph, pw.n_pairs, pw.num_tiles), "validate")
+    out = torch.zeros_like(pw.q)
+
+    def step():
+        H.check(H.hetis_attn_decode_pairs(shape, pw.q, pw.k_tiles, pw.v_tiles, bt, sl, ps, ph,
+                                          pw.n_pairs, spec.scale, out, stream), "decode_pairs")
+
+    wall, dev_ms, kern_ms = timed_steps(step, H.hetis_attn_profile_events, stream, args.steps,
+                                        args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    kv_bytes = pw.kv_bytes()
+    achieved = kv_bytes / (float(kern_ms.mean()) * 1e-3) / 1e9
+    rec = {
+        "metric": "decode-attention tokens/s with per-request head subsets "
+                  "(KV-read HBM GB/s in roofline), 1 GPU",
+        "value": spec.batch / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate", "data": "synthetic",
+        "config": {"workload": spec.name, "op": "decode_pairs", "batch": spec.batch,
+                   "n_q_heads": spec.n_q_heads, "n_kv_heads": spec.n_kv_heads,
+                   "head_dim": spec.head_dim, "n_pairs": pw.n_pairs,
+                   "mean_heads_per_request": pw.n_pairs / spec.batch, "seed": spec.seed,
+                   "entry_point": "hetis_attn_decode_pairs"},
+        "kv_gbps_step": kv_bytes / (ms_per_step * 1e-3) / 1e9,
+        "device_us_per_step": dev_ms * 1e3,
+        "chunk_kernel_us": {"mean": float(kern_ms.mean() * 1e3),
+                            "median": float(np.median(kern_ms) * 1e3),
+                            "min": float(kern_ms.min() * 1e3)},
+        "roofline": {"bound": "hbm", "kernel": "attn_chunk_persistent_kernel<..., pairs>",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": read_traffic(f"decode_pairs_{spec.name}"),
+                     "algorithmic_bytes": kv_bytes},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        lens_p = pw.seq_lens[pw.pair_seq].astype(np.int64)
+        n = max(1, min(pw.n_pairs, int(np.searchsorted(np.cumsum(lens_p), 40000))))
+        q, k, v = pw.q.cpu().numpy(), pw.k_tiles.cpu().numpy(), pw.v_tiles.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.attn_decode_pairs(q, k, v, pw.block_table[:n], pw.seq_lens, pw.pair_seq[:n],
+                                 pw.pair_head[:n], spec.n_kv_heads, spec.scale)
+        dt = time.perf_counter() - t0
+        seqs = len(np.unique(pw.pair_seq[:n]))
+        rec["cpu_baseline"] = {
+            "value": seqs / dt, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": f"first {n} of {pw.n_pairs} pairs ({seqs} sequences, {int(lens_p[:n].sum())} "
+                      f"cached tokens x heads), {dt:.2f} s wall"}
+    print(json.dumps(rec))
+
+
 def bench_kv(args):
     """Cache-management kernels on the workload's shapes: the decode-step store of the new
     token (kv_append), a store of every cached token as after prefill (kv_store), and the move
@@ -234,7 +303,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3_13b_subset")
-    ap.add_argument("--op", default="decode", choices=["decode", "kv_append", "kv_store", "kv_copy"])
+    ap.add_argument("--op", default="decode", choices=["decode", "decode_pairs", "kv_append", "kv_store", "kv_copy"])
     ap.add_argument("--cpu-seconds", type=float, default=1.5,
                     help="wall-clock budget of the CPU checker sample (x cores = CPU work)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -253,6 +322,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     H.binding.load()                       # the HIP library must be built; no fallback exists
+    if args.op == "decode_pairs":
+        return bench_pairs(args)
     if args.op != "decode":
         return bench_kv(args)
     spec = W.SPECS[args.workload]

@@ -2,9 +2,9 @@
 // independent of how a tile is turned into scores and sums (that is the Policy: vector ALU
 // arithmetic for small query groups, MFMA for grouped-query attention).
 //
-// Work enumeration: every workgroup scans the sequence lengths into tables of running counts
-// (LDS): whole chunks per sequence, and ragged last chunks per sequence in four classes by
-// size.  A flat item number then decodes into (sequence, chunk, selected head) by binary
+// Work enumeration: every workgroup loads the sequence lengths and scans them into tables of
+// running counts (LDS): whole chunks per sequence, and ragged last chunks per sequence in four
+// classes by size.  A flat item number then decodes into (sequence, chunk, selected head) by binary
 // search, whole chunks first, then the ragged ones from the longest class to the shortest,
 // without launching a workgroup per possible chunk; the items handed out last are the
 // shortest, which keeps the tail of the launch short.  An item is one chunk of one
@@ -168,63 +168,96 @@ __global__ __launch_bounds__((NW + 1) * 64)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // ---- work enumeration: exclusive scan of items per sequence, done by wave 0 alone
-    // (64 sequences per step: per-lane count, in-wave inclusive scan, running carry)
+    // ---- work enumeration.  All threads fetch the lengths and work out the counts of their
+    // rows (whole chunks; size class of the ragged last chunk), four rows a thread and round
+    // so that the loads of a round are in flight together.  Wave 0 then turns the counts into
+    // running counts in place: lane l owns `per` consecutive rows, adds up their counts, the
+    // 64 lane totals go through one in-wave scan, and a second pass over the lane's rows
+    // writes the tables.  `per` is odd so that the lanes' LDS accesses (stride `per` words)
+    // fall into different banks.
     for (int i = tid; i < n_ids; i += NT) {
         hids[i] = PAIRS ? p.pair_head[i] : p.head_ids[i];
         if (PAIRS) pseq[i] = p.pair_seq[i];
+    }
+    // size class of a ragged last chunk of `rt` tokens: 0 = longest quarter ... 3 = shortest
+    auto ragged_class = [&](int rt) { return 3 - min(3, (4 * rt - 1) / p.chunk_tokens); };
+    for (int i0 = tid; i0 < batch; i0 += 4 * NT) {
+        int row[4], L[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = min(i0 + u * NT, batch - 1);
+            row[u] = PAIRS ? p.pair_seq[i] : i;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) L[u] = p.seq_lens[row[u]];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * NT;
+            if (i >= batch) continue;
+            const int nF = L[u] > 0 ? L[u] / p.chunk_tokens : 0;
+            const int rt = L[u] > 0 ? L[u] - nF * p.chunk_tokens : 0;
+            int cls = -1;
+            if (rt > 0) cls = ragged_class(rt);
+            if (L[u] <= 0 && p.direct_single) cls = 3;      // the item that writes the zeros
+            lens[i] = L[u];
+            firstF[i] = nF;                 // counts for now; running counts after the scan
+            firstT[i] = cls;
+        }
     }
     if (tid < 2 * NW) mail[tid].flag = kMailEmpty;
     if (tid == 0) {
         pool.next = 0;
         pool.end = 0;
     }
-    // size class of a ragged last chunk of `rt` tokens: 0 = longest quarter ... 3 = shortest
-    auto ragged_class = [&](int rt) { return 3 - min(3, (4 * rt - 1) / p.chunk_tokens); };
+    __syncthreads();
     if (wave == 0) {
-        // counts of classes 0,1 and 2,3 travel packed in 16-bit halves (batch < 65536)
-        int carryF = 0, carry01 = 0, carry23 = 0;
-        for (int b0 = 0; b0 < batch; b0 += 64) {
-            const int b = b0 + lane;
-            const int L = b < batch ? p.seq_lens[PAIRS ? p.pair_seq[b] : b] : 0;
-            const int nF = L > 0 ? L / p.chunk_tokens : 0;
-            const int rt = L > 0 ? L % p.chunk_tokens : 0;
-            int cls = -1;
-            if (rt > 0) cls = ragged_class(rt);
-            if (L <= 0 && b < batch && p.direct_single) cls = 3;      // the item that writes the zeros
-            const int n01 = cls == 0 ? 1 : (cls == 1 ? 1 << 16 : 0);
-            const int n23 = cls == 2 ? 1 : (cls == 3 ? 1 << 16 : 0);
-            int inclF = nF, incl01 = n01, incl23 = n23;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int upF = __shfl_up(inclF, off, 64);
-                const int up01 = __shfl_up(incl01, off, 64);
-                const int up23 = __shfl_up(incl23, off, 64);
-                if (lane >= off) {
-                    inclF += upF;
-                    incl01 += up01;
-                    incl23 += up23;
-                }
-            }
-            if (b < batch) {
-                lens[b] = L;
-                firstF[b] = carryF + inclF - nF;
-                const int e01 = carry01 + incl01 - n01, e23 = carry23 + incl23 - n23;
-                firstT[0 * (batch + 1) + b] = e01 & 0xffff;
-                firstT[1 * (batch + 1) + b] = e01 >> 16;
-                firstT[2 * (batch + 1) + b] = e23 & 0xffff;
-                firstT[3 * (batch + 1) + b] = e23 >> 16;
-            }
-            carryF += __shfl(inclF, 63, 64);
-            carry01 += __shfl(incl01, 63, 64);
-            carry23 += __shfl(incl23, 63, 64);
+        // classes 0,1 and 2,3 travel packed in 16-bit halves (batch < 65536)
+        auto class_counts = [&](int cls, int &n01, int &n23) {
+            n01 = cls == 0 ? 1 : (cls == 1 ? 1 << 16 : 0);
+            n23 = cls == 2 ? 1 : (cls == 3 ? 1 << 16 : 0);
+        };
+        const int per = ((batch + 63) / 64) | 1;
+        const int lo = min(lane * per, batch), hi = min(lo + per, batch);
+        int sumF = 0, sum01 = 0, sum23 = 0;
+        for (int b = lo; b < hi; ++b) {
+            int n01, n23;
+            class_counts(firstT[b], n01, n23);
+            sumF += firstF[b];
+            sum01 += n01;
+            sum23 += n23;
         }
-        if (lane == 0) {
-            firstF[batch] = carryF;
-            firstT[0 * (batch + 1) + batch] = carry01 & 0xffff;
-            firstT[1 * (batch + 1) + batch] = carry01 >> 16;
-            firstT[2 * (batch + 1) + batch] = carry23 & 0xffff;
-            firstT[3 * (batch + 1) + batch] = carry23 >> 16;
+        int inclF = sumF, incl01 = sum01, incl23 = sum23;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int upF = __shfl_up(inclF, off, 64);
+            const int up01 = __shfl_up(incl01, off, 64);
+            const int up23 = __shfl_up(incl23, off, 64);
+            if (lane >= off) {
+                inclF += upF;
+                incl01 += up01;
+                incl23 += up23;
+            }
+        }
+        int runF = inclF - sumF, run01 = incl01 - sum01, run23 = incl23 - sum23;
+        for (int b = lo; b < hi; ++b) {
+            int n01, n23;
+            class_counts(firstT[b], n01, n23);
+            const int nF = firstF[b];
+            firstF[b] = runF;
+            firstT[0 * (batch + 1) + b] = run01 & 0xffff;
+            firstT[1 * (batch + 1) + b] = run01 >> 16;
+            firstT[2 * (batch + 1) + b] = run23 & 0xffff;
+            firstT[3 * (batch + 1) + b] = run23 >> 16;
+            runF += nF;
+            run01 += n01;
+            run23 += n23;
+        }
+        if (lane == 63) {
+            firstF[batch] = inclF;
+            firstT[0 * (batch + 1) + batch] = incl01 & 0xffff;
+            firstT[1 * (batch + 1) + batch] = incl01 >> 16;
+            firstT[2 * (batch + 1) + batch] = incl23 & 0xffff;
+            firstT[3 * (batch + 1) + batch] = incl23 >> 16;
         }
     }
     __syncthreads();
