@@ -11,8 +11,8 @@ fp16 store) over one batch of seeded synthetic input that is already resident
 in HBM.  Prints ONE JSON line:
   value       decode tokens/s of this device's head share (batch / step time)
   roofline    KV bytes the step must read / average duration of the chunk kernel (the
-              kernel that streams the KV cache), measured with events that the library
-              records around that launch on the launch stream, against the 8 TB/s peak
+              kernel that streams the KV cache), measured with an event pair that the library
+              attaches to that kernel's dispatch on the launch stream, against the 8 TB/s peak
   cpu_baseline  the fp64 CPU checker timed on a bounded sample of the same workload
 """
 import argparse
@@ -74,7 +74,7 @@ def cpu_baseline(w_host, budget_s: float):
 def timed_steps(step, set_events, stream, steps, warmup):
     """W untimed steps, then K timed ones between synchronisations.  Returns (wall seconds,
     device ms per step from one event pair, per-step kernel ms from the pairs that the library
-    records around its main kernel launch)."""
+    attaches to the dispatch of its main kernel)."""
     import numpy as np
     import torch
     for _ in range(warmup):
@@ -359,7 +359,7 @@ def main():
         path = "hetis_attn_decode"
 
     # Events: one pair brackets the whole timed region on the launch stream; one pair per
-    # step is handed to the library, which records it around the launch of the chunk kernel
+    # step is handed to the library, which attaches it to the dispatch of the chunk kernel
     # (the kernel that streams the KV cache) inside the call.
     wall, dev_ms_per_step, kern_ms = timed_steps(step, H.hetis_attn_profile_events, stream,
                                                  args.steps, args.warmup)

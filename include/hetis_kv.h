@@ -120,9 +120,10 @@ int hetis_kv_copy_tiles(const hetis_kv_pool *src_pool, const void *src_k, const 
                         void *stream);
 
 /*
- * Measurement hook, like hetis_attn_profile_events: the two events are recorded
- * right before and after the kernel launch of every later hetis_kv_* call of
- * the same host thread.  (NULL, NULL) switches it off.
+ * Measurement hook, like hetis_attn_profile_events: the two events are attached to
+ * the kernel dispatch of every later hetis_kv_* call of the same host thread
+ * (start when the kernel begins to execute, stop when it has finished).
+ * (NULL, NULL) switches it off.
  */
 int hetis_kv_profile_events(void *begin, void *end);
 

@@ -3,6 +3,8 @@
 // exercised on a machine without a GPU.
 #include "../../include/hetis_attn.h"
 
+#include <hip/hip_ext.h>
+
 #include <cstdlib>
 #include <mutex>
 #include <vector>
@@ -149,6 +151,22 @@ static int tickets_for(unsigned int **out)
     return HETIS_OK;
 }
 
+// Optional events attached to the dispatch of the chunk kernel (measurement hook, per host
+// thread): start is stamped when the kernel begins to execute, stop when it has finished.
+static thread_local hipEvent_t t_prof_begin = nullptr;
+static thread_local hipEvent_t t_prof_end = nullptr;
+
+template <class Kernel, class... Args>
+static void launch_timed(Kernel kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                         Args... args)
+{
+    if (t_prof_begin)
+        hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)lds, st, t_prof_begin,
+                              t_prof_end, 0, args...);
+    else
+        kernel<<<grid, block, lds, st>>>(args...);
+}
+
 template <class Policy, bool PAIRS>
 static int launch_persistent(AttnParams p, int batch, hipStream_t st)
 {
@@ -175,7 +193,7 @@ static int launch_persistent(AttnParams p, int batch, hipStream_t st)
     int64_t G = (int64_t)cus * occ;
     const int64_t enough = (max_items + NW - 1) / NW;     // one item per streaming wave
     if (G > enough) G = enough;
-    kernel<<<dim3((unsigned)G), (NW + 1) * 64, lds, st>>>(p, batch);
+    launch_timed(kernel, dim3((unsigned)G), dim3((NW + 1) * 64), lds, st, p, batch);
     return HETIS_OK;
 }
 
@@ -191,7 +209,7 @@ static int launch_chunk(const AttnParams &p, int batch, hipStream_t st)
     if (batch > kMaxPersistBatch || p.n_sel > kMaxPersistHeads || max_items >= (int64_t)1 << 31) {
         if (batch > 65535 || p.n_sel > 65535) return HETIS_ERR_UNSUPPORTED;   // grid limits
         dim3 grid(p.max_chunks, p.n_sel, batch);
-        attn_chunk_vec_kernel<D, R, kVecWaves><<<grid, kVecWaves * 64, 0, st>>>(p);
+        launch_timed(attn_chunk_vec_kernel<D, R, kVecWaves>, grid, dim3(kVecWaves * 64), 0, st, p);
         return HETIS_OK;
     }
     if constexpr (R >= 4)
@@ -212,17 +230,9 @@ static int dispatch_chunks(const AttnParams &p, int D, int r, int batch, hipStre
     return HETIS_ERR_UNSUPPORTED;
 }
 
-// Optional events around the chunk-kernel launch (measurement hook, per host thread).
-static thread_local hipEvent_t t_prof_begin = nullptr;
-static thread_local hipEvent_t t_prof_end = nullptr;
-
 static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
 {
-    if (t_prof_begin && hipEventRecord(t_prof_begin, st) != hipSuccess) return HETIS_ERR_LAUNCH;
-    const int rc = dispatch_chunks(p, D, r, batch, st);
-    if (rc != HETIS_OK) return rc;
-    if (t_prof_end && hipEventRecord(t_prof_end, st) != hipSuccess) return HETIS_ERR_LAUNCH;
-    return HETIS_OK;
+    return dispatch_chunks(p, D, r, batch, st);
 }
 
 // `batch`: sequences, or pairs in pairs mode (p.n_sel is 1 there)

@@ -2,6 +2,8 @@
 // Argument errors are reported before the first HIP call.
 #include "../../include/hetis_kv.h"
 
+#include <hip/hip_ext.h>
+
 #include "kv_cache.hpp"
 
 namespace hetis {
@@ -45,24 +47,20 @@ static int check_pool(const hetis_kv_pool *pl, KvChecked *c)
     return HETIS_OK;
 }
 
-// Optional events around the kernel launch (measurement hook, per host thread).
+// Optional events attached to the kernel's dispatch (measurement hook, per host thread):
+// start is stamped when the kernel begins to execute, stop when it has finished.
 static thread_local hipEvent_t t_kv_begin = nullptr;
 static thread_local hipEvent_t t_kv_end = nullptr;
 
-struct ProfileScope {
-    hipStream_t st;
-    bool ok;
-    explicit ProfileScope(hipStream_t s) : st(s), ok(true)
-    {
-        if (t_kv_begin && hipEventRecord(t_kv_begin, st) != hipSuccess) ok = false;
-    }
-    int finish()
-    {
-        if (t_kv_end && hipEventRecord(t_kv_end, st) != hipSuccess) ok = false;
-        if (hipGetLastError() != hipSuccess) ok = false;
-        return ok ? HETIS_OK : HETIS_ERR_LAUNCH;
-    }
-};
+template <class Kernel, class Params>
+static int launch_kv(Kernel kernel, dim3 grid, hipStream_t st, const Params &p)
+{
+    if (t_kv_begin)
+        hipExtLaunchKernelGGL(kernel, grid, dim3(256), 0, st, t_kv_begin, t_kv_end, 0, p);
+    else
+        kernel<<<grid, 256, 0, st>>>(p);
+    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
 
 // Threads of one launch of the row kernel are spread over entries (x) and, while the grid
 // is small, over the selected heads (y), so that a decode-step store of a few thousand rows
@@ -81,19 +79,11 @@ static int launch_rows(bool fetch, const hetis_attn_shape *s, const KvChecked &c
     p.stride_block = c.stride_block / 8;
     p.stride_head = c.stride_head / 8;
     const dim3 grid((unsigned)gx, (unsigned)gy);
-    ProfileScope scope(st);
-    if (D == 128) {
-        if (fetch)
-            kv_rows_kernel<128, true><<<grid, 256, 0, st>>>(p);
-        else
-            kv_rows_kernel<128, false><<<grid, 256, 0, st>>>(p);
-    } else {
-        if (fetch)
-            kv_rows_kernel<64, true><<<grid, 256, 0, st>>>(p);
-        else
-            kv_rows_kernel<64, false><<<grid, 256, 0, st>>>(p);
-    }
-    return scope.finish();
+    if (D == 128)
+        return fetch ? launch_kv(kv_rows_kernel<128, true>, grid, st, p)
+                     : launch_kv(kv_rows_kernel<128, false>, grid, st, p);
+    return fetch ? launch_kv(kv_rows_kernel<64, true>, grid, st, p)
+                 : launch_kv(kv_rows_kernel<64, false>, grid, st, p);
 }
 
 static int rows_call(bool fetch, const hetis_attn_shape *shape, const void *rows_k,
@@ -207,12 +197,9 @@ int hetis_kv_copy_tiles(const hetis_kv_pool *src_pool, const void *src_k, const 
     int64_t wgs = (p.n_items + 3) / 4;
     if (wgs > kKvCopyMaxWorkgroups) wgs = kKvCopyMaxWorkgroups;
     const hipStream_t st = (hipStream_t)stream;
-    ProfileScope scope(st);
     if (src_pool->head_dim == 128)
-        kv_copy_tiles_kernel<128><<<dim3((unsigned)wgs), 256, 0, st>>>(p);
-    else
-        kv_copy_tiles_kernel<64><<<dim3((unsigned)wgs), 256, 0, st>>>(p);
-    return scope.finish();
+        return launch_kv(kv_copy_tiles_kernel<128>, dim3((unsigned)wgs), st, p);
+    return launch_kv(kv_copy_tiles_kernel<64>, dim3((unsigned)wgs), st, p);
 }
 
 int hetis_kv_profile_events(void *begin, void *end)
