@@ -230,3 +230,18 @@ def kv_copy_tiles(src_k, src_v, dst_k, dst_v, src_blocks, dst_blocks, src_heads,
     if rc != 0:
         raise RuntimeError(f"oracle_kv_copy_tiles failed: {rc}")
     return dk, dv
+
+
+# ---------------------------------------------------------------- Profiler model (Eq. (3))
+
+def profiler_fit(h, g, tau):
+    """Least-squares (a, b, c) of tau = a*h + b*g + c (Section 5.1, Eq. (3)) and the mean
+    relative accuracy 1 - mean |prediction - tau| / tau on the samples.  The definition,
+    written with numpy's least-squares routine on the plain design matrix [h, g, 1]."""
+    h, g, tau = (np.asarray(x, dtype=np.float64) for x in (h, g, tau))
+    X = np.stack([h, g, np.ones_like(h)], axis=1)
+    abc, _, rank, _ = np.linalg.lstsq(X, tau, rcond=None)
+    if rank < 3:
+        raise ValueError("samples do not determine a, b, c")
+    acc = 1.0 - float(np.mean(np.abs(X @ abc - tau) / tau))
+    return abc, acc

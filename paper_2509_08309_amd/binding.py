@@ -91,6 +91,10 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_decode_pairs.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
     lib.hetis_attn_validate_pairs.restype = C.c_int
     lib.hetis_attn_validate_pairs.argtypes = [shp, vp, vp, vp, vp, i32, i64, vp]
+    lib.hetis_profiler_fit.restype = C.c_int
+    lib.hetis_profiler_fit.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.hetis_profiler_predict.restype = C.c_int
+    lib.hetis_profiler_predict.argtypes = [vp, vp, vp, i32, vp]
     pool = C.POINTER(hetis_kv_pool)
     lib.hetis_kv_append.restype = C.c_int
     lib.hetis_kv_append.argtypes = [shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
@@ -107,12 +111,14 @@ def load(build_if_missing: bool = False):
 
 
 def _ptr(t) -> Optional[int]:
-    """Device (or host) address of a torch tensor / raw int / None."""
+    """Device (or host) address of a torch tensor / numpy array / raw int / None."""
     if t is None:
         return None
     if isinstance(t, int):
         return t
-    return t.data_ptr()
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data            # numpy array (host pointer)
 
 
 def _stream(stream) -> Optional[int]:
@@ -248,6 +254,17 @@ def hetis_kv_copy_tiles(src_pool, src_k, src_v, dst_pool, dst_k, dst_v, src_bloc
 def hetis_kv_profile_events(begin, end) -> int:
     """begin/end: raw hipEvent_t handles (ints) or None."""
     return load().hetis_kv_profile_events(begin, end)
+
+
+def hetis_profiler_fit(h, g, tau, n, abc, accuracy=None) -> int:
+    """h, g, tau, abc: contiguous float64 numpy arrays (host); accuracy: ctypes.c_double or None."""
+    acc = None if accuracy is None else C.byref(accuracy)
+    return load().hetis_profiler_fit(_ptr(h), _ptr(g), _ptr(tau), int(n), _ptr(abc),
+                                     C.cast(acc, C.c_void_p) if acc is not None else None)
+
+
+def hetis_profiler_predict(abc, h, g, n, tau_out) -> int:
+    return load().hetis_profiler_predict(_ptr(abc), _ptr(h), _ptr(g), int(n), _ptr(tau_out))
 
 
 def check(status: int, where: str = "hetis_attn") -> None:

@@ -22,7 +22,7 @@ def declared_functions():
         if fn.endswith(".h"):
             text = open(os.path.join(ROOT, "include", fn)).read()
             text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-            names += re.findall(r"\b(hetis_(?:attn|kv)_\w+)\s*\(", text)
+            names += re.findall(r"\b(hetis_(?:attn|kv|profiler)_\w+)\s*\(", text)
     return sorted(set(names))
 
 

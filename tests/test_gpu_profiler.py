@@ -1,0 +1,35 @@
+"""The Profiler's offline run (Section 5.1, Eq. (3)) on a reduced grid: the sweep runs through
+hetis_attn_decode_pairs, the fit through hetis_profiler_fit, and the model has the properties
+the paper's dispatcher relies on (time grows with the cache amount, does not depend on how
+many requests the heads belong to)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_08309_amd import profiler
+
+pytestmark = pytest.mark.gpu
+
+
+def test_reduced_sweep_and_fit():
+    rec = profiler.run("13b", reps=5, h_values=(128, 512, 1536),
+                       g_values=(256 * 1024, 1024 * 1024, 2048 * 1024))
+    assert rec["n_points"] == 9
+    assert rec["b_us_per_token_head"] > 0
+    # 512 B per unit of g: the slope is a bandwidth; it must lie between 2 and 8 TB/s
+    assert 2000 < rec["b_as_GBps"] < 8000
+    assert rec["accuracy"] > 0.85
+    assert rec["fig7a_requests"]["spread"] < 0.15
+    assert rec["fig7b_r2_linear_in_g"] > 0.98
+    assert rec["held_out_ragged"]["accuracy"] > 0.8
+    # the library's fit is the checker's fit on the measured points
+    pts = rec["points"]
+    h = [p["h"] for p in pts]
+    g = [p["g"] for p in pts]
+    tau = [p["tau_us"] for p in pts]
+    ref, _ = oracle.profiler_fit(h, g, tau)
+    got = np.array([rec["a_us_per_query_head"], rec["b_us_per_token_head"], rec["c_us"]])
+    # tau was rounded to 0.01 us in the record: compare predictions, loosely
+    hh, gg = np.asarray(h, float), np.asarray(g, float)
+    assert np.allclose(got[0] * hh + got[1] * gg + got[2], ref[0] * hh + ref[1] * gg + ref[2],
+                       rtol=1e-3, atol=0.05)
