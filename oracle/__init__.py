@@ -245,3 +245,11 @@ def profiler_fit(h, g, tau):
         raise ValueError("samples do not determine a, b, c")
     acc = 1.0 - float(np.mean(np.abs(X @ abc - tau) / tau))
     return abc, acc
+
+
+# ---------------------------------------------------------------- Dispatcher (Eq. (7))
+
+def dispatch(devices, lengths, n_heads, r):
+    """See oracle/dispatch_oracle.py."""
+    from . import dispatch_oracle
+    return dispatch_oracle.dispatch(devices, lengths, n_heads, r)

@@ -1,0 +1,130 @@
+"""The Dispatcher's head-wise division (Section 5.2.2, Eq. (7)): pins of the checker, then the
+library's solver (host C ABI) against the checker.  No GPU needed."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import dispatch_oracle as DO
+
+
+def dev(a=0.001, b=1e-4, c=10.0, h=0.0, g=0.0, capacity=1e9, primary=True, gamma=0.0, beta=0.0):
+    return dict(a=a, b=b, c=c, h=h, g=g, capacity=capacity, primary=primary, gamma=gamma, beta=beta)
+
+
+# ---------------------------------------------------------------- pins of the checker
+
+def test_single_device_takes_everything():
+    d = [dev(h=100, g=5000)]
+    l = [300, 50]
+    z, x, xh, zr = DO.dispatch(d, l, 32, 1)
+    want = 0.001 * (100 + 64) + 1e-4 * (5000 + 2 * (300 + 50) * 32) + 10
+    assert abs(z - want) < 1e-9 and abs(zr - want) < 1e-9
+    assert np.array_equal(xh, [[32], [32]])
+
+
+def test_identical_idle_devices_split_evenly():
+    N, H, r = 4, 32, 1
+    d = [dev() for _ in range(N)]
+    l = [1000.0]
+    z, x, xh, zr = DO.dispatch(d, l, H, r)
+    want = 0.001 * H / N + 1e-4 * 2 * 1000 * H / N + 10
+    assert abs(z - want) < 1e-9
+    assert np.array_equal(xh, [[8, 8, 8, 8]]) and abs(zr - want) < 1e-9
+
+
+def test_two_devices_equalise_their_times():
+    """One request, ample capacity: the optimum puts both devices at the same time; solved by
+    hand from K1 + s1 x = K2 + s2 (H - x)."""
+    d = [dev(b=1e-4, c=5.0, h=50, g=2e5), dev(b=3e-4, c=8.0, h=10, g=1e4)]
+    H, r, l = 64, 1, 2000.0
+    A, b, K, _ = DO.device_terms(d, r)
+    s = A + b * 2 * l
+    x1 = (K[1] - K[0] + s[1] * H) / (s[0] + s[1])
+    assert 0 < x1 < H
+    z, x, xh, zr = DO.dispatch(d, [l], H, r)
+    assert abs(z - (K[0] + s[0] * x1)) < 1e-8
+    assert abs(x[0, 0] - x1) < 1e-6
+    assert xh.sum() == H and zr >= z - 1e-12
+    # rounding moved at most one head: the rounded time is within one head's cost
+    assert zr - z <= s.max() + 1e-9
+
+
+def test_attention_worker_pays_for_the_transfer():
+    """Same device parameters, one is an Attention worker with a link cost: it gets fewer heads."""
+    d = [dev(primary=True), dev(primary=False, gamma=0.01, beta=3.0)]
+    z, x, xh, zr = DO.dispatch(d, [500.0], 40, 1)
+    assert x[0, 0] > x[0, 1]
+    A, b, K, _ = DO.device_terms(d, 1)
+    assert abs(A[1] - (0.001 + 4 * 0.01)) < 1e-15 and abs(K[1] - 13.0) < 1e-12
+
+
+def test_capacity_binds_and_infeasible():
+    # device 0 is much faster but can hold only 1/4 of the request
+    l, H, r = 1000.0, 32, 1
+    d = [dev(b=1e-5, capacity=2 * l * 8), dev(b=1e-3)]
+    z, x, xh, zr = DO.dispatch(d, [l], H, r)
+    assert abs(x[0, 0] - 8) < 1e-7 and np.array_equal(xh, [[8, 24]])
+    # existing cache counts against the capacity
+    d[0]["g"] = 2 * l * 4
+    z2, x2, _, _ = DO.dispatch(d, [l], H, r)
+    assert abs(x2[0, 0] - 4) < 1e-7 and z2 > z
+    # nothing fits
+    assert DO.dispatch([dev(capacity=10.0), dev(capacity=10.0)], [l], H, r) is None
+
+
+def test_groups_of_r_and_brute_force_on_a_tiny_instance():
+    """r = 4, two requests, two devices: the rounded division is whole groups; the LP value is
+    a lower bound of, and close to, the best whole-group division found by enumeration."""
+    r, H = 4, 16
+    d = [dev(a=0.002, b=2e-4, c=4.0, h=16, g=3000), dev(a=0.001, b=5e-4, c=6.0)]
+    l = [700.0, 150.0]
+    z, x, xh, zr = DO.dispatch(d, l, H, r)
+    assert (xh % r == 0).all() and (xh.sum(axis=1) == H).all() and (xh >= 0).all()
+    best = min(DO.times(d, l, r, [[4 * u0, H - 4 * u0], [4 * u1, H - 4 * u1]]).max()
+               for u0, u1 in itertools.product(range(5), repeat=2))
+    assert z <= best + 1e-9
+    assert zr >= best - 1e-9
+    A, b, K, _ = DO.device_terms(d, r)
+    one_group = (A + b * (2 / r) * max(l)).max() * r
+    assert zr - z <= 2 * one_group            # at most one group per request moved by rounding
+
+
+def test_rounding_repairs_capacity():
+    r, H = 1, 8
+    l = [100.0, 100.0]
+    # LP optimum fills device 0 exactly with 4.5 + 4.5 heads; rounding up both would overflow
+    d = [dev(b=1e-5, capacity=2 * 100 * 9), dev(b=1e-3)]
+    z, x, xh, zr = DO.dispatch(d, l, H, r)
+    assert abs(x[:, 0].sum() - 9) < 1e-6
+    assert (2 * 100 * xh[:, 0]).sum() <= 2 * 100 * 9 + 1e-9
+    assert (xh.sum(axis=1) == H).all()
+
+
+def random_instance(rng, N, J, r):
+    H = r * int(rng.integers(2, 9))
+    d = [dev(a=float(rng.uniform(0, 0.01)), b=float(rng.uniform(5e-5, 5e-4)),
+             c=float(rng.uniform(2, 30)), h=float(rng.integers(0, 500)),
+             g=float(rng.integers(0, 200000)), capacity=float(rng.integers(300000, 2000000)),
+             primary=bool(i == 0), gamma=float(rng.uniform(0, 0.005)), beta=float(rng.uniform(0, 5)))
+         for i in range(N)]
+    l = rng.integers(16, 8000, size=J).astype(np.float64)
+    return d, l, H
+
+
+def test_lp_value_is_a_lower_bound_of_any_feasible_division():
+    rng = np.random.default_rng(81)
+    for _ in range(20):
+        N, J, r = int(rng.integers(2, 5)), int(rng.integers(1, 6)), int(rng.choice([1, 2, 8]))
+        d, l, H = random_instance(rng, N, J, r)
+        sol = DO.solve_lp(d, l, H, r)
+        if sol is None:
+            continue
+        z, x = sol
+        assert np.allclose(x.sum(axis=1), H, atol=1e-7) and (x >= -1e-9).all()
+        assert abs(DO.times(d, l, r, x).max() - z) < 1e-7 * max(1.0, abs(z))
+        _, _, _, cap = DO.device_terms(d, r)
+        for _ in range(30):                      # random feasible points are never better
+            w = rng.dirichlet(np.ones(N), size=J) * H
+            if ((2 / r) * (l[:, None] * w).sum(axis=0) <= cap).all():
+                assert DO.times(d, l, r, w).max() >= z - 1e-7 * max(1.0, abs(z))
