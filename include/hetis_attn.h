@@ -69,7 +69,8 @@ enum {
     HETIS_ERR_WORKSPACE = -5,   /* max_seq_len inconsistent with the shape / chunking */
     HETIS_ERR_LAUNCH = -6,      /* HIP reported an error when launching */
     HETIS_ERR_ALLOC = -7,       /* the internal workspace could not be allocated */
-    HETIS_ERR_BAD_CONTENT = -8  /* hetis_attn_validate found an out-of-range value */
+    HETIS_ERR_BAD_CONTENT = -8, /* hetis_attn_validate found an out-of-range value */
+    HETIS_ERR_INFEASIBLE = -9   /* hetis_dispatch_solve: the capacities cannot hold the requests */
 };
 
 typedef struct {

@@ -25,6 +25,7 @@ HETIS_ERR_WORKSPACE = -5
 HETIS_ERR_LAUNCH = -6
 HETIS_ERR_ALLOC = -7
 HETIS_ERR_BAD_CONTENT = -8
+HETIS_ERR_INFEASIBLE = -9
 
 
 class hetis_attn_shape(C.Structure):
@@ -38,6 +39,12 @@ class hetis_kv_pool(C.Structure):
     _fields_ = [("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_size", C.c_int32),
                 ("reserved", C.c_int32), ("num_blocks", C.c_int64),
                 ("kv_stride_block", C.c_int64), ("kv_stride_head", C.c_int64)]
+
+
+class hetis_dispatch_device(C.Structure):
+    _fields_ = [("a", C.c_double), ("b", C.c_double), ("c", C.c_double), ("gamma", C.c_double),
+                ("beta", C.c_double), ("h", C.c_double), ("g", C.c_double),
+                ("capacity", C.c_double), ("is_primary", C.c_int32), ("reserved", C.c_int32)]
 
 
 class HetisError(RuntimeError):
@@ -91,6 +98,8 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_decode_pairs.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
     lib.hetis_attn_validate_pairs.restype = C.c_int
     lib.hetis_attn_validate_pairs.argtypes = [shp, vp, vp, vp, vp, i32, i64, vp]
+    lib.hetis_dispatch_solve.restype = C.c_int
+    lib.hetis_dispatch_solve.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.hetis_profiler_fit.restype = C.c_int
     lib.hetis_profiler_fit.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.hetis_profiler_predict.restype = C.c_int
@@ -265,6 +274,17 @@ def hetis_profiler_fit(h, g, tau, n, abc, accuracy=None) -> int:
 
 def hetis_profiler_predict(abc, h, g, n, tau_out) -> int:
     return load().hetis_profiler_predict(_ptr(abc), _ptr(h), _ptr(g), int(n), _ptr(tau_out))
+
+
+def hetis_dispatch_solve(devices, n_devices, lengths, n_requests, n_heads, group, x_frac, x_heads,
+                         z_lp=None, z_rounded=None) -> int:
+    """devices: ctypes array of hetis_dispatch_device (or None); lengths, x_frac: float64 numpy
+    arrays; x_heads: int32 numpy array; z_lp, z_rounded: ctypes.c_double or None."""
+    dp = None if devices is None else C.cast(devices, C.c_void_p)
+    ref = lambda v: None if v is None else C.cast(C.byref(v), C.c_void_p)
+    return load().hetis_dispatch_solve(dp, int(n_devices), _ptr(lengths), int(n_requests),
+                                       int(n_heads), int(group), _ptr(x_frac), _ptr(x_heads),
+                                       ref(z_lp), ref(z_rounded))
 
 
 def check(status: int, where: str = "hetis_attn") -> None:

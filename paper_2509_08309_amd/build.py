@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhetis_attn.so")
-SOURCES = ["hetis_attn.hip", "hetis_kv.hip", "hetis_profiler.hip"]
+SOURCES = ["hetis_attn.hip", "hetis_kv.hip", "hetis_profiler.hip", "hetis_dispatch.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
@@ -20,7 +20,7 @@ def sources():
     for root, _, files in os.walk(CSRC):
         out += [os.path.join(root, f) for f in files if f.endswith((".hip", ".hpp", ".h"))]
     inc = os.path.join(os.path.dirname(HERE), "include")
-    out += [os.path.join(inc, f) for f in ("hetis_attn.h", "hetis_kv.h", "hetis_profiler.h")]
+    out += [os.path.join(inc, f) for f in ("hetis_attn.h", "hetis_kv.h", "hetis_profiler.h", "hetis_dispatch.h")]
     return out
 
 

@@ -322,6 +322,7 @@ const char *hetis_attn_status_string(int status)
     case HETIS_ERR_LAUNCH: return "kernel launch failed";
     case HETIS_ERR_ALLOC: return "internal workspace allocation failed";
     case HETIS_ERR_BAD_CONTENT: return "device-side argument content out of range";
+    case HETIS_ERR_INFEASIBLE: return "capacities cannot hold the requests";
     default: return "unknown status";
     }
 }

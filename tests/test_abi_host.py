@@ -22,7 +22,7 @@ def declared_functions():
         if fn.endswith(".h"):
             text = open(os.path.join(ROOT, "include", fn)).read()
             text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-            names += re.findall(r"\b(hetis_(?:attn|kv|profiler)_\w+)\s*\(", text)
+            names += re.findall(r"\b(hetis_(?:attn|kv|profiler|dispatch)_\w+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -36,8 +36,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert H.hetis_attn_version() >= 100
-    seen = {H.hetis_attn_status_string(s) for s in range(0, -9, -1)}
-    assert len(seen) == 9 and "unknown status" not in seen
+    seen = {H.hetis_attn_status_string(s) for s in range(0, -10, -1)}
+    assert len(seen) == 10 and "unknown status" not in seen
     assert H.hetis_attn_status_string(-99) == "unknown status"
 
 

@@ -128,3 +128,100 @@ def test_lp_value_is_a_lower_bound_of_any_feasible_division():
             w = rng.dirichlet(np.ones(N), size=J) * H
             if ((2 / r) * (l[:, None] * w).sum(axis=0) <= cap).all():
                 assert DO.times(d, l, r, w).max() >= z - 1e-7 * max(1.0, abs(z))
+
+
+# ---------------------------------------------------------------- library against the checker
+
+import ctypes as C
+
+import paper_2509_08309_amd as H
+from paper_2509_08309_amd import binding
+
+
+def lib_dispatch(devices, lengths, n_heads, r):
+    binding.load(build_if_missing=True)
+    N, J = len(devices), len(lengths)
+    arr = (H.hetis_dispatch_device * N)()
+    for i, d in enumerate(devices):
+        arr[i] = H.hetis_dispatch_device(d["a"], d["b"], d["c"], d.get("gamma", 0.0),
+                                         d.get("beta", 0.0), d.get("h", 0.0), d.get("g", 0.0),
+                                         d["capacity"], 1 if d.get("primary", False) else 0, 0)
+    l = np.ascontiguousarray(lengths, dtype=np.float64)
+    xf = np.zeros((J, N))
+    xh = np.zeros((J, N), dtype=np.int32)
+    z, zr = C.c_double(0), C.c_double(0)
+    rc = H.hetis_dispatch_solve(arr, N, l, J, n_heads, r, xf, xh, z, zr)
+    return rc, z.value, xf, xh, zr.value
+
+
+def check_against_checker(d, l, H_, r):
+    rc, z, xf, xh, zr = lib_dispatch(d, l, H_, r)
+    ref = DO.solve_lp(d, l, H_, r)
+    if ref is None:
+        assert rc == binding.HETIS_ERR_INFEASIBLE
+        return None
+    assert rc == 0
+    z_ref, _ = ref
+    tol = 1e-7 * max(1.0, abs(z_ref))
+    assert abs(z - z_ref) <= tol, (z, z_ref)
+    # the library's fractional division is feasible and attains its own optimum
+    _, _, _, cap = DO.device_terms(d, r)
+    l = np.asarray(l, dtype=np.float64)
+    assert (xf >= -1e-9).all() and np.allclose(xf.sum(axis=1), H_, atol=1e-6)
+    assert ((2 / r) * (l[:, None] * xf).sum(axis=0) <= cap * (1 + 1e-9) + 1e-6).all()
+    assert abs(DO.times(d, l, r, xf).max() - z) <= 10 * tol
+    # rounding: the stated rule applied by the checker to the same fractional division
+    want = DO.round_to_groups(d, l, H_, r, xf)
+    assert want is not None and np.array_equal(xh, want)
+    assert (xh % r == 0).all() and (xh.sum(axis=1) == H_).all()
+    assert abs(zr - DO.times(d, l, r, xh).max()) <= 1e-9 * max(1.0, abs(zr))
+    return z
+
+
+def test_library_on_the_pinned_cases():
+    check_against_checker([dev(h=100, g=5000)], [300, 50], 32, 1)
+    check_against_checker([dev() for _ in range(4)], [1000.0], 32, 1)
+    check_against_checker([dev(b=1e-4, c=5.0, h=50, g=2e5), dev(b=3e-4, c=8.0, h=10, g=1e4)],
+                          [2000.0], 64, 1)
+    check_against_checker([dev(primary=True), dev(primary=False, gamma=0.01, beta=3.0)], [500.0], 40, 1)
+    check_against_checker([dev(b=1e-5, capacity=2 * 1000.0 * 8), dev(b=1e-3)], [1000.0], 32, 1)
+    check_against_checker([dev(a=0.002, b=2e-4, c=4.0, h=16, g=3000), dev(a=0.001, b=5e-4, c=6.0)],
+                          [700.0, 150.0], 16, 4)
+    check_against_checker([dev(b=1e-5, capacity=2 * 100 * 9), dev(b=1e-3)], [100.0, 100.0], 8, 1)
+    assert check_against_checker([dev(capacity=10.0), dev(capacity=10.0)], [1000.0], 32, 1) is None
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_library_on_random_instances(seed):
+    rng = np.random.default_rng(900 + seed)
+    for _ in range(6):
+        N, J, r = int(rng.integers(1, 7)), int(rng.integers(1, 25)), int(rng.choice([1, 2, 4, 8]))
+        d, l, H_ = random_instance(rng, N, J, r)
+        check_against_checker(d, l, H_, r)
+
+
+def test_library_with_the_fitted_mi355x_parameters():
+    """Four devices with the coefficients fitted on this kernel (one of them a Primary worker,
+    one half as fast, one almost full): 16 new requests of a 40-head model."""
+    fit = dict(a=0.00064, b=9.32e-5, c=15.4)
+    d = [dev(**fit, h=640, g=4e5, capacity=4e6, primary=True),
+         dev(**fit, h=320, g=1e5, capacity=4e6, primary=False, gamma=0.002, beta=8.0),
+         dev(a=0.0013, b=1.9e-4, c=20.0, h=0, g=0, capacity=2e6, primary=False, gamma=0.002, beta=8.0),
+         dev(**fit, h=900, g=3.7e6, capacity=4e6, primary=False, gamma=0.002, beta=8.0)]
+    rng = np.random.default_rng(82)
+    l = np.clip(np.round(np.exp(rng.normal(np.log(800), 0.8, size=16))), 32, 4096)
+    z = check_against_checker(d, l, 40, 1)
+    assert z is not None
+
+
+def test_library_argument_errors():
+    lib = binding.load(build_if_missing=True)
+    d = [dev(), dev()]
+    ok = lib_dispatch(d, [100.0], 8, 1)
+    assert ok[0] == 0
+    assert lib_dispatch(d, [100.0], 9, 2)[0] == binding.HETIS_ERR_BAD_SHAPE        # H % r
+    assert lib_dispatch(d, [0.0], 8, 1)[0] == binding.HETIS_ERR_BAD_SHAPE          # length <= 0
+    assert lib_dispatch(d, [np.nan], 8, 1)[0] == binding.HETIS_ERR_BAD_SHAPE
+    assert lib_dispatch([dev(capacity=-1.0)], [100.0], 8, 1)[0] == binding.HETIS_ERR_BAD_SHAPE
+    assert lib_dispatch([dev(g=50.0, capacity=10.0)], [100.0], 8, 1)[0] == binding.HETIS_ERR_INFEASIBLE
+    assert lib.hetis_dispatch_solve(None, 1, None, 1, 8, 1, None, None, None, None) == binding.HETIS_ERR_NULL
