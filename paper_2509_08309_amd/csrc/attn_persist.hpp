@@ -12,8 +12,9 @@
 // Work distribution: the first two items of a streaming wave are fixed by its number; the
 // rest come from a global ticket counter, so that waves which drew short chunks simply take
 // more of them.  Tickets are drawn by the workgroup's writer wave, eight per device atomic
-// while plenty of work is left and fewer towards the end, into a small LDS pool from which
-// the streaming waves take them with an LDS atomic shortly before they finish an item.  Which wave computes an item has no
+// while plenty of work is left and fewer towards the end, decoded there (one ticket per
+// lane), and put into a small LDS pool from which the streaming waves take them, ready to
+// use, with an LDS atomic shortly before they finish an item.  Which wave computes an item has no
 // influence on the item's arithmetic.  The ticket counter and a counter of finished
 // workgroups live in a small device buffer (AttnParams::tickets); the workgroup that
 // finishes last sets both back to zero for the next launch.
@@ -55,11 +56,22 @@ constexpr int kSpinLimit = 1 << 22;     // polls before a wait gives up (far bey
 constexpr int kPoolSize = 32;           // item numbers the LDS ticket pool can hold
 constexpr int kTicketBatch = 8;         // tickets per device atomic
 
-// Item numbers waiting to be taken by the streaming waves of one workgroup.
+// An item, decoded: what a streaming wave needs to start on it.
+struct ItemDesc {
+    int b, c, si, g;    // enumeration row (sequence, or pair), chunk, position in head_ids, KV head
+    int seq;            // sequence whose query rows and output rows the item uses
+    int n_tok;          // tokens of the chunk
+    int flags;          // kItemExists | kItemToOut | kItemZero
+    int pad;
+};
+enum : int { kItemExists = 1, kItemToOut = 2, kItemZero = 4 };
+
+// Items waiting to be taken by the streaming waves of one workgroup, already decoded by the
+// writer wave.
 struct TicketPool {
-    int next;               // entries taken so far  (LDS atomic, streaming waves)
-    int end;                // entries published so far (written by the writer wave)
-    int items[kPoolSize];   // ring: entry i lives in items[i % kPoolSize]
+    int next;                   // entries taken so far  (LDS atomic, streaming waves)
+    int end;                    // entries published so far (written by the writer wave)
+    ItemDesc desc[kPoolSize];   // ring: entry i lives in desc[i % kPoolSize]
 };
 
 // One finished item on its way to global memory.
@@ -274,6 +286,54 @@ __global__ __launch_bounds__((NW + 1) * 64)
     const int total = class_end[3] * n_sel;
     const int stride = gridDim.x * NW;                        // streaming waves in the grid
 
+    // item number -> (row, chunk, head): whole chunks come first, ragged last chunks after
+    // them by size class; binary search in the matching running-count table.  Works per lane
+    // (the writer wave decodes a batch of tickets at once, one per lane).
+    auto upper = [&](const int *tab, int key) {               // last b with tab[b] <= key
+        int lo = 0, hi = batch - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (tab[mid] <= key)
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        return lo;
+    };
+    auto decode = [&](int item) {
+        ItemDesc d;
+        d.flags = item < total ? kItemExists : 0;
+        const int w = min(item, max(total - 1, 0));
+        const int cg = PAIRS ? w : w / n_sel;
+        d.si = PAIRS ? 0 : w - cg * n_sel;
+        int L;
+        if (cg < totalF) {
+            d.b = upper(firstF, cg);
+            d.c = cg - firstF[d.b];
+            L = lens[d.b];
+            d.n_tok = p.chunk_tokens;
+        } else {
+            int k = 0, begin = totalF;
+#pragma unroll
+            for (int j = 0; j < 3; ++j)
+                if (cg >= class_end[j]) {
+                    k = j + 1;
+                    begin = class_end[j];
+                }
+            d.b = upper(firstT + k * (batch + 1), cg - begin);
+            L = lens[d.b];
+            d.c = L > 0 ? L / p.chunk_tokens : 0;
+            d.n_tok = L > 0 ? L - d.c * p.chunk_tokens : 0;
+        }
+        d.g = hids[PAIRS ? d.b : d.si];
+        d.seq = PAIRS ? pseq[d.b] : d.b;
+        const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
+        if (p.direct_single && n_chunks <= 1) d.flags |= kItemToOut;
+        if (L <= 0) d.flags |= kItemZero;
+        d.pad = 0;
+        return d;
+    };
+
     if (wave == NW) {
         // ------------------------------------------------------------ writer wave
         int next_box[NW];
@@ -292,21 +352,22 @@ __global__ __launch_bounds__((NW + 1) * 64)
             // batch size shrinks as the work runs out (judged by the last ticket seen), so
             // that the last items are not parked in one workgroup's pool
             const long long left = (long long)total - last_base;
-            const int batch = left > 16ll * stride ? kTicketBatch : (left > 4ll * stride ? 2 : 1);
-            if (pool_end - taken < batch) {
+            const int n_draw = left > 16ll * stride ? kTicketBatch : (left > 4ll * stride ? 2 : 1);
+            if (pool_end - taken < n_draw) {
                 long long base = total;   // past the last item: "no more work"
                 if (!exhausted) {
                     unsigned t = 0;
                     if (lane == 0)
-                        t = __hip_atomic_fetch_add(p.tickets, (unsigned)batch, __ATOMIC_RELAXED,
+                        t = __hip_atomic_fetch_add(p.tickets, (unsigned)n_draw, __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT);
                     base = 2ll * stride + __builtin_amdgcn_readfirstlane(t);
                     last_base = base;
-                    if (base + batch >= total) exhausted = true;
+                    if (base + n_draw >= total) exhausted = true;
                 }
-                if (lane < batch)
-                    pool.items[(pool_end + lane) % kPoolSize] = (int)min(base + lane, (long long)total);
-                pool_end += batch;
+                if (lane < n_draw)
+                    pool.desc[(pool_end + lane) % kPoolSize] =
+                        decode((int)min(base + lane, (long long)total));
+                pool_end += n_draw;
                 __hip_atomic_store(&pool.end, pool_end, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 progressed = true;
             }
@@ -346,69 +407,27 @@ __global__ __launch_bounds__((NW + 1) * 64)
     }
 
     // ---------------------------------------------------------------- streaming waves
-    // item number -> (sequence, chunk, head): whole chunks come first, ragged last chunks
-    // after them; binary search in the matching running-count table.  Item numbers of a wave
-    // only grow, so the last answer of each table is the lower end of the next search.
-    int cursorF = 0, cursorT[4] = {0, 0, 0, 0};
-    auto upper = [&](const int *tab, int key, int lo) {       // last b with tab[b] <= key
-        int hi = batch - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (tab[mid] <= key)
-                lo = mid;
-            else
-                hi = mid - 1;
-        }
-        return __builtin_amdgcn_readfirstlane(lo);
-    };
-    auto decode = [&](int w, ItemHdr &h) {
-        const int cg = PAIRS ? w : w / n_sel;
-        h.si = PAIRS ? 0 : w - cg * n_sel;
-        int L, n_tok;
-        if (cg < totalF) {
-            cursorF = upper(firstF, cg, cursorF);
-            h.b = cursorF;
-            h.c = __builtin_amdgcn_readfirstlane(cg - firstF[h.b]);
-            L = __builtin_amdgcn_readfirstlane(lens[h.b]);
-            n_tok = p.chunk_tokens;
-        } else {
-            int k = 0, begin = totalF;
-#pragma unroll
-            for (int j = 0; j < 3; ++j)
-                if (cg >= class_end[j]) {
-                    k = j + 1;
-                    begin = class_end[j];
-                }
-            // the four cursors live in registers: pick and update with selects, not indexing
-            int cur = k == 0 ? cursorT[0] : (k == 1 ? cursorT[1] : (k == 2 ? cursorT[2] : cursorT[3]));
-            cur = upper(firstT + k * (batch + 1), cg - begin, cur);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (j == k) cursorT[j] = cur;
-            h.b = cur;
-            L = __builtin_amdgcn_readfirstlane(lens[h.b]);
-            h.c = L > 0 ? L / p.chunk_tokens : 0;
-            n_tok = L > 0 ? L - h.c * p.chunk_tokens : 0;
-        }
-        h.g = __builtin_amdgcn_readfirstlane(hids[PAIRS ? h.b : h.si]);
-        h.seq = PAIRS ? __builtin_amdgcn_readfirstlane(pseq[h.b]) : h.b;
-        const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-        h.to_out = p.direct_single && n_chunks <= 1;
-        h.zero = L <= 0;
-        h.t0 = h.c * p.chunk_tokens;
-        h.nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
-        h.rem = n_tok & (kBlockTokens - 1);
-    };
     struct Slot {
         ItemHdr h;
         int ids;            // lane i: physical block of the item's i-th tile
         int64_t head_off;
         bool exists;
     };
-    auto fill = [&](int wi, Slot &s) {
-        s.exists = wi < total;
-        decode(min(wi, max(total - 1, 0)), s.h);
-        if (!s.exists) s.h.nblk = 0;
+    // decoded item -> the wave's (uniform) bookkeeping, and the load of its block ids
+    auto fill = [&](const ItemDesc &d, Slot &s) {
+        const int flags = __builtin_amdgcn_readfirstlane(d.flags);
+        const int n_tok = __builtin_amdgcn_readfirstlane(d.n_tok);
+        s.h.b = __builtin_amdgcn_readfirstlane(d.b);
+        s.h.c = __builtin_amdgcn_readfirstlane(d.c);
+        s.h.si = __builtin_amdgcn_readfirstlane(d.si);
+        s.h.g = __builtin_amdgcn_readfirstlane(d.g);
+        s.h.seq = __builtin_amdgcn_readfirstlane(d.seq);
+        s.exists = (flags & kItemExists) != 0;
+        s.h.to_out = (flags & kItemToOut) != 0;
+        s.h.zero = (flags & kItemZero) != 0;
+        s.h.t0 = s.h.c * p.chunk_tokens;
+        s.h.nblk = s.exists ? (n_tok + kBlockTokens - 1) / kBlockTokens : 0;
+        s.h.rem = n_tok & (kBlockTokens - 1);
         s.head_off = PAIRS ? 0 : (int64_t)s.h.g * p.stride_head;   // pairs: single-head tiles
         const int32_t *bt =
             p.block_table + (int64_t)s.h.b * p.max_blocks_per_seq + s.h.t0 / kBlockTokens;
@@ -430,7 +449,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             __builtin_amdgcn_s_sleep(2);
         }
     };
-    // next item number from the workgroup's ticket pool (`total` = none left)
+    // next item from the workgroup's pool, decoded by the writer wave (flags 0 = none left)
     auto take_ticket = [&]() {
         int i = 0;
         if (lane == 0)
@@ -439,10 +458,11 @@ __global__ __launch_bounds__((NW + 1) * 64)
         for (int spin = 0; spin < kSpinLimit; ++spin) {
             const int end = __builtin_amdgcn_readfirstlane(
                 __hip_atomic_load(&pool.end, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
-            if (end > i) return __builtin_amdgcn_readfirstlane(pool.items[i % kPoolSize]);
+            if (end > i) return pool.desc[i % kPoolSize];
             __builtin_amdgcn_s_sleep(2);
         }
-        return total;
+        ItemDesc none{};
+        return none;
     };
 
     const int w = blockIdx.x * NW + wave;
@@ -458,7 +478,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
     typename Policy::Query q;
     typename Policy::QueryPrefetch q_pre;
     Tile ring[RING];
-    fill(w, cur);                   // items w and w + stride are this wave's without a ticket
+    fill(decode(w), cur);           // items w and w + stride are this wave's without a ticket
     nxt = cur;
     Policy::q_prefetch(q_pre, q_rows(cur), lane);
 #pragma unroll
@@ -489,7 +509,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // out.
         int i = 0;
         for (; i + 4 * RING < lim; i += RING) steady_turn(i);
-        fill(n == 0 ? w + stride : take_ticket(), nxt);
+        fill(n == 0 ? decode(w + stride) : take_ticket(), nxt);
         Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next item's query rows
         for (; i + RING < lim; i += RING) steady_turn(i);
         // last turn of this item (the only place a ragged block can be): its refills are the
