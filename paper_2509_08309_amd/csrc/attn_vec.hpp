@@ -47,12 +47,19 @@ template <int D>
 __device__ __forceinline__ void tile_issue(TileRegs<D> &t, const __half *k_cache,
                                            const __half *v_cache, int64_t base, int lane)
 {
-    const uint4 *kp = reinterpret_cast<const uint4 *>(k_cache + base) + lane;
-    const uint4 *vp = reinterpret_cast<const uint4 *>(v_cache + base) + lane;
+    // non-temporal like the buffer loads of the persistent kernel: a tile is read once
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(k_cache + base) + lane;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(v_cache + base) + lane;
 #pragma unroll
-    for (int i = 0; i < TileRegs<D>::NI; ++i) t.k[i] = kp[i * 64];
+    for (int i = 0; i < TileRegs<D>::NI; ++i) {
+        const u32x4 x = __builtin_nontemporal_load(kp + i * 64);
+        t.k[i] = make_uint4(x.x, x.y, x.z, x.w);
+    }
 #pragma unroll
-    for (int i = 0; i < TileRegs<D>::NI; ++i) t.v[i] = vp[i * 64];
+    for (int i = 0; i < TileRegs<D>::NI; ++i) {
+        const u32x4 x = __builtin_nontemporal_load(vp + i * 64);
+        t.v[i] = make_uint4(x.x, x.y, x.z, x.w);
+    }
 }
 
 // One tile (16 tokens) of K and V held in registers -> update of the running state.
