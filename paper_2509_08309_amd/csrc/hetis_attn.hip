@@ -22,7 +22,7 @@ namespace hetis {
 #define HETIS_DECODE_CHUNK_TOKENS 256
 #endif
 #ifndef HETIS_DECODE_CHUNK_TOKENS_GQA
-#define HETIS_DECODE_CHUNK_TOKENS_GQA 512
+#define HETIS_DECODE_CHUNK_TOKENS_GQA 768
 #endif
 constexpr int decode_chunk_tokens(int group)
 {
