@@ -2,6 +2,7 @@
 accuracy"): time head-wise decode Attention over a grid of eight head counts h and eight
 cache amounts g, fit tau = a*h + b*g + c, and check the three properties the model rests on
 (Fig. 7: time independent of the number of requests at fixed (h, g); linear in g; linear in h).
+The grid is laid over (request, KV head) pairs, 64 to 2048 of them, i.e. h = r times that.
 
 Measurements go through hetis_attn_decode_pairs (the per-request head-subset entry point: h
 query heads spread over some requests, g cached tokens x KV heads in single-head tiles); the
@@ -20,7 +21,7 @@ import json
 
 import numpy as np
 
-H_VALUES = (64, 128, 256, 512, 768, 1024, 1536, 2048)            # query heads among requests
+H_VALUES = (64, 128, 256, 512, 768, 1024, 1536, 2048)            # (request, KV head) pairs; h = r times that
 G_VALUES = tuple(k * 1024 for k in (32, 64, 128, 256, 512, 1024, 1536, 2048))   # tokens x heads
 MODELS = {"13b": (40, 40, 128), "70b": (64, 8, 128)}             # Hq, Hkv, D
 
@@ -144,9 +145,11 @@ def r_squared(x, y):
     return 1.0 - float(res @ res) / float(((y - y.mean()) ** 2).sum())
 
 
-def run(model: str = "13b", reps: int = 7, h_values=H_VALUES, g_values=G_VALUES) -> dict:
-    bench = Bench(model, max(g_values) + 16 * max(h_values))
-    r = bench.r
+def run(model: str = "13b", reps: int = 7, h_values=None, g_values=G_VALUES) -> dict:
+    r = MODELS[model][0] // MODELS[model][1]
+    if h_values is None:
+        h_values = tuple(v * r for v in H_VALUES)       # query heads: r per (request, KV head)
+    bench = Bench(model, max(g_values) + 16 * max(h_values) // r)
     hs, gs, taus = [], [], []
     for h in h_values:
         for g in g_values:
@@ -175,10 +178,10 @@ def run(model: str = "13b", reps: int = 7, h_values=H_VALUES, g_values=G_VALUES)
                              "spread": float(v.max() / v.min() - 1.0)}
     # (b) linear in g at fixed h, (c) linear in h at fixed g
     hs_a, gs_a, ta = np.asarray(hs), np.asarray(gs), np.asarray(taus)
-    mh = hs_a == 512 if 512 in hs_a else hs_a == hs_a[len(hs_a) // 2]
+    mh = hs_a == 512 * r if 512 * r in hs_a else hs_a == hs_a[len(hs_a) // 2]
     rec["fig7b_r2_linear_in_g"] = r_squared(gs_a[mh], ta[mh])
     g_mid = sorted(set(g_values))[len(set(g_values)) // 2]
-    mg = np.abs(gs_a - g_mid) <= 16 * max(h_values)
+    mg = np.abs(gs_a - g_mid) <= 16 * max(h_values) // r
     # a straight line in h may well be flat here (a close to 0): report slope and spread too
     A = np.stack([hs_a[mg], np.ones(int(mg.sum()))], axis=1)
     slope_h = float(np.linalg.lstsq(A, ta[mg], rcond=None)[0][0])
