@@ -352,7 +352,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             // batch size shrinks as the work runs out (judged by the last ticket seen), so
             // that the last items are not parked in one workgroup's pool
             const long long left = (long long)total - last_base;
-            const int n_draw = left > 16ll * stride ? kTicketBatch : (left > 4ll * stride ? 2 : 1);
+            const int n_draw = left > 8ll * stride ? kTicketBatch : (left > 2ll * stride ? 2 : 1);
             if (pool_end - taken < n_draw) {
                 long long base = total;   // past the last item: "no more work"
                 if (!exhausted) {
