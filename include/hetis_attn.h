@@ -103,7 +103,8 @@ const char *hetis_attn_status_string(int status);
  *   n_sel_heads  host, 1 .. Hkv
  *   scale        host, normally 1/sqrt(D)
  *   out          fp16 [B, Hq, D]; rows of unselected heads are left untouched
- * Sequences longer than an internal fixed chunk (a compile-time constant) are
+ * Sequences longer than an internal fixed chunk (a compile-time constant: 256
+ * tokens for r < 4, 768 for r >= 4) are
  * processed as several chunks whose fp32 partial results go through a
  * workspace that the library owns: it is allocated with hipMalloc on the first
  * call on a device and grown when a call needs more (both synchronise the

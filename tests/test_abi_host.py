@@ -106,6 +106,9 @@ def test_split_argument_errors(lib):
     assert H.hetis_attn_split_num_chunks(100, 0) == binding.HETIS_ERR_UNSUPPORTED
     assert H.hetis_attn_split_num_chunks(100, 24) == binding.HETIS_ERR_UNSUPPORTED
     assert H.hetis_attn_split_num_chunks(0, 16) == binding.HETIS_ERR_WORKSPACE
+    # a wave keeps the block ids of a chunk in one register: at most 64 blocks = 1024 tokens
+    assert H.hetis_attn_split_num_chunks(4096, 1024) == 4
+    assert H.hetis_attn_split_num_chunks(4096, 1040) == binding.HETIS_ERR_UNSUPPORTED
     rc, ob, lb = H.hetis_attn_split_workspace_bytes(s, 4, 256, 48)
     assert rc == 0 and ob == 4 * 4 * 6 * 64 * 4 and lb == 4 * 4 * 6 * 4
     assert H.hetis_attn_split_workspace_bytes(s, 4, 257, 48)[0] == binding.HETIS_ERR_WORKSPACE
@@ -117,6 +120,7 @@ def test_split_argument_errors(lib):
     assert split(o=None) == binding.HETIS_ERR_NULL
     assert split(lse=None) == binding.HETIS_ERR_NULL
     assert split(chunk=8) == binding.HETIS_ERR_UNSUPPORTED
+    assert split(chunk=2048) == binding.HETIS_ERR_UNSUPPORTED
     assert split(msl=0) == binding.HETIS_ERR_WORKSPACE
     assert split(msl=4096) == binding.HETIS_ERR_WORKSPACE
     assert split(n_sel=9) == binding.HETIS_ERR_BAD_HEADS
