@@ -305,3 +305,78 @@ def test_many_short_sequences_and_repeat_calls():
     check_against_oracle(first, ref, w.spec, [0, 2, 3])
     for _ in range(5):
         assert np.array_equal(bits(d.decode([0, 2, 3])), bits(first))
+
+
+# ------------------------------------------------------------------ graphs and streams
+
+def test_graph_capture_and_replay():
+    """hetis_attn_decode and hetis_kv_append captured into a HIP graph (after one eager call has
+    allocated the library's workspace): every replay, with new queries and new rows in the same
+    buffers and eager work in between, matches an eager call bit for bit."""
+    w = W.make_custom([40, 300, 1500, 17, 700], 8, 8, 128, [1, 4, 6], seed=91, device="cuda:0")
+    d = Dev(w)
+    heads = [1, 4, 6]
+    hid, n = d.heads(heads)
+    kn, vn = W.new_token_rows(w)
+    out = d.new_out()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        H.check(H.hetis_attn_decode(d.shape, d.q, d.k, d.v, d.bt, d.sl, hid, n, d.scale, out, side))
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        H.check(H.hetis_kv_append(d.shape, kn, vn, d.bt, d.sl, hid, n, w.num_blocks, d.k, d.v, side))
+        H.check(H.hetis_attn_decode(d.shape, d.q, d.k, d.v, d.bt, d.sl, hid, n, d.scale, out, side))
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(92)
+    for it in range(4):
+        d.q.copy_(torch.randn(d.q.shape, generator=gen, device="cuda:0").half())
+        kn.copy_(torch.randn(kn.shape, generator=gen, device="cuda:0").half())
+        vn.copy_(torch.randn(vn.shape, generator=gen, device="cuda:0").half())
+        out.view(torch.int16).fill_(np.int16(SENTINEL))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        # eager reference on the same (already appended) cache
+        ref = d.decode(heads)
+        assert torch.equal(got.view(torch.int16), ref.view(torch.int16)), f"replay {it}"
+        rows = selected_rows(w.spec, heads)
+        last = (w.seq_lens - 1)
+        b = 2
+        assert torch.equal(d.k[w.block_table[b, last[b] // 16], 4, last[b] % 16], kn[b, 4])
+        check_untouched(got, w.spec, heads)
+        assert not np.isnan(as_f64(got)[:, rows]).any()
+
+
+def test_two_streams_with_their_own_buffers():
+    """Split-KV calls on two streams at once (each with its own partial buffers and outputs)
+    give what the same calls give one after the other."""
+    w1 = W.make_custom([2000, 900, 3000, 64], 8, 8, 128, [0, 3, 5, 7], seed=93, device="cuda:0")
+    w2 = W.make_custom([1200, 2500, 300], 16, 2, 128, [1, 0], seed=94, device="cuda:0")
+    devs = [Dev(w1), Dev(w2)]
+    heads = [[0, 3, 5, 7], [1, 0]]
+    msl = [3000, 2500]
+    serial = []
+    for d, h, m in zip(devs, heads, msl):
+        o_p, lse_p = d.split(h, 512, m)
+        serial.append(d.merge(o_p, lse_p, h, 512, m))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bufs = []
+    for d, h, m in zip(devs, heads, msl):
+        s = d.w.spec
+        C = H.hetis_attn_split_num_chunks(m, 512)
+        bufs.append((torch.empty((s.batch, len(h), C, s.group_size, s.head_dim), dtype=torch.float32,
+                                 device="cuda:0"),
+                     torch.empty((s.batch, len(h), C, s.group_size), dtype=torch.float32,
+                                 device="cuda:0"), d.new_out(), d.heads(h)))
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for d, h, m, st, (o_p, lse_p, out, (hid, n)) in zip(devs, heads, msl, streams, bufs):
+            H.check(H.hetis_attn_decode_split(d.shape, d.q, d.k, d.v, d.bt, d.sl, hid, n, d.scale, 512,
+                                              m, o_p, lse_p, st))
+            H.check(H.hetis_attn_merge(d.shape, o_p, lse_p, d.sl, hid, n, 512, m, out, st))
+    torch.cuda.synchronize()
+    for (o_p, lse_p, out, _), ref in zip(bufs, serial):
+        assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
