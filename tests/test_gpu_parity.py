@@ -380,3 +380,69 @@ def test_two_streams_with_their_own_buffers():
     torch.cuda.synchronize()
     for (o_p, lse_p, out, _), ref in zip(bufs, serial):
         assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
+
+
+# ------------------------------------------------------------------ mid-size shapes of every kernel variant
+
+@pytest.mark.parametrize("Hq,Hkv,D,hid", [
+    (16, 16, 64, [3, 9, 10, 15]),      # vector path, D = 64
+    (32, 16, 128, [0, 5, 6, 14]),      # vector path, r = 2
+    (32, 8, 128, [1, 6]),              # MFMA path, r = 4
+    (64, 8, 64, [0, 3, 7]),            # MFMA path, r = 8, D = 64
+])
+def test_mid_size_ragged_batch(Hq, Hkv, D, hid):
+    """96 sequences, lognormal lengths up to 4096 (several decode chunks of either size, a ragged
+    tail everywhere), several thousand items: sampled rows against the checker, subset rows
+    bit-identical to the all-heads run."""
+    rng = np.random.default_rng(95)
+    lens = np.clip(np.rint(rng.lognormal(np.log(900), 0.9, size=96)), 1, 4096).astype(int)
+    lens[:3] = [4096, 1, 769]
+    w = W.make_custom(lens, Hq, Hkv, D, hid, seed=96, device="cuda:0")
+    d = Dev(w)
+    out = d.decode(hid)
+    idx = np.unique(np.concatenate([[0, 1, 2], rng.integers(0, 96, size=5)]))
+    ref = oracle.attn_decode(w.q.cpu().numpy()[idx], w.k_cache.cpu().numpy(), w.v_cache.cpu().numpy(),
+                             w.block_table[idx], w.seq_lens[idx], np.asarray(hid, dtype=np.int32),
+                             w.spec.scale)
+    rows = selected_rows(w.spec, hid)
+    got = as_f64(out)
+    assert not np.isnan(got[:, rows]).any()
+    err = np.abs(got[idx][:, rows] - ref[:, rows]).max()
+    assert err <= TOL, f"max abs err {err:.3e}"
+    check_untouched(out, w.spec, hid)
+    full = d.decode(list(range(Hkv)))
+    assert np.array_equal(bits(full)[:, rows], bits(out)[:, rows])
+
+
+def test_split_with_the_largest_chunk():
+    """chunk_tokens = 1024: a wave's block-id register is full (64 blocks)."""
+    lens = [1024, 1025, 3000, 2048, 5]
+    hid = [0, 2]
+    w = W.make_custom(lens, 4, 4, 128, hid, seed=97, device="cuda:0")
+    d = Dev(w)
+    o_p, lse_p = d.split(hid, 1024, 3000)
+    out = d.merge(o_p, lse_p, hid, 1024, 3000)
+    ref = oracle.attn_decode(w.q.cpu().numpy(), w.k_cache.cpu().numpy(), w.v_cache.cpu().numpy(),
+                             w.block_table, w.seq_lens, np.asarray(hid, dtype=np.int32), w.spec.scale)
+    check_against_oracle(out, ref, w.spec, hid)
+    C = H.hetis_attn_split_num_chunks(3000, 1024)
+    lse = as_f64(lse_p)
+    assert C == 3 and np.isnan(lse[0, :, 1:]).all() and not np.isnan(lse[1, :, :2]).any()
+
+
+def test_batch_at_the_persistent_kernel_limit():
+    """Exactly 2048 sequences: the largest batch the persistent kernel's tables hold."""
+    rng = np.random.default_rng(98)
+    lens = rng.integers(1, 200, size=2048)
+    hid = [1]
+    w = W.make_custom(lens, 2, 2, 64, hid, seed=99, device="cuda:0")
+    d = Dev(w)
+    out = d.decode(hid)
+    idx = rng.integers(0, 2048, size=40)
+    ref = oracle.attn_decode(w.q.cpu().numpy()[idx], w.k_cache.cpu().numpy(), w.v_cache.cpu().numpy(),
+                             w.block_table[idx], w.seq_lens[idx], np.asarray(hid, dtype=np.int32),
+                             w.spec.scale)
+    got = as_f64(out)
+    assert not np.isnan(got[:, 1]).any()
+    assert np.abs(got[idx, 1] - ref[:, 1]).max() <= TOL
+    check_untouched(out, w.spec, hid)
