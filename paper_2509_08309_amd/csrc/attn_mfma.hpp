@@ -54,7 +54,7 @@ struct MfmaPolicy {
     static constexpr int kQBytes = R * D * 2;
     static constexpr int kWaveLdsBytes = kStageV + kQBytes;
     static constexpr int kWavesPerEu = 2;             // register budget: 512 / 2 per lane
-    static constexpr int kRing = 2;   // tile pairs in flight per wave
+    static constexpr int kRing = D_ == 64 ? 4 : 2;   // tile pairs in flight per wave (16 KB)
 
     struct Tile {
         uint4 k[KS];

@@ -323,7 +323,8 @@ struct VecPolicy {
     static constexpr int R = R_;
     static constexpr int kWaveLdsBytes = 0;      // no per-wave staging area
     static constexpr int kWavesPerEu = 2;        // register budget: 512 / 2 per lane
-    static constexpr int kRing = 2;              // tile pairs in flight per wave
+    // tile pairs in flight per wave: 16 KB either way (a tile pair is 8 KB at D = 128, 4 KB at 64)
+    static constexpr int kRing = D_ == 64 ? 4 : 2;
     using Tile = TileRegs<D>;
     using State = VecState<D, R>;
     struct Query {
