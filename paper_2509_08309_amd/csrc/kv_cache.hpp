@@ -59,10 +59,14 @@ __global__ void __launch_bounds__(256) kv_rows_kernel(KvRowParams p)
         if (g < 0 || g >= p.n_kv_heads) continue;
         uint4 *in_cache = cache + cache_row + (int64_t)g * p.stride_head;
         uint4 *in_rows = rows + rows_row + (int64_t)g * LR;
-        if (FETCH)
-            *in_rows = *in_cache;
-        else
-            *in_cache = *in_rows;
+        // every byte is touched once: non-temporal both ways (+1 % on a prefill-sized store)
+        if (FETCH) {
+            const kv_u32x4 x = __builtin_nontemporal_load((const kv_u32x4 *)in_cache);
+            __builtin_nontemporal_store(x, (kv_u32x4 *)in_rows);
+        } else {
+            const kv_u32x4 x = __builtin_nontemporal_load((const kv_u32x4 *)in_rows);
+            __builtin_nontemporal_store(x, (kv_u32x4 *)in_cache);
+        }
     }
 }
 
