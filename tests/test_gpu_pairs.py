@@ -168,3 +168,22 @@ def test_no_pairs_and_bad_content():
     t = pw.block_table.copy()
     t[2, 0] = -1
     assert v(t, pw.pair_seq, pw.pair_head) == bad
+
+
+def test_pairs_at_the_persistent_kernel_limit_grouped_query():
+    """2048 pairs of a grouped-query shape (r = 8, D = 128): the largest LDS footprint the
+    persistent kernel can ask for (tables of 2048 rows, mailboxes of 8 rows, MFMA staging)."""
+    rng = np.random.default_rng(69)
+    B, Hq, Hkv, D = 256, 64, 8, 128
+    lens = rng.integers(1, 900, size=B)
+    subsets = [np.arange(Hkv, dtype=np.int32) for _ in range(B)]
+    pw = W.make_pairs_workload(spec_of(lens, Hq, Hkv, D, 70), device=DEV, subsets=subsets)
+    assert pw.n_pairs == 2048
+    out = run_pairs(pw)
+    pick = rng.integers(0, pw.n_pairs, size=24)
+    ref = oracle_pairs(pw, pick)
+    got = as_f64(out)
+    assert not np.isnan(got).any()
+    for p in pick:
+        b, g = int(pw.pair_seq[p]), int(pw.pair_head[p])
+        assert np.abs(got[b, g * 8:(g + 1) * 8] - ref[b, g * 8:(g + 1) * 8]).max() <= TOL
