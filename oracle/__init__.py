@@ -32,7 +32,7 @@ def lib():
         _lib.oracle_half_to_double.argtypes = [C.c_uint16]
         for name in ("oracle_attn_decode", "oracle_attn_partial", "oracle_attn_merge",
                      "oracle_attn_decode_pairs", "oracle_max_threads", "oracle_kv_store", "oracle_kv_append",
-                     "oracle_kv_fetch", "oracle_kv_copy_tiles"):
+                     "oracle_kv_fetch", "oracle_kv_copy_tiles", "oracle_kv_append_pairs"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -193,6 +193,23 @@ def kv_append(k_cache, v_cache, k_new, v_new, block_table, seq_lens, head_ids, s
                                 C.c_int32(len(hid)), C.c_int32(nb), _ptr(k), _ptr(v))
     if rc != 0:
         raise RuntimeError(f"oracle_kv_append failed: {rc}")
+    return k, v
+
+
+def kv_append_pairs(k_tiles, v_tiles, k_new, v_new, block_table, seq_lens, pair_seq, pair_head):
+    """Copies of the two tile pools [num_tiles, 16, D] with the new row of every (sequence, KV
+    head) pair stored at seq_lens[b] - 1 through the pair's own block-table row."""
+    k, v = _u16(k_tiles).copy(), _u16(v_tiles).copy()
+    kn, vn = _u16(k_new), _u16(v_new)
+    nt, bs, D = k.shape
+    B, Hkv, D2 = kn.shape
+    bt, sl, ps, ph = _i32(block_table), _i32(seq_lens), _i32(pair_seq), _i32(pair_head)
+    assert D == D2 and vn.shape == kn.shape and bt.shape[0] == len(ps) == len(ph) and len(sl) == B
+    shp = _Shape(B, Hkv, Hkv, D, bs, bt.shape[1], bs * D, 0)
+    rc = lib().oracle_kv_append_pairs(C.byref(shp), _ptr(kn), _ptr(vn), _ptr(bt), _ptr(sl), _ptr(ps),
+                                      _ptr(ph), C.c_int32(len(ps)), C.c_int32(nt), _ptr(k), _ptr(v))
+    if rc != 0:
+        raise RuntimeError(f"oracle_kv_append_pairs failed: {rc}")
     return k, v
 
 

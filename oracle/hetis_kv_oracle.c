@@ -105,6 +105,35 @@ int oracle_kv_append(const oracle_shape *s, const uint16_t *k_new, const uint16_
     return 0;
 }
 
+/*
+ * Decode-step store for per-request head subsets (Section 4.2 / 5.2.1): the work is a list of
+ * (sequence, KV head) pairs over a pool of single-head tiles, one block-table row per pair.
+ * Pair p = (b, g) stores k_new[b][g][:] and v_new[b][g][:] at position seq_lens[b] - 1:
+ *   tile = block_table[p][pos / block_size], element tile * kv_stride_block + (pos % block_size) * D.
+ * Pairs whose sequence or head id is out of range, whose sequence is empty, whose position is
+ * past the table row or whose tile id is outside [0, num_tiles) are skipped.
+ */
+int oracle_kv_append_pairs(const oracle_shape *s, const uint16_t *k_new, const uint16_t *v_new,
+                           const int32_t *block_table, const int32_t *seq_lens,
+                           const int32_t *pair_seq, const int32_t *pair_head, int32_t n_pairs,
+                           int32_t num_tiles, uint16_t *k_tiles, uint16_t *v_tiles)
+{
+    const int D = s->head_dim;
+    for (int64_t p = 0; p < n_pairs; ++p) {
+        int64_t b = pair_seq[p], g = pair_head[p];
+        if (b < 0 || b >= s->batch || g < 0 || g >= s->n_kv_heads) continue;
+        int64_t pos = (int64_t)seq_lens[b] - 1;
+        if (pos < 0 || pos / s->block_size >= s->max_blocks_per_seq) continue;
+        int64_t tile = block_table[p * s->max_blocks_per_seq + pos / s->block_size];
+        if (tile < 0 || tile >= num_tiles) continue;
+        const int64_t dst = tile * s->kv_stride_block + (pos % s->block_size) * D;
+        const int64_t src = (b * s->n_kv_heads + g) * D;
+        memcpy(k_tiles + dst, k_new + src, (size_t)D * 2);
+        memcpy(v_tiles + dst, v_new + src, (size_t)D * 2);
+    }
+    return 0;
+}
+
 /* Fetch: the inverse gather, k_out[n][g][:] = K[row(seq[n], pos[n], g)]; skipped entries and
  * rows of heads that are not selected stay as they were. */
 int oracle_kv_fetch(const oracle_shape *s, const uint16_t *k_cache, const uint16_t *v_cache,

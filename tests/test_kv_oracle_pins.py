@@ -256,3 +256,49 @@ def test_attention_is_invariant_under_migration_to_a_compact_pool(head_major):
     q2 = np.ascontiguousarray(q[:, moved])
     out = oracle.attn_decode(q2, dk, dv, bt2, np.array(lens), [0, 1], 0.25)
     assert np.array_equal(out, ref[:, moved])
+
+
+# ---------------------------------------------------------------- pairs form of the decode-step store
+
+def test_append_pairs_then_attention_sees_the_new_token():
+    """Per-request head subsets over single-head tiles: after the append, the pairs Attention
+    checker equals brute-force attention on the dense sequences (new token included), the rows
+    written are exactly one K and one V row per pair, and pairs that point outside the tables
+    are skipped."""
+    from paper_2509_08309_amd import workloads as W
+    lens = [5, 17, 64, 33]
+    Hq = Hkv = 4
+    D = 16
+    subsets = [[0, 3], [1], [0, 1, 2, 3], [2]]
+    spec = W.WorkloadSpec("pairs", len(lens), Hq, Hkv, D, tuple(range(Hkv)), 24, "fixed",
+                          (tuple(lens),), max(lens))
+    pw = W.make_pairs_workload(spec, subsets=subsets, poison=False)
+    k0, v0 = pw.k_tiles.numpy().view(np.uint16), pw.v_tiles.numpy().view(np.uint16)
+    rng = np.random.default_rng(25)
+    kn = (rng.integers(-64, 64, size=(len(lens), Hkv, D)) / 16.0).astype(np.float16)
+    vn = (rng.integers(-64, 64, size=(len(lens), Hkv, D)) / 16.0).astype(np.float16)
+    k1, v1 = oracle.kv_append_pairs(k0, v0, kn, vn, pw.block_table, pw.seq_lens, pw.pair_seq,
+                                    pw.pair_head)
+    assert int((k1 != k0).any(axis=-1).sum()) == pw.n_pairs
+    assert int((v1 != v0).any(axis=-1).sum()) == pw.n_pairs
+    q = pw.q.numpy()
+    out = oracle.attn_decode_pairs(q, k1.view(np.float16), v1.view(np.float16), pw.block_table,
+                                   pw.seq_lens, pw.pair_seq, pw.pair_head, Hkv, 0.25)
+    for p in range(pw.n_pairs):
+        b, g = int(pw.pair_seq[p]), int(pw.pair_head[p])
+        L = lens[b]
+        t = np.arange(L)
+        tiles = pw.block_table[p, t // 16]
+        Kd = k0.view(np.float16)[tiles, t % 16].copy()
+        Vd = v0.view(np.float16)[tiles, t % 16].copy()
+        Kd[-1], Vd[-1] = kn[b, g], vn[b, g]             # the new token is the last one
+        ref = brute_attention(q[b, g], Kd, Vd, 0.25)
+        assert np.max(np.abs(out[b, g] - ref)) < 1e-12
+    # skipped pairs: bad sequence id, bad head id, empty sequence, tile id outside the pool
+    bad_seq = pw.pair_seq.copy(); bad_seq[0] = len(lens)
+    bad_head = pw.pair_head.copy(); bad_head[1] = -1
+    sl0 = pw.seq_lens.copy(); sl0[2] = 0
+    bt_bad = pw.block_table.copy(); bt_bad[-1, (lens[3] - 1) // 16] = pw.num_tiles
+    k2, v2 = oracle.kv_append_pairs(k0, v0, kn, vn, bt_bad, sl0, bad_seq, bad_head)
+    changed = (k2 != k0).any(axis=-1)
+    assert int(changed.sum()) == pw.n_pairs - (1 + 1 + 4 + 1)
