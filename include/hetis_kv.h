@@ -62,6 +62,22 @@ int hetis_kv_append(const hetis_attn_shape *shape, const void *k_new, const void
                     void *k_cache, void *v_cache, void *stream);
 
 /*
+ * Decode-step store for per-request head subsets (the companion of
+ * hetis_attn_decode_pairs; Section 4.2 / 5.2.1: the heads a device holds differ per
+ * request): pair p = (pair_seq[p], pair_head[p]) stores k_new[b, g, :] and
+ * v_new[b, g, :] at position seq_lens[b] - 1 of its own block-table row,
+ *   tile = block_table[p][pos / 16], element tile * kv_stride_block + (pos % 16) * D
+ * in a pool of single-head tiles (kv_stride_block 0 = 16 * D; kv_stride_head unused).
+ *   k_new, v_new fp16 [B, Hkv, D]     block_table int32 [n_pairs, max_blocks_per_seq]
+ *   num_tiles    host, tiles in the pool; pairs that point outside the tables are skipped
+ * Errors: NULL, BAD_SHAPE, UNSUPPORTED, LAUNCH.  n_pairs = 0 is a no-op.
+ */
+int hetis_kv_append_pairs(const hetis_attn_shape *shape, const void *k_new, const void *v_new,
+                          const int32_t *block_table, const int32_t *seq_lens,
+                          const int32_t *pair_seq, const int32_t *pair_head, int32_t n_pairs,
+                          int64_t num_tiles, void *k_tiles, void *v_tiles, void *stream);
+
+/*
  * General store by (sequence id, position, head id): entry n carries the rows
  * k_new[n, g, :], v_new[n, g, :] of sequence token_seq[n] at position
  * token_pos[n] (e.g. all prompt tokens after prefill).

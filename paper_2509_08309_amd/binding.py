@@ -107,6 +107,8 @@ def load(build_if_missing: bool = False):
     pool = C.POINTER(hetis_kv_pool)
     lib.hetis_kv_append.restype = C.c_int
     lib.hetis_kv_append.argtypes = [shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    lib.hetis_kv_append_pairs.restype = C.c_int
+    lib.hetis_kv_append_pairs.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.hetis_kv_store.restype = C.c_int
     lib.hetis_kv_store.argtypes = [shp, vp, vp, vp, vp, i32, vp, vp, i32, i64, vp, vp, vp]
     lib.hetis_kv_fetch.restype = C.c_int
@@ -233,6 +235,14 @@ def hetis_kv_append(shape, k_new, v_new, block_table, seq_lens, head_ids, n_sel_
     return load().hetis_kv_append(C.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(block_table),
                                   _ptr(seq_lens), _ptr(head_ids), int(n_sel_heads),
                                   int(num_blocks), _ptr(k_cache), _ptr(v_cache), _stream(stream))
+
+
+def hetis_kv_append_pairs(shape, k_new, v_new, block_table, seq_lens, pair_seq, pair_head, n_pairs,
+                          num_tiles, k_tiles, v_tiles, stream=None) -> int:
+    return load().hetis_kv_append_pairs(C.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(block_table),
+                                        _ptr(seq_lens), _ptr(pair_seq), _ptr(pair_head),
+                                        int(n_pairs), int(num_tiles), _ptr(k_tiles), _ptr(v_tiles),
+                                        _stream(stream))
 
 
 def hetis_kv_store(shape, k_new, v_new, token_seq, token_pos, n_tokens, block_table, head_ids,

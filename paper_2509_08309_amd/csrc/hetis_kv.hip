@@ -136,6 +136,45 @@ int hetis_kv_append(const hetis_attn_shape *shape, const void *k_new, const void
                      k_cache, v_cache, stream);
 }
 
+int hetis_kv_append_pairs(const hetis_attn_shape *shape, const void *k_new, const void *v_new,
+                          const int32_t *block_table, const int32_t *seq_lens,
+                          const int32_t *pair_seq, const int32_t *pair_head, int32_t n_pairs,
+                          int64_t num_tiles, void *k_tiles, void *v_tiles, void *stream)
+{
+    KvChecked c;
+    const int rc = check_kv_shape(shape, 1, &c);
+    if (rc != HETIS_OK) return rc;
+    if (n_pairs < 0 || num_tiles <= 0) return HETIS_ERR_BAD_SHAPE;
+    // the pool holds single-head tiles: one stride, no head term
+    const int64_t tile = (int64_t)shape->block_size * shape->head_dim;
+    const int64_t stride = shape->kv_stride_block ? shape->kv_stride_block : tile;
+    if (stride % 8 != 0 || stride < tile) return HETIS_ERR_BAD_SHAPE;
+    if (!k_new || !v_new || !block_table || !seq_lens || !pair_seq || !pair_head || !k_tiles ||
+        !v_tiles)
+        return HETIS_ERR_NULL;
+    if (n_pairs == 0) return HETIS_OK;
+    KvPairParams p{};
+    p.k_new = (const uint4 *)k_new;
+    p.v_new = (const uint4 *)v_new;
+    p.k_tiles = (uint4 *)k_tiles;
+    p.v_tiles = (uint4 *)v_tiles;
+    p.block_table = block_table;
+    p.seq_lens = seq_lens;
+    p.pair_seq = pair_seq;
+    p.pair_head = pair_head;
+    p.stride_tile = stride / 8;
+    p.num_tiles = num_tiles;
+    p.n_pairs = n_pairs;
+    p.n_kv_heads = shape->n_kv_heads;
+    p.batch = shape->batch;
+    p.max_blocks_per_seq = shape->max_blocks_per_seq;
+    const int64_t threads = (int64_t)n_pairs * (2 * shape->head_dim / 8);
+    const dim3 grid((unsigned)((threads + 255) / 256));
+    const hipStream_t st = (hipStream_t)stream;
+    if (shape->head_dim == 128) return launch_kv(kv_append_pairs_kernel<128>, grid, st, p);
+    return launch_kv(kv_append_pairs_kernel<64>, grid, st, p);
+}
+
 int hetis_kv_store(const hetis_attn_shape *shape, const void *k_new, const void *v_new,
                    const int32_t *token_seq, const int32_t *token_pos, int32_t n_tokens,
                    const int32_t *block_table, const int32_t *head_ids, int32_t n_sel_heads,

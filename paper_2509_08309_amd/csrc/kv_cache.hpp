@@ -70,6 +70,43 @@ __global__ void __launch_bounds__(256) kv_rows_kernel(KvRowParams p)
     }
 }
 
+struct KvPairParams {
+    const uint4 *k_new, *v_new;     // [batch, Hkv, D]
+    uint4 *k_tiles, *v_tiles;       // single-head tiles
+    const int32_t *block_table;     // [n_pairs, max_blocks_per_seq]
+    const int32_t *seq_lens, *pair_seq, *pair_head;
+    int64_t stride_tile;            // in 16-byte units
+    int64_t num_tiles;
+    int32_t n_pairs, n_kv_heads, batch, max_blocks_per_seq;
+};
+
+// Decode-step store for per-request head subsets: 2*D/8 lanes move the new K row and V row
+// of one (sequence, KV head) pair to position seq_lens[b] - 1 through the pair's own
+// block-table row.  Same checks as kv_rows_kernel; a pair that fails one is skipped.
+template <int D>
+__global__ void __launch_bounds__(256) kv_append_pairs_kernel(KvPairParams p)
+{
+    constexpr int LR = D / 8;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t pr = t / (2 * LR);
+    if (pr >= p.n_pairs) return;
+    const int within = (int)(t % (2 * LR));
+    const bool is_v = within >= LR;
+    const int c = within % LR;
+    const int64_t b = p.pair_seq[pr];
+    const int64_t g = p.pair_head[pr];
+    if (b < 0 || b >= p.batch || g < 0 || g >= p.n_kv_heads) return;
+    const int64_t pos = (int64_t)p.seq_lens[b] - 1;
+    if (pos < 0) return;
+    const int64_t j = pos / kKvBlockTokens;
+    if (j >= p.max_blocks_per_seq) return;
+    const int64_t tile = p.block_table[pr * p.max_blocks_per_seq + j];
+    if (tile < 0 || tile >= p.num_tiles) return;
+    const uint4 *src = (is_v ? p.v_new : p.k_new) + (b * p.n_kv_heads + g) * LR + c;
+    uint4 *dst = (is_v ? p.v_tiles : p.k_tiles) + tile * p.stride_tile + (pos % kKvBlockTokens) * LR + c;
+    *dst = *src;
+}
+
 struct KvCopyParams {
     const uint4 *src_k, *src_v;
     uint4 *dst_k, *dst_v;

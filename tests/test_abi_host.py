@@ -254,3 +254,18 @@ def test_pairs_argument_errors(lib):
     assert H.hetis_attn_validate_pairs(good(), P, P, None, P, 3, 10, 0) == binding.HETIS_ERR_NULL
     assert H.hetis_attn_validate_pairs(good(), P, P, P, P, 3, 0, 0) == binding.HETIS_ERR_BAD_SHAPE
     assert H.hetis_attn_validate_pairs(good(), P, P, P, P, 0, 10, 0) == binding.HETIS_OK
+
+
+def test_kv_append_pairs_argument_errors(lib):
+    def call(shape=None, n_pairs=3, num_tiles=10, **kw):
+        a = dict(kn=P, vn=P, bt=P, sl=P, ps=P, ph=P, k=P, v=P)
+        a.update(kw)
+        return H.hetis_kv_append_pairs(shape or good(), a["kn"], a["vn"], a["bt"], a["sl"], a["ps"],
+                                       a["ph"], n_pairs, num_tiles, a["k"], a["v"], 0)
+    for arg in ("kn", "vn", "bt", "sl", "ps", "ph", "k", "v"):
+        assert call(**{arg: None}) == binding.HETIS_ERR_NULL
+    assert call(n_pairs=-1) == binding.HETIS_ERR_BAD_SHAPE
+    assert call(num_tiles=0) == binding.HETIS_ERR_BAD_SHAPE
+    assert call(shape=H.make_shape(4, 8, 8, 96, 16)) == binding.HETIS_ERR_UNSUPPORTED
+    assert call(shape=H.make_shape(4, 8, 8, 64, 16, kv_stride_block=1000)) == binding.HETIS_ERR_BAD_SHAPE
+    assert call(n_pairs=0) == binding.HETIS_OK

@@ -187,3 +187,67 @@ def test_pairs_at_the_persistent_kernel_limit_grouped_query():
     for p in pick:
         b, g = int(pw.pair_seq[p]), int(pw.pair_head[p])
         assert np.abs(got[b, g * 8:(g + 1) * 8] - ref[b, g * 8:(g + 1) * 8]).max() <= TOL
+
+
+@pytest.mark.parametrize("name", [None, "c3_13b_subset"])
+def test_append_pairs_then_decode_pairs(name):
+    """The decode step of the pairs form: the new rows go into the single-head tiles through
+    the per-pair tables (bit-exact against the checker, whole pools compared), then Attention
+    over the appended pools matches the checker on the checker's own appended pools."""
+    if name is None:
+        lens = [1, 16, 17, 255, 256, 300, 0, 1025]
+        rng = np.random.default_rng(71)
+        subsets = W.draw_head_subsets(len(lens), 8, 3, rng)
+        subsets[0] = np.arange(8, dtype=np.int32)
+        subsets[6] = np.array([2], dtype=np.int32)
+        pw = W.make_pairs_workload(spec_of(lens, 16, 8, 128, 72), device=DEV, subsets=subsets)
+    else:
+        pw = W.make_pairs_workload(W.SPECS[name], device=DEV)
+    s = pw.spec
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(73)
+    kn = torch.randn((s.batch, s.n_kv_heads, s.head_dim), generator=gen, device=DEV).half()
+    vn = torch.randn((s.batch, s.n_kv_heads, s.head_dim), generator=gen, device=DEV).half()
+    ref_k, ref_v = oracle.kv_append_pairs(bits(pw.k_tiles), bits(pw.v_tiles), bits(kn), bits(vn),
+                                          pw.block_table, pw.seq_lens, pw.pair_seq, pw.pair_head)
+    shape = H.make_shape(s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim, pw.block_table.shape[1])
+    H.check(H.hetis_kv_append_pairs(shape, kn, vn, i32(pw.block_table), i32(pw.seq_lens),
+                                    i32(pw.pair_seq), i32(pw.pair_head), pw.n_pairs, pw.num_tiles,
+                                    pw.k_tiles, pw.v_tiles), "hetis_kv_append_pairs")
+    torch.cuda.synchronize()
+    same = lambda t, ref: bool(torch.equal(t.view(torch.int16).reshape(-1),
+                                           torch.from_numpy(ref.view(np.int16)).to(DEV).reshape(-1)))
+    assert same(pw.k_tiles, ref_k) and same(pw.v_tiles, ref_v)
+    out = run_pairs(pw)
+    rng = np.random.default_rng(74)
+    pick = np.unique(rng.integers(0, pw.n_pairs, size=min(30, pw.n_pairs)))
+    ref = oracle.attn_decode_pairs(pw.q.cpu().numpy(), ref_k.view(np.float16), ref_v.view(np.float16),
+                                   pw.block_table[pick], pw.seq_lens, pw.pair_seq[pick],
+                                   pw.pair_head[pick], s.n_kv_heads, s.scale)
+    r = s.group_size
+    got = as_f64(out)
+    for p in pick:
+        b, g = int(pw.pair_seq[p]), int(pw.pair_head[p])
+        assert np.abs(got[b, g * r:(g + 1) * r] - ref[b, g * r:(g + 1) * r]).max() <= TOL
+
+
+def test_append_pairs_skips_what_points_outside():
+    lens = [20, 7, 64, 0]
+    pw = W.make_pairs_workload(spec_of(lens, 4, 4, 64, 75), device=DEV,
+                               subsets=[[0, 2], [1], [3], [0]])
+    s = pw.spec
+    kn = torch.ones((4, 4, 64), dtype=torch.float16, device=DEV)
+    ps, ph, bt = pw.pair_seq.copy(), pw.pair_head.copy(), pw.block_table.copy()
+    ps[0] = 4                  # sequence id past the batch
+    ph[1] = -1                 # head id out of range
+    bt[2, 0] = pw.num_tiles    # tile id past the pool
+    ref_k, ref_v = oracle.kv_append_pairs(bits(pw.k_tiles), bits(pw.v_tiles), bits(kn), bits(kn), bt,
+                                          pw.seq_lens, ps, ph)
+    k, v = pw.k_tiles.clone(), pw.v_tiles.clone()
+    shape = H.make_shape(4, 4, 4, 64, bt.shape[1])
+    H.check(H.hetis_kv_append_pairs(shape, kn, kn, i32(bt), i32(pw.seq_lens), i32(ps), i32(ph),
+                                    pw.n_pairs, pw.num_tiles, k, v), "hetis_kv_append_pairs")
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(k), ref_k) and np.array_equal(bits(v), ref_v)
+    # only the pair of sequence 2 was stored (sequence 3 is empty)
+    assert int((bits(k) != bits(pw.k_tiles)).any(axis=-1).sum()) == 1
