@@ -59,11 +59,11 @@ def cpu_baseline(w_host, budget_s: float):
     n = int(np.searchsorted(csum, rate * budget_s, side="right"))
     n = max(1, min(spec.batch, n))
     t0 = time.perf_counter()
-    oracle.attn_decode(q[:n], k, v, w_host.block_table[:n], w_host.seq_lens[:n], w_host.head_ids,
-                       spec.scale)
+    ref = oracle.attn_decode(q[:n], k, v, w_host.block_table[:n], w_host.seq_lens[:n],
+                             w_host.head_ids, spec.scale)
     dt = time.perf_counter() - t0
     kv_bytes = int(lens[:n].sum()) * len(w_host.head_ids) * 4 * spec.head_dim
-    return {
+    return ref, {
         "value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
         "sample": f"first {n} of {spec.batch} sequences of {spec.name}, all {len(w_host.head_ids)} "
                   f"selected heads, {int(lens[:n].sum())} cached tokens, {dt:.2f} s wall",
@@ -403,7 +403,16 @@ def main():
     if not args.no_cpu_baseline:
         w_host = W.Workload(spec, w.seq_lens, w.block_table, w.num_blocks, w.q.cpu(),
                             w.k_cache.cpu(), w.v_cache.cpu(), w.head_ids)
-        rec["cpu_baseline"] = cpu_baseline(w_host, args.cpu_seconds)
+        ref, rec["cpu_baseline"] = cpu_baseline(w_host, args.cpu_seconds)
+        # the checker's result is not thrown away: every selected row of the sequences it
+        # covered is compared with what the timed GPU steps left in `out`
+        r = spec.group_size
+        rows = sorted(int(g) * r + i for g in w.head_ids for i in range(r))
+        n = ref.shape[0]
+        got = out[:n].cpu().numpy().astype(np.float64)[:, rows]
+        rec["parity"] = {"max_abs_err": float(np.abs(got - ref[:, rows]).max()),
+                         "tolerance": 4e-3, "sequences_checked": n, "sequences": spec.batch,
+                         "rows_checked": n * len(rows), "against": "oracle (fp64 CPU checker)"}
     print(json.dumps(rec))
 
 

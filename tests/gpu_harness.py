@@ -111,3 +111,36 @@ def selected_rows(spec: W.WorkloadSpec, head_ids):
 def unselected_rows(spec: W.WorkloadSpec, head_ids):
     sel = set(selected_rows(spec, head_ids))
     return [h for h in range(spec.n_q_heads) if h not in sel]
+
+
+def check_rows(out: torch.Tensor, ref: np.ndarray, rows, tol=TOL, what="") -> float:
+    """Every element of the listed head rows of every sequence against the checker's fp64
+    result: none still holds the sentinel the output was filled with (a row the library never
+    wrote would otherwise pass as a finite number), none is NaN, all within `tol`."""
+    rows = list(rows)
+    raw = bits(out)[:, rows]
+    assert (raw != SENTINEL).all(), f"{what}: {int((raw == SENTINEL).all(axis=-1).sum())} selected rows never written"
+    got = as_f64(out)[:, rows]
+    assert not np.isnan(got).any(), f"{what}: NaN in a selected row"
+    err = float(np.abs(got - ref[:, rows]).max()) if got.size else 0.0
+    assert err <= tol, f"{what}: max abs err {err:.3e} > {tol}"
+    return err
+
+
+def check_mask(out: torch.Tensor, ref: np.ndarray, mask: np.ndarray, tol=TOL, what="") -> float:
+    """As check_rows for a boolean [B, Hq] mask of rows (per-request head subsets); rows outside
+    the mask must still hold the sentinel."""
+    raw = bits(out)
+    assert (raw[mask] != SENTINEL).all(), f"{what}: a named row was never written"
+    assert (raw[~mask] == SENTINEL).all(), f"{what}: rows that no pair names were written"
+    got = as_f64(out)[mask]
+    assert not np.isnan(got).any(), f"{what}: NaN in a named row"
+    err = float(np.abs(got - ref[mask]).max()) if got.size else 0.0
+    assert err <= tol, f"{what}: max abs err {err:.3e} > {tol}"
+    return err
+
+
+def host_copy(w: W.Workload) -> W.Workload:
+    """The same workload with its tensors in host memory (what the checker reads)."""
+    return W.Workload(w.spec, w.seq_lens, w.block_table, w.num_blocks, w.q.cpu(), w.k_cache.cpu(),
+                      w.v_cache.cpu(), w.head_ids)
