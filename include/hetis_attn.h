@@ -47,6 +47,19 @@
  *   - Every function returns a status (0 = HETIS_OK, negative = error) and
  *     never throws, aborts or prints.  Argument errors are detected before any
  *     HIP call is made.
+ *   - Memory.  The entry points whose names end in _ws take every byte of device
+ *     memory they use from the caller: they allocate nothing, keep no state
+ *     between calls and never synchronise, so they may be called under stream
+ *     capture and on several streams at once (one workspace per stream).  The
+ *     entry points without the suffix are the same calls run from a workspace
+ *     that the library owns (see hetis_attn_decode).
+ *   - Workspace.  A workspace is a 256-byte aligned device buffer whose first
+ *     HETIS_ATTN_CONTROL_BYTES are control words (work tickets and an error
+ *     word); the rest holds fp32 partial results whose contents mean nothing
+ *     between calls.  The control words must be zero before the first call
+ *     (hetis_attn_workspace_init, or any zero fill); every launch leaves them at
+ *     zero again, so one workspace serves any number of calls in stream order.
+ *     Two launches that may run at the same time must not share a workspace.
  *
  * Supported: head_dim in {64, 128}; block_size 16; r in {1, 2, 4, 8}.
  */
@@ -66,12 +79,18 @@ enum {
     HETIS_ERR_BAD_SHAPE = -2,   /* non-positive size, n_q_heads % n_kv_heads != 0, bad strides */
     HETIS_ERR_UNSUPPORTED = -3, /* head_dim, block_size, group size or chunk_tokens not supported */
     HETIS_ERR_BAD_HEADS = -4,   /* n_sel_heads outside [1, n_kv_heads] */
-    HETIS_ERR_WORKSPACE = -5,   /* max_seq_len inconsistent with the shape / chunking */
+    HETIS_ERR_WORKSPACE = -5,   /* max_seq_len inconsistent with the shape / chunking; workspace too
+                                   small, misaligned, or in need of growth during stream capture */
     HETIS_ERR_LAUNCH = -6,      /* HIP reported an error when launching */
     HETIS_ERR_ALLOC = -7,       /* the internal workspace could not be allocated */
     HETIS_ERR_BAD_CONTENT = -8, /* hetis_attn_validate found an out-of-range value */
-    HETIS_ERR_INFEASIBLE = -9   /* hetis_dispatch_solve: the capacities cannot hold the requests */
+    HETIS_ERR_INFEASIBLE = -9,  /* hetis_dispatch_solve: the capacities cannot hold the requests */
+    HETIS_ERR_DEVICE_WAIT = -10 /* hetis_attn_workspace_status: a bounded wait inside a kernel
+                                   expired, results of that workspace's launches are suspect */
 };
+
+/* Bytes at the start of every workspace that hold control words. */
+#define HETIS_ATTN_CONTROL_BYTES 256
 
 typedef struct {
     int32_t batch;              /* B  > 0 */
@@ -104,21 +123,62 @@ const char *hetis_attn_status_string(int status);
  *   scale        host, normally 1/sqrt(D)
  *   out          fp16 [B, Hq, D]; rows of unselected heads are left untouched
  * Sequences longer than an internal fixed chunk (a compile-time constant: 256
- * tokens for r < 4, 768 for r >= 4) are
- * processed as several chunks whose fp32 partial results go through a
- * workspace that the library owns: it is allocated with hipMalloc on the first
- * call on a device and grown when a call needs more (both synchronise the
- * device); steady-state calls allocate nothing.  The workspace is shared by all
- * calls on one device: calls on different streams that may overlap must be
- * serialised by the caller, or use the split entry points with their own
- * buffers.  Errors: NULL, BAD_SHAPE, UNSUPPORTED, BAD_HEADS, ALLOC, LAUNCH.
+ * tokens for r < 4, 768 for r >= 4) are processed as several chunks whose fp32
+ * partial results go through the workspace.
+ *
+ * hetis_attn_decode_ws: the caller's workspace, at least
+ *   hetis_attn_decode_workspace_bytes(shape, n_sel_heads) bytes (the size depends on
+ *   batch, n_sel_heads, the group size, head_dim and max_blocks_per_seq only).
+ *   Errors: NULL, BAD_SHAPE, UNSUPPORTED, BAD_HEADS, WORKSPACE (too small or not 256-byte
+ *   aligned), LAUNCH.
+ * hetis_attn_decode: convenience form of the same call on a workspace that the library
+ *   owns, one per device.  It is allocated (hipMalloc) by the first call that needs it, by
+ *   a later call that needs a larger one, or ahead of time by
+ *   hetis_attn_reserve_workspace; a buffer that has been outgrown is kept until
+ *   hetis_attn_release_workspace, so that a HIP graph captured earlier can still be
+ *   replayed.  A call on a capturing stream never allocates: if the workspace is missing
+ *   or too small it returns HETIS_ERR_WORKSPACE (reserve first, or use the _ws form).
+ *   All calls on one device share the workspace: calls that may overlap (different
+ *   streams, graphs replayed side by side) must use the _ws form with one workspace each.
+ *   Errors: NULL, BAD_SHAPE, UNSUPPORTED, BAD_HEADS, WORKSPACE, ALLOC, LAUNCH.
  */
 int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *k_cache,
                       const void *v_cache, const int32_t *block_table, const int32_t *seq_lens,
                       const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
                       void *stream);
+int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                         const void *v_cache, const int32_t *block_table,
+                         const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
+                         float scale, void *out, void *workspace, size_t workspace_bytes,
+                         void *stream);
 
-/* Frees the internal workspace of every device (synchronises).  Optional. */
+/* Workspace size in bytes (host out-pointer) of hetis_attn_decode_ws for this shape and
+ * head count, and of hetis_attn_decode_pairs_ws for this shape and pair count (n_pairs >= 0). */
+int hetis_attn_decode_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,
+                                      size_t *bytes);
+int hetis_attn_decode_pairs_workspace_bytes(const hetis_attn_shape *shape, int32_t n_pairs,
+                                            size_t *bytes);
+
+/* Zero-fills a workspace on `stream` with a kernel (no memset node, so the call can be
+ * captured): needed once after allocation and after hetis_attn_workspace_status reported an
+ * expired wait.  `bytes` a multiple of 16, at least HETIS_ATTN_CONTROL_BYTES; 256-byte
+ * aligned.  Errors: NULL, WORKSPACE, LAUNCH. */
+int hetis_attn_workspace_init(void *workspace, size_t bytes, void *stream);
+
+/* Debug helper: synchronises `stream`, reads the workspace's error word into *flags (host,
+ * may be NULL) and clears it on the device.  workspace == NULL means the library-owned
+ * workspace of the current device (flags 0 if there is none).  Every wait inside the kernels
+ * is a polling loop with an iteration bound, so that a wave always reaches its end; a wait
+ * that ran into its bound sets a bit here (1: writer wave, 2: a result mailbox stayed full,
+ * 4: the ticket pool stayed empty).  Returns HETIS_OK when the word is zero,
+ * HETIS_ERR_DEVICE_WAIT otherwise (results written through this workspace since the last
+ * check are suspect), or NULL / LAUNCH. */
+int hetis_attn_workspace_status(void *workspace, void *stream, uint32_t *flags);
+
+/* Library-owned workspace of the current device: make it at least `bytes` large now (so that
+ * later calls, also under stream capture, find it), and free the workspaces of every device,
+ * outgrown ones included (synchronises each device).  Both optional. */
+int hetis_attn_reserve_workspace(size_t bytes);
 int hetis_attn_release_workspace(void);
 
 /*
@@ -130,7 +190,8 @@ int hetis_attn_release_workspace(void);
  * hetis_attn_split_num_chunks: C_max = ceil(max_seq_len / chunk_tokens), or a
  *   negative status.  chunk_tokens must be a positive multiple of 16, at most 1024.
  * hetis_attn_split_workspace_bytes: sizes in bytes of the two partial buffers
- *   (host out-pointers).
+ *   (host out-pointers; a status is returned, so that a bad argument is not mistaken for
+ *   a size).
  */
 int hetis_attn_split_num_chunks(int32_t max_seq_len, int32_t chunk_tokens);
 int hetis_attn_split_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,
@@ -145,6 +206,10 @@ int hetis_attn_split_workspace_bytes(const hetis_attn_shape *shape, int32_t n_se
  * (the r rows of one chunk are adjacent, so a chunk's result is one contiguous run).
  * Entries of chunks c >= ceil(L_b / chunk_tokens) are not written.
  * max_seq_len (host) bounds every seq_lens[b]; it fixes C_max and the grid.
+ * hetis_attn_decode_split_ws takes its control words from the caller: `control` is a
+ * 256-byte aligned device buffer of HETIS_ATTN_CONTROL_BYTES, zeroed once (it is a
+ * workspace with no partial area); hetis_attn_decode_split uses the control words of the
+ * library-owned workspace (rules as for hetis_attn_decode).
  * Errors: as hetis_attn_decode, plus WORKSPACE when max_seq_len is not in
  * [1, 16 * max_blocks_per_seq].
  */
@@ -153,6 +218,12 @@ int hetis_attn_decode_split(const hetis_attn_shape *shape, const void *q, const 
                             const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
                             float scale, int32_t chunk_tokens, int32_t max_seq_len,
                             float *o_partial, float *lse_partial, void *stream);
+int hetis_attn_decode_split_ws(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                               const void *v_cache, const int32_t *block_table,
+                               const int32_t *seq_lens, const int32_t *head_ids,
+                               int32_t n_sel_heads, float scale, int32_t chunk_tokens,
+                               int32_t max_seq_len, float *o_partial, float *lse_partial,
+                               void *control, void *stream);
 
 /*
  * Log-sum-exp merge of the partials, ascending chunk order, in fp32:
@@ -204,15 +275,22 @@ int hetis_attn_validate(const hetis_attn_shape *shape, const int32_t *block_tabl
  * of `out` that no pair names are left untouched.  A (sequence, head) listed twice is computed
  * twice (same bytes written).  n_pairs = 0 is a no-op; at most 65535 pairs per call.
  * The arithmetic of a pair is that of hetis_attn_decode for the same sequence length: the
- * rows agree bit for bit with an all-heads run over the same tile contents.  Uses the same
- * library-owned workspace as hetis_attn_decode (same rules for overlapping calls).
- * Errors: NULL, BAD_SHAPE, UNSUPPORTED, ALLOC, LAUNCH.
+ * rows agree bit for bit with an all-heads run over the same tile contents.
+ * hetis_attn_decode_pairs_ws runs from the caller's workspace
+ * (hetis_attn_decode_pairs_workspace_bytes), hetis_attn_decode_pairs from the library-owned
+ * one; the rules are those of hetis_attn_decode_ws / hetis_attn_decode.
+ * Errors: NULL, BAD_SHAPE, UNSUPPORTED, WORKSPACE, ALLOC, LAUNCH.
  */
 int hetis_attn_decode_pairs(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
                             const void *v_tiles, const int32_t *block_table,
                             const int32_t *seq_lens, const int32_t *pair_seq,
                             const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
                             void *stream);
+int hetis_attn_decode_pairs_ws(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
+                               const void *v_tiles, const int32_t *block_table,
+                               const int32_t *seq_lens, const int32_t *pair_seq,
+                               const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
+                               void *workspace, size_t workspace_bytes, void *stream);
 
 /* Debug helper like hetis_attn_validate for the pairs form: sequence ids, head ids, lengths
  * and every tile id a call would read (0 <= id < num_tiles). */

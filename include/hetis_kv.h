@@ -16,8 +16,9 @@
  * decode work).
  *
  * Conventions: those of hetis_attn.h (device pointers unless marked host, caller
- * owns all buffers, calls enqueue on `stream` and return, status codes, no
- * allocation, nothing printed).  In addition:
+ * owns all buffers, calls enqueue on `stream` and return, status codes, nothing
+ * printed).  The kernels of this header use no memory besides their arguments:
+ * no entry point here allocates, keeps state or synchronises.  In addition:
  *   - New rows and fetched rows are fp16 [n_tokens, n_kv_heads, head_dim],
  *     indexed by the model's KV head id like the query rows; only rows of
  *     heads in head_ids are read / written.  The kernels move bytes and never

@@ -26,6 +26,8 @@ HETIS_ERR_LAUNCH = -6
 HETIS_ERR_ALLOC = -7
 HETIS_ERR_BAD_CONTENT = -8
 HETIS_ERR_INFEASIBLE = -9
+HETIS_ERR_DEVICE_WAIT = -10
+HETIS_ATTN_CONTROL_BYTES = 256
 
 
 class hetis_attn_shape(C.Structure):
@@ -80,6 +82,24 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_decode.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
     lib.hetis_attn_release_workspace.restype = C.c_int
     lib.hetis_attn_release_workspace.argtypes = []
+    lib.hetis_attn_reserve_workspace.restype = C.c_int
+    lib.hetis_attn_reserve_workspace.argtypes = [C.c_size_t]
+    lib.hetis_attn_decode_ws.restype = C.c_int
+    lib.hetis_attn_decode_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, C.c_size_t, vp]
+    lib.hetis_attn_decode_workspace_bytes.restype = C.c_int
+    lib.hetis_attn_decode_workspace_bytes.argtypes = [shp, i32, C.POINTER(C.c_size_t)]
+    lib.hetis_attn_decode_pairs_workspace_bytes.restype = C.c_int
+    lib.hetis_attn_decode_pairs_workspace_bytes.argtypes = [shp, i32, C.POINTER(C.c_size_t)]
+    lib.hetis_attn_workspace_init.restype = C.c_int
+    lib.hetis_attn_workspace_init.argtypes = [vp, C.c_size_t, vp]
+    lib.hetis_attn_workspace_status.restype = C.c_int
+    lib.hetis_attn_workspace_status.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
+    lib.hetis_attn_decode_split_ws.restype = C.c_int
+    lib.hetis_attn_decode_split_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, i32, i32,
+                                               vp, vp, vp, vp]
+    lib.hetis_attn_decode_pairs_ws.restype = C.c_int
+    lib.hetis_attn_decode_pairs_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp,
+                                               C.c_size_t, vp]
     lib.hetis_attn_split_num_chunks.restype = C.c_int
     lib.hetis_attn_split_num_chunks.argtypes = [i32, i32]
     lib.hetis_attn_split_workspace_bytes.restype = C.c_int
@@ -162,6 +182,43 @@ def hetis_attn_decode(shape, q, k_cache, v_cache, block_table, seq_lens, head_id
                                     int(n_sel_heads), float(scale), _ptr(out), _stream(stream))
 
 
+def hetis_attn_decode_ws(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
+                         scale, out, workspace, workspace_bytes, stream=None) -> int:
+    return load().hetis_attn_decode_ws(C.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                       _ptr(block_table), _ptr(seq_lens), _ptr(head_ids),
+                                       int(n_sel_heads), float(scale), _ptr(out), _ptr(workspace),
+                                       int(workspace_bytes), _stream(stream))
+
+
+def hetis_attn_decode_workspace_bytes(shape, n_sel_heads):
+    """(status, bytes)."""
+    n = C.c_size_t(0)
+    rc = load().hetis_attn_decode_workspace_bytes(C.byref(shape), int(n_sel_heads), C.byref(n))
+    return rc, n.value
+
+
+def hetis_attn_decode_pairs_workspace_bytes(shape, n_pairs):
+    """(status, bytes)."""
+    n = C.c_size_t(0)
+    rc = load().hetis_attn_decode_pairs_workspace_bytes(C.byref(shape), int(n_pairs), C.byref(n))
+    return rc, n.value
+
+
+def hetis_attn_workspace_init(workspace, nbytes, stream=None) -> int:
+    return load().hetis_attn_workspace_init(_ptr(workspace), int(nbytes), _stream(stream))
+
+
+def hetis_attn_workspace_status(workspace=None, stream=None):
+    """(status, flags); workspace None = the library-owned one of the current device."""
+    flags = C.c_uint32(0)
+    rc = load().hetis_attn_workspace_status(_ptr(workspace), _stream(stream), C.byref(flags))
+    return rc, flags.value
+
+
+def hetis_attn_reserve_workspace(nbytes: int) -> int:
+    return load().hetis_attn_reserve_workspace(int(nbytes))
+
+
 def hetis_attn_release_workspace() -> int:
     return load().hetis_attn_release_workspace()
 
@@ -187,6 +244,16 @@ def hetis_attn_decode_split(shape, q, k_cache, v_cache, block_table, seq_lens, h
                                           int(n_sel_heads), float(scale), int(chunk_tokens),
                                           int(max_seq_len), _ptr(o_partial), _ptr(lse_partial),
                                           _stream(stream))
+
+
+def hetis_attn_decode_split_ws(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                               n_sel_heads, scale, chunk_tokens, max_seq_len, o_partial,
+                               lse_partial, control, stream=None) -> int:
+    return load().hetis_attn_decode_split_ws(C.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                             _ptr(block_table), _ptr(seq_lens), _ptr(head_ids),
+                                             int(n_sel_heads), float(scale), int(chunk_tokens),
+                                             int(max_seq_len), _ptr(o_partial), _ptr(lse_partial),
+                                             _ptr(control), _stream(stream))
 
 
 def hetis_attn_merge(shape, o_partial, lse_partial, seq_lens, head_ids, n_sel_heads,
@@ -215,6 +282,16 @@ def hetis_attn_decode_pairs(shape, q, k_tiles, v_tiles, block_table, seq_lens, p
                                           _ptr(block_table), _ptr(seq_lens), _ptr(pair_seq),
                                           _ptr(pair_head), int(n_pairs), float(scale), _ptr(out),
                                           _stream(stream))
+
+
+def hetis_attn_decode_pairs_ws(shape, q, k_tiles, v_tiles, block_table, seq_lens, pair_seq,
+                               pair_head, n_pairs, scale, out, workspace, workspace_bytes,
+                               stream=None) -> int:
+    return load().hetis_attn_decode_pairs_ws(C.byref(shape), _ptr(q), _ptr(k_tiles), _ptr(v_tiles),
+                                             _ptr(block_table), _ptr(seq_lens), _ptr(pair_seq),
+                                             _ptr(pair_head), int(n_pairs), float(scale),
+                                             _ptr(out), _ptr(workspace), int(workspace_bytes),
+                                             _stream(stream))
 
 
 def hetis_attn_validate_pairs(shape, block_table, seq_lens, pair_seq, pair_head, n_pairs,

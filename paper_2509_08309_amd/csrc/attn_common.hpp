@@ -35,10 +35,22 @@ struct AttnParams {
     int32_t chunk_tokens;       // multiple of 16
     int32_t max_chunks;
     int32_t direct_single;      // 1: a sequence of <= 1 chunk is written to `out` by the partial pass
-    unsigned int *tickets;      // [2] device words, zero between launches: item tickets drawn,
-                                // workgroups finished
+    unsigned int *control;      // device words of the call's workspace (see kCtl* below)
     float scale_log2;           // scale * log2(e): scores are kept in the base-2 domain
 };
+
+// Control words at the start of a call's workspace.  All are zero between launches: the last
+// workgroup to leave a launch sets the first two back; kCtlError is sticky (only the host
+// clears it) and records that a bounded wait inside a kernel expired, which means that the
+// launch may have dropped or overwritten a result.
+enum : int { kCtlTickets = 0, kCtlGone = 1, kCtlError = 2 };
+enum : unsigned { kErrWriterWait = 1u, kErrMailboxWait = 2u, kErrTicketWait = 4u };
+constexpr int kControlBytes = 256;
+
+__device__ __forceinline__ void report_error(unsigned int *control, unsigned flag)
+{
+    __hip_atomic_fetch_or(control + kCtlError, flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }

@@ -16,8 +16,8 @@
 // lane), and put into a small LDS pool from which the streaming waves take them, ready to
 // use, with an LDS atomic shortly before they finish an item.  Which wave computes an item has no
 // influence on the item's arithmetic.  The ticket counter and a counter of finished
-// workgroups live in a small device buffer (AttnParams::tickets); the workgroup that
-// finishes last sets both back to zero for the next launch.
+// workgroups are control words of the call's workspace (AttnParams::control); the workgroup
+// that finishes last sets both back to zero for the next launch.
 //
 // A workgroup is NW streaming waves plus one writer wave; after the prologue they never
 // meet at a barrier.
@@ -36,7 +36,9 @@
 // Mailbox protocol (flag is a workgroup-scope atomic in LDS): EMPTY -> the producer fills
 // data and header -> FULL -> the writer copies it out -> EMPTY.  A producer that has no more
 // items marks its next mailbox DONE; the writer leaves when all NW are DONE.  All waits are
-// polling loops with an iteration bound, so every wave reaches its end whatever happens.
+// polling loops with an iteration bound, so every wave reaches its end whatever happens; a
+// wait that runs into its bound sets a flag in the workspace's error word, which the host
+// reads with hetis_attn_workspace_status (the launch may then have lost a result).
 // Dynamic LDS: int lens[batch], int firstF[batch + 1], int firstT[4][batch + 1], int
 // hids[n_sel] (pairs mode: hids[batch], pseq[batch]); NW x 2 mailboxes; NW per-wave staging
 // areas of Policy::kWaveLdsBytes.
@@ -358,8 +360,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 if (!exhausted) {
                     unsigned t = 0;
                     if (lane == 0)
-                        t = __hip_atomic_fetch_add(p.tickets, (unsigned)n_draw, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
+                        t = __hip_atomic_fetch_add(p.control + kCtlTickets, (unsigned)n_draw,
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     base = 2ll * stride + __builtin_amdgcn_readfirstlane(t);
                     last_base = base;
                     if (base + n_draw >= total) exhausted = true;
@@ -396,11 +398,14 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // every streaming wave of this workgroup is done, so no more tickets will be drawn
         // here: count the workgroup out; the last one to leave rearms both counters
         if (lane == 0) {
-            const unsigned gone = __hip_atomic_fetch_add(p.tickets + 1, 1u, __ATOMIC_RELAXED,
+            if (done_mask != (1 << NW) - 1) report_error(p.control, kErrWriterWait);
+            const unsigned gone = __hip_atomic_fetch_add(p.control + kCtlGone, 1u, __ATOMIC_RELAXED,
                                                          __HIP_MEMORY_SCOPE_AGENT);
             if (gone == gridDim.x - 1) {
-                __hip_atomic_store(p.tickets + 0, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(p.tickets + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(p.control + kCtlTickets, 0u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(p.control + kCtlGone, 0u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         return;
@@ -445,9 +450,10 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // bounded wait for a mailbox of this wave to be empty
     auto wait_empty = [&](Mail &mb) {
         for (int spin = 0; spin < kSpinLimit; ++spin) {
-            if (__builtin_amdgcn_readfirstlane(mail_load(&mb.flag)) == kMailEmpty) break;
+            if (__builtin_amdgcn_readfirstlane(mail_load(&mb.flag)) == kMailEmpty) return;
             __builtin_amdgcn_s_sleep(2);
         }
+        if (lane == 0) report_error(p.control, kErrMailboxWait);
     };
     // next item from the workgroup's pool, decoded by the writer wave (flags 0 = none left)
     auto take_ticket = [&]() {
@@ -461,6 +467,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             if (end > i) return pool.desc[i % kPoolSize];
             __builtin_amdgcn_s_sleep(2);
         }
+        if (lane == 0) report_error(p.control, kErrTicketWait);
         ItemDesc none{};
         return none;
     };

@@ -5,6 +5,7 @@
 
 #include <hip/hip_ext.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <mutex>
 #include <vector>
@@ -95,60 +96,31 @@ static int device_cu_count()
     return cus[dev];
 }
 
-// Resident workgroups per compute unit of a persistent-kernel instantiation (cached per
-// instantiation and LDS size).
+// Resident workgroups per compute unit of a persistent-kernel instantiation, cached per
+// (kernel, dynamic LDS bytes, device): the LDS size follows the batch, so a serving loop with
+// a few recurring batch sizes asks the runtime once per size.
 template <class Kernel>
 static int resident_per_cu(Kernel kernel, int threads, size_t lds)
 {
+    struct Entry {
+        const void *kernel;
+        size_t lds;
+        int dev, occ;
+    };
     static std::mutex mu;
-    static size_t cached_lds = (size_t)-1;
-    static int cached_occ = 0;
-    std::lock_guard<std::mutex> lock(mu);
-    if (cached_lds != lds) {
-        int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds) != hipSuccess || n < 1)
-            return 0;
-        cached_occ = n;
-        cached_lds = lds;
-    }
-    return cached_occ;
-}
-
-// Ticket counters of the persistent kernel: kTicketSlots pairs of device words per device,
-// zeroed when allocated and left at zero by every launch that uses them.  Successive
-// launches rotate through the slots, so launches that overlap on different streams do not
-// share a pair unless more than kTicketSlots of them are in flight at once.
-constexpr int kTicketSlots = 64;
-struct TicketBuf {
-    unsigned int *ptr = nullptr;
-    unsigned int next = 0;
-};
-static std::mutex g_ticket_mutex;
-static std::vector<TicketBuf> g_tickets;
-
-static int tickets_for(unsigned int **out)
-{
-    std::lock_guard<std::mutex> lock(g_ticket_mutex);
+    static std::vector<Entry> cache;
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return HETIS_ERR_ALLOC;
-    if ((size_t)dev >= g_tickets.size()) g_tickets.resize(dev + 1);
-    TicketBuf &t = g_tickets[dev];
-    if (!t.ptr) {
-        void *ptr = nullptr;
-        const size_t bytes = kTicketSlots * 2 * sizeof(unsigned int);
-        if (hipMalloc(&ptr, bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return HETIS_ERR_ALLOC;
-        }
-        if (hipMemset(ptr, 0, bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-            (void)hipFree(ptr);
-            (void)hipGetLastError();
-            return HETIS_ERR_ALLOC;
-        }
-        t.ptr = static_cast<unsigned int *>(ptr);
-    }
-    *out = t.ptr + 2 * (t.next++ % kTicketSlots);
-    return HETIS_OK;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    const void *key = reinterpret_cast<const void *>(kernel);
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Entry &e : cache)
+        if (e.kernel == key && e.lds == lds && e.dev == dev) return e.occ;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds) != hipSuccess || n < 1)
+        return 0;
+    if (cache.size() >= 256) cache.clear();
+    cache.push_back(Entry{key, lds, dev, n});
+    return n;
 }
 
 // Optional events attached to the dispatch of the chunk kernel (measurement hook, per host
@@ -187,8 +159,6 @@ static int launch_persistent(AttnParams p, int batch, hipStream_t st)
         return v > 0 ? v : kWgsPerCu;
     }();
     if (occ > env_wgs) occ = env_wgs;
-    const int rc = tickets_for(&p.tickets);
-    if (rc != HETIS_OK) return rc;
     const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
     int64_t G = (int64_t)cus * occ;
     const int64_t enough = (max_items + NW - 1) / NW;     // one item per streaming wave
@@ -201,12 +171,18 @@ static int launch_persistent(AttnParams p, int batch, hipStream_t st)
 // query groups of 1 or 2, MFMA for groups of 4 or 8; batches too large for the persistent
 // kernel's LDS tables take the simple one-workgroup-per-chunk-slot kernel.  `batch` is the
 // number of rows of the enumeration: sequences, or (sequence, head) pairs in pairs mode.
+static bool takes_simple_kernel(int rows, int n_kv_heads, int max_chunks)
+{
+    // judged by the shape (all KV heads), not by how many heads this call selects
+    const int64_t max_items = (int64_t)rows * max_chunks * n_kv_heads;
+    return rows > kMaxPersistBatch || n_kv_heads > kMaxPersistHeads || max_items >= (int64_t)1 << 31;
+}
+
 template <int D, int R>
-static int launch_chunk(const AttnParams &p, int batch, hipStream_t st)
+static int launch_chunk(const AttnParams &p, int batch, int n_kv_heads, hipStream_t st)
 {
     const bool pairs = p.pair_seq != nullptr;
-    const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
-    if (batch > kMaxPersistBatch || p.n_sel > kMaxPersistHeads || max_items >= (int64_t)1 << 31) {
+    if (takes_simple_kernel(batch, pairs ? 1 : n_kv_heads, p.max_chunks)) {
         if (batch > 65535 || p.n_sel > 65535) return HETIS_ERR_UNSUPPORTED;   // grid limits
         dim3 grid(p.max_chunks, p.n_sel, batch);
         launch_timed(attn_chunk_vec_kernel<D, R, kVecWaves>, grid, dim3(kVecWaves * 64), 0, st, p);
@@ -220,19 +196,15 @@ static int launch_chunk(const AttnParams &p, int batch, hipStream_t st)
                      : launch_persistent<VecPolicy<D, R>, false>(p, batch, st);
 }
 
-static int dispatch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
+static int launch_chunks(const AttnParams &p, int D, int r, int batch, int n_kv_heads,
+                         hipStream_t st)
 {
 #define HETIS_CASE(DD, RR) \
-    if (D == DD && r == RR) return launch_chunk<DD, RR>(p, batch, st);
+    if (D == DD && r == RR) return launch_chunk<DD, RR>(p, batch, n_kv_heads, st);
     HETIS_CASE(128, 1) HETIS_CASE(128, 2) HETIS_CASE(128, 4) HETIS_CASE(128, 8)
     HETIS_CASE(64, 1) HETIS_CASE(64, 2) HETIS_CASE(64, 4) HETIS_CASE(64, 8)
 #undef HETIS_CASE
     return HETIS_ERR_UNSUPPORTED;
-}
-
-static int launch_chunks(const AttnParams &p, int D, int r, int batch, hipStream_t st)
-{
-    return dispatch_chunks(p, D, r, batch, st);
 }
 
 // `batch`: sequences, or pairs in pairs mode (p.n_sel is 1 there)
@@ -245,35 +217,106 @@ static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream
         attn_merge_kernel<64><<<grid, 64, 0, st>>>(p, r);
 }
 
-// Internal workspace of hetis_attn_decode (fp32 chunk partials), one per device, grown on
-// demand; its contents are meaningless between launches.
-struct Workspace {
-    float *ptr = nullptr;
+// ---- workspaces.  Layout of a decode workspace (all offsets multiples of 256 bytes):
+//   [0, kControlBytes)   control words (tickets drawn, workgroups finished, error word)
+//   o_partial            fp32 [rows, n_sel, max_chunks, r, D]
+//   lse_partial          fp32 [rows, n_sel, max_chunks, r]
+// rows = sequences, or pairs in pairs mode (n_sel = 1 there).
+struct WsLayout {
+    size_t o_partial = 0, lse_partial = 0, total = kControlBytes;
+};
+constexpr size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static WsLayout decode_ws_layout(int64_t rows, int n_sel, int group, int D, int max_chunks)
+{
+    WsLayout w;
+    if (max_chunks <= 1 || rows <= 0) return w;      // every sequence is written directly
+    const size_t partial_rows = (size_t)rows * n_sel * group * max_chunks;
+    w.o_partial = kControlBytes;
+    w.lse_partial = align256(w.o_partial + partial_rows * D * sizeof(float));
+    w.total = align256(w.lse_partial + partial_rows * sizeof(float));
+    return w;
+}
+
+static int decode_max_chunks(const hetis_attn_shape *s, int group)
+{
+    const int chunk = decode_chunk_tokens(group);
+    const int64_t max_tokens = (int64_t)s->max_blocks_per_seq * kBlockTokens;
+    return (int)((max_tokens + chunk - 1) / chunk);
+}
+
+static int check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (!ws) return HETIS_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0 || have < need) return HETIS_ERR_WORKSPACE;
+    return HETIS_OK;
+}
+
+__global__ void zero_fill_kernel(uint4 *dst, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+static int zero_fill(void *ptr, size_t bytes, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 2048);
+    zero_fill_kernel<<<blocks, 256, 0, st>>>(static_cast<uint4 *>(ptr), n16);
+    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
+
+// Library-owned workspace of the convenience entry points, one per device.  It only ever
+// grows; a buffer that has been outgrown stays allocated until hetis_attn_release_workspace,
+// because a HIP graph captured earlier holds its address.  Nothing is allocated on a
+// capturing stream.
+struct OwnedWs {
+    void *ptr = nullptr;
     size_t bytes = 0;
+    std::vector<void *> outgrown;
 };
 static std::mutex g_ws_mutex;
-static std::vector<Workspace> g_ws;
+static std::vector<OwnedWs> g_ws;
 
-static int workspace_for(size_t need, float **out)
+static bool stream_is_capturing(hipStream_t st)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return true;      // e.g. the legacy stream while another stream captures: do not allocate
+    }
+    return status != hipStreamCaptureStatusNone;
+}
+
+// `st` == nullptr with `may_be_capturing` false: called outside any launch (reserve).
+static int owned_workspace(size_t need, hipStream_t st, bool may_be_capturing, void **out)
 {
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return HETIS_ERR_ALLOC;
     if ((size_t)dev >= g_ws.size()) g_ws.resize(dev + 1);
-    Workspace &w = g_ws[dev];
+    OwnedWs &w = g_ws[dev];
     if (w.bytes < need) {
-        if (w.ptr) {
-            if (hipDeviceSynchronize() != hipSuccess) return HETIS_ERR_ALLOC;
-            (void)hipFree(w.ptr);
-            w = Workspace();
-        }
-        const size_t want = need + need / 4;
+        if (may_be_capturing && stream_is_capturing(st)) return HETIS_ERR_WORKSPACE;
+        const size_t want = align256(need + need / 4);
         void *ptr = nullptr;
         if (hipMalloc(&ptr, want) != hipSuccess) {
             (void)hipGetLastError();
             return HETIS_ERR_ALLOC;
         }
-        w.ptr = static_cast<float *>(ptr);
+        // zero the whole buffer before its first use, in stream order with that use
+        if (zero_fill(ptr, want, st) != HETIS_OK) {
+            (void)hipFree(ptr);
+            return HETIS_ERR_ALLOC;
+        }
+        if (!may_be_capturing && hipStreamSynchronize(st) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(ptr);
+            return HETIS_ERR_ALLOC;
+        }
+        if (w.ptr) w.outgrown.push_back(w.ptr);
+        w.ptr = ptr;
         w.bytes = want;
     }
     *out = w.ptr;
@@ -308,7 +351,7 @@ using namespace hetis;
 
 extern "C" {
 
-int hetis_attn_version(void) { return 100; }
+int hetis_attn_version(void) { return 200; }
 
 const char *hetis_attn_status_string(int status)
 {
@@ -318,13 +361,55 @@ const char *hetis_attn_status_string(int status)
     case HETIS_ERR_BAD_SHAPE: return "bad shape";
     case HETIS_ERR_UNSUPPORTED: return "unsupported head_dim, block_size, group size or chunk_tokens";
     case HETIS_ERR_BAD_HEADS: return "n_sel_heads outside [1, n_kv_heads]";
-    case HETIS_ERR_WORKSPACE: return "max_seq_len inconsistent with shape or chunking";
+    case HETIS_ERR_WORKSPACE:
+        return "max_seq_len inconsistent with shape or chunking, or workspace too small, "
+               "misaligned or in need of growth during stream capture";
     case HETIS_ERR_LAUNCH: return "kernel launch failed";
     case HETIS_ERR_ALLOC: return "internal workspace allocation failed";
     case HETIS_ERR_BAD_CONTENT: return "device-side argument content out of range";
     case HETIS_ERR_INFEASIBLE: return "capacities cannot hold the requests";
+    case HETIS_ERR_DEVICE_WAIT: return "a bounded wait inside a kernel expired";
     default: return "unknown status";
     }
+}
+
+// Shared body of hetis_attn_decode / hetis_attn_decode_ws.  `workspace` == nullptr: take the
+// library-owned one.
+static int decode_common(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                         const void *v_cache, const int32_t *block_table, const int32_t *seq_lens,
+                         const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
+                         void *workspace, size_t workspace_bytes, bool owned, void *stream)
+{
+    Checked c;
+    if (!shape || !q || !k_cache || !v_cache || !block_table || !seq_lens || !head_ids || !out)
+        return HETIS_ERR_NULL;
+    int rc = check_shape(shape, n_sel_heads, &c);
+    if (rc != HETIS_OK) return rc;
+    const int max_chunks = decode_max_chunks(shape, c.group);
+    const WsLayout lay = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
+                                          max_chunks);
+    hipStream_t st = (hipStream_t)stream;
+    if (owned)
+        rc = owned_workspace(lay.total, st, true, &workspace);
+    else
+        rc = check_workspace(workspace, workspace_bytes, lay.total);
+    if (rc != HETIS_OK) return rc;
+
+    AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                               n_sel_heads, scale, out);
+    p.chunk_tokens = decode_chunk_tokens(c.group);
+    p.max_chunks = max_chunks;
+    p.direct_single = 1;
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    p.control = reinterpret_cast<unsigned int *>(base);
+    if (max_chunks > 1) {
+        p.o_partial = reinterpret_cast<float *>(base + lay.o_partial);
+        p.lse_partial = reinterpret_cast<float *>(base + lay.lse_partial);
+    }
+    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, shape->n_kv_heads, st);
+    if (rc != HETIS_OK) return rc;
+    if (max_chunks > 1) launch_merge(p, shape->head_dim, c.group, shape->batch, st);
+    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
 
 int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *k_cache,
@@ -332,31 +417,100 @@ int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *
                       const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
                       void *stream)
 {
-    Checked c;
-    if (!shape || !q || !k_cache || !v_cache || !block_table || !seq_lens || !head_ids || !out)
-        return HETIS_ERR_NULL;
-    int rc = check_shape(shape, n_sel_heads, &c);
-    if (rc != HETIS_OK) return rc;
+    return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
+                         scale, out, nullptr, 0, true, stream);
+}
 
-    AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
-                               n_sel_heads, scale, out);
-    const int chunk = decode_chunk_tokens(c.group);
-    p.chunk_tokens = chunk;
-    const int64_t max_tokens = (int64_t)shape->max_blocks_per_seq * kBlockTokens;
-    p.max_chunks = (int)((max_tokens + chunk - 1) / chunk);
-    p.direct_single = 1;
-    hipStream_t st = (hipStream_t)stream;
-    if (p.max_chunks > 1) {
-        const size_t rows = (size_t)shape->batch * n_sel_heads * c.group * p.max_chunks;
-        float *ws = nullptr;
-        rc = workspace_for(rows * (shape->head_dim + 1) * sizeof(float), &ws);
-        if (rc != HETIS_OK) return rc;
-        p.o_partial = ws;
-        p.lse_partial = ws + rows * shape->head_dim;
-    }
-    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, st);
+int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                         const void *v_cache, const int32_t *block_table,
+                         const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
+                         float scale, void *out, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    if (!workspace) return HETIS_ERR_NULL;
+    return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
+                         scale, out, workspace, workspace_bytes, false, stream);
+}
+
+int hetis_attn_decode_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,
+                                      size_t *bytes)
+{
+    Checked c;
+    if (!shape || !bytes) return HETIS_ERR_NULL;
+    const int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
-    if (p.max_chunks > 1) launch_merge(p, shape->head_dim, c.group, shape->batch, st);
+    *bytes = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
+                              decode_max_chunks(shape, c.group)).total;
+    return HETIS_OK;
+}
+
+static int check_pairs(const hetis_attn_shape *shape, int32_t n_pairs, Checked *c)
+{
+    int rc = check_shape(shape, 1, c);
+    if (rc != HETIS_OK) return rc;
+    if (n_pairs < 0) return HETIS_ERR_BAD_SHAPE;
+    if (n_pairs > 65535) return HETIS_ERR_UNSUPPORTED;
+    // the pool holds single-head tiles: one stride, no head term
+    const int64_t tile = (int64_t)shape->block_size * shape->head_dim;
+    c->stride_block = shape->kv_stride_block ? shape->kv_stride_block : tile;
+    if (c->stride_block % 8 != 0 || c->stride_block < tile) return HETIS_ERR_BAD_SHAPE;
+    c->stride_head = 0;
+    return HETIS_OK;
+}
+
+int hetis_attn_decode_pairs_workspace_bytes(const hetis_attn_shape *shape, int32_t n_pairs,
+                                            size_t *bytes)
+{
+    Checked c;
+    if (!shape || !bytes) return HETIS_ERR_NULL;
+    const int rc = check_pairs(shape, n_pairs, &c);
+    if (rc != HETIS_OK) return rc;
+    *bytes = decode_ws_layout(n_pairs, 1, c.group, shape->head_dim,
+                              decode_max_chunks(shape, c.group)).total;
+    return HETIS_OK;
+}
+
+static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
+                               const void *v_tiles, const int32_t *block_table,
+                               const int32_t *seq_lens, const int32_t *pair_seq,
+                               const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
+                               void *workspace, size_t workspace_bytes, bool owned, void *stream)
+{
+    Checked c;
+    if (!shape || !q || !k_tiles || !v_tiles || !block_table || !seq_lens || !pair_seq ||
+        !pair_head || !out)
+        return HETIS_ERR_NULL;
+    int rc = check_pairs(shape, n_pairs, &c);
+    if (rc != HETIS_OK) return rc;
+    const int max_chunks = decode_max_chunks(shape, c.group);
+    const WsLayout lay = decode_ws_layout(n_pairs, 1, c.group, shape->head_dim, max_chunks);
+    if (!owned) {
+        rc = check_workspace(workspace, workspace_bytes, lay.total);
+        if (rc != HETIS_OK) return rc;
+    }
+    if (n_pairs == 0) return HETIS_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (owned) {
+        rc = owned_workspace(lay.total, st, true, &workspace);
+        if (rc != HETIS_OK) return rc;
+    }
+
+    AttnParams p = make_params(shape, c, q, k_tiles, v_tiles, block_table, seq_lens, nullptr, 1,
+                               scale, out);
+    p.pair_seq = pair_seq;
+    p.pair_head = pair_head;
+    p.chunk_tokens = decode_chunk_tokens(c.group);
+    p.max_chunks = max_chunks;
+    p.direct_single = 1;
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    p.control = reinterpret_cast<unsigned int *>(base);
+    if (max_chunks > 1) {
+        p.o_partial = reinterpret_cast<float *>(base + lay.o_partial);
+        p.lse_partial = reinterpret_cast<float *>(base + lay.lse_partial);
+    }
+    rc = launch_chunks(p, shape->head_dim, c.group, n_pairs, shape->n_kv_heads, st);
+    if (rc != HETIS_OK) return rc;
+    if (max_chunks > 1) launch_merge(p, shape->head_dim, c.group, n_pairs, st);
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
 
@@ -366,75 +520,76 @@ int hetis_attn_decode_pairs(const hetis_attn_shape *shape, const void *q, const 
                             const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
                             void *stream)
 {
-    Checked c;
-    if (!shape || !q || !k_tiles || !v_tiles || !block_table || !seq_lens || !pair_seq ||
-        !pair_head || !out)
-        return HETIS_ERR_NULL;
-    int rc = check_shape(shape, 1, &c);
-    if (rc != HETIS_OK) return rc;
-    if (n_pairs < 0) return HETIS_ERR_BAD_SHAPE;
-    if (n_pairs > 65535) return HETIS_ERR_UNSUPPORTED;
-    // the pool holds single-head tiles: one stride, no head term
-    const int64_t tile = (int64_t)shape->block_size * shape->head_dim;
-    c.stride_block = shape->kv_stride_block ? shape->kv_stride_block : tile;
-    if (c.stride_block % 8 != 0 || c.stride_block < tile) return HETIS_ERR_BAD_SHAPE;
-    c.stride_head = 0;
-    if (n_pairs == 0) return HETIS_OK;
+    return decode_pairs_common(shape, q, k_tiles, v_tiles, block_table, seq_lens, pair_seq,
+                               pair_head, n_pairs, scale, out, nullptr, 0, true, stream);
+}
 
-    AttnParams p = make_params(shape, c, q, k_tiles, v_tiles, block_table, seq_lens, nullptr, 1,
-                               scale, out);
-    p.pair_seq = pair_seq;
-    p.pair_head = pair_head;
-    const int chunk = decode_chunk_tokens(c.group);
-    p.chunk_tokens = chunk;
-    const int64_t max_tokens = (int64_t)shape->max_blocks_per_seq * kBlockTokens;
-    p.max_chunks = (int)((max_tokens + chunk - 1) / chunk);
-    p.direct_single = 1;
-    hipStream_t st = (hipStream_t)stream;
-    if (p.max_chunks > 1) {
-        const size_t rows = (size_t)n_pairs * c.group * p.max_chunks;
-        float *ws = nullptr;
-        rc = workspace_for(rows * (shape->head_dim + 1) * sizeof(float), &ws);
-        if (rc != HETIS_OK) return rc;
-        p.o_partial = ws;
-        p.lse_partial = ws + rows * shape->head_dim;
+int hetis_attn_decode_pairs_ws(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
+                               const void *v_tiles, const int32_t *block_table,
+                               const int32_t *seq_lens, const int32_t *pair_seq,
+                               const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return HETIS_ERR_NULL;
+    return decode_pairs_common(shape, q, k_tiles, v_tiles, block_table, seq_lens, pair_seq,
+                               pair_head, n_pairs, scale, out, workspace, workspace_bytes, false,
+                               stream);
+}
+
+int hetis_attn_workspace_init(void *workspace, size_t bytes, void *stream)
+{
+    if (!workspace) return HETIS_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || bytes < (size_t)kControlBytes ||
+        bytes % 16 != 0)
+        return HETIS_ERR_WORKSPACE;
+    return zero_fill(workspace, bytes, (hipStream_t)stream);
+}
+
+int hetis_attn_workspace_status(void *workspace, void *stream, uint32_t *flags)
+{
+    if (flags) *flags = 0;
+    if (!workspace) {
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
+        int dev = 0;
+        if (g_ws.empty()) return HETIS_OK;             // nothing was ever allocated: no HIP call
+        if (hipGetDevice(&dev) != hipSuccess) return HETIS_ERR_LAUNCH;
+        if ((size_t)dev >= g_ws.size() || !g_ws[dev].ptr) return HETIS_OK;
+        workspace = g_ws[dev].ptr;
     }
-    rc = launch_chunks(p, shape->head_dim, c.group, n_pairs, st);
-    if (rc != HETIS_OK) return rc;
-    if (p.max_chunks > 1) launch_merge(p, shape->head_dim, c.group, n_pairs, st);
-    return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t word = 0;
+    unsigned int *dev_word = static_cast<unsigned int *>(workspace) + kCtlError;
+    if (hipStreamSynchronize(st) != hipSuccess ||
+        hipMemcpy(&word, dev_word, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess)
+        return HETIS_ERR_LAUNCH;
+    if (word != 0 && hipMemset(dev_word, 0, sizeof(word)) != hipSuccess) return HETIS_ERR_LAUNCH;
+    if (flags) *flags = word;
+    return word == 0 ? HETIS_OK : HETIS_ERR_DEVICE_WAIT;
+}
+
+int hetis_attn_reserve_workspace(size_t bytes)
+{
+    void *ws = nullptr;
+    return owned_workspace(std::max<size_t>(bytes, kControlBytes), nullptr, false, &ws);
 }
 
 int hetis_attn_release_workspace(void)
 {
     std::lock_guard<std::mutex> lock(g_ws_mutex);
-    int cur = 0;
     bool any = false;
-    for (size_t d = 0; d < g_ws.size(); ++d)
-        if (g_ws[d].ptr) any = true;
-    {
-        std::lock_guard<std::mutex> tlock(g_ticket_mutex);
-        for (size_t d = 0; d < g_tickets.size(); ++d)
-            if (g_tickets[d].ptr) any = true;
-    }
+    for (const OwnedWs &w : g_ws)
+        if (w.ptr || !w.outgrown.empty()) any = true;
     if (!any) return HETIS_OK;
+    int cur = 0;
     if (hipGetDevice(&cur) != hipSuccess) return HETIS_ERR_ALLOC;
     for (size_t d = 0; d < g_ws.size(); ++d) {
-        if (!g_ws[d].ptr) continue;
+        OwnedWs &w = g_ws[d];
+        if (!w.ptr && w.outgrown.empty()) continue;
         (void)hipSetDevice((int)d);
         (void)hipDeviceSynchronize();
-        (void)hipFree(g_ws[d].ptr);
-        g_ws[d] = Workspace();
-    }
-    {
-        std::lock_guard<std::mutex> tlock(g_ticket_mutex);
-        for (size_t d = 0; d < g_tickets.size(); ++d) {
-            if (!g_tickets[d].ptr) continue;
-            (void)hipSetDevice((int)d);
-            (void)hipDeviceSynchronize();
-            (void)hipFree(g_tickets[d].ptr);
-            g_tickets[d] = TicketBuf();
-        }
+        if (w.ptr) (void)hipFree(w.ptr);
+        for (void *old : w.outgrown) (void)hipFree(old);
+        w = OwnedWs();
     }
     (void)hipSetDevice(cur);
     return HETIS_OK;
@@ -465,11 +620,12 @@ int hetis_attn_split_workspace_bytes(const hetis_attn_shape *shape, int32_t n_se
     return HETIS_OK;
 }
 
-int hetis_attn_decode_split(const hetis_attn_shape *shape, const void *q, const void *k_cache,
-                            const void *v_cache, const int32_t *block_table,
-                            const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
-                            float scale, int32_t chunk_tokens, int32_t max_seq_len,
-                            float *o_partial, float *lse_partial, void *stream)
+static int decode_split_common(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                               const void *v_cache, const int32_t *block_table,
+                               const int32_t *seq_lens, const int32_t *head_ids,
+                               int32_t n_sel_heads, float scale, int32_t chunk_tokens,
+                               int32_t max_seq_len, float *o_partial, float *lse_partial,
+                               void *control, bool owned, void *stream)
 {
     Checked c;
     if (!shape || !q || !k_cache || !v_cache || !block_table || !seq_lens || !head_ids ||
@@ -479,6 +635,12 @@ int hetis_attn_decode_split(const hetis_attn_shape *shape, const void *q, const 
     if (rc != HETIS_OK) return rc;
     rc = check_chunking(shape, chunk_tokens, max_seq_len);
     if (rc != HETIS_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (owned)
+        rc = owned_workspace(kControlBytes, st, true, &control);
+    else
+        rc = check_workspace(control, kControlBytes, kControlBytes);
+    if (rc != HETIS_OK) return rc;
     AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
                                n_sel_heads, scale, nullptr);
     p.chunk_tokens = chunk_tokens;
@@ -486,9 +648,34 @@ int hetis_attn_decode_split(const hetis_attn_shape *shape, const void *q, const 
     p.direct_single = 0;
     p.o_partial = o_partial;
     p.lse_partial = lse_partial;
-    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, (hipStream_t)stream);
+    p.control = static_cast<unsigned int *>(control);
+    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, shape->n_kv_heads, st);
     if (rc != HETIS_OK) return rc;
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
+}
+
+int hetis_attn_decode_split(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                            const void *v_cache, const int32_t *block_table,
+                            const int32_t *seq_lens, const int32_t *head_ids, int32_t n_sel_heads,
+                            float scale, int32_t chunk_tokens, int32_t max_seq_len,
+                            float *o_partial, float *lse_partial, void *stream)
+{
+    return decode_split_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                               n_sel_heads, scale, chunk_tokens, max_seq_len, o_partial,
+                               lse_partial, nullptr, true, stream);
+}
+
+int hetis_attn_decode_split_ws(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                               const void *v_cache, const int32_t *block_table,
+                               const int32_t *seq_lens, const int32_t *head_ids,
+                               int32_t n_sel_heads, float scale, int32_t chunk_tokens,
+                               int32_t max_seq_len, float *o_partial, float *lse_partial,
+                               void *control, void *stream)
+{
+    if (!control) return HETIS_ERR_NULL;
+    return decode_split_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                               n_sel_heads, scale, chunk_tokens, max_seq_len, o_partial,
+                               lse_partial, control, false, stream);
 }
 
 int hetis_attn_merge(const hetis_attn_shape *shape, const float *o_partial,

@@ -49,6 +49,28 @@ class Dev:
         H.check(H.hetis_attn_decode(self.shape, self.q, self.k, self.v, self.bt, self.sl, hid, n,
                                     self.scale, out), "hetis_attn_decode")
         torch.cuda.synchronize()
+        no_expired_wait()
+        return out
+
+    def workspace(self, n_sel):
+        """A fresh caller-owned workspace for hetis_attn_decode_ws, control words zeroed."""
+        rc, nbytes = H.hetis_attn_decode_workspace_bytes(self.shape, n_sel)
+        H.check(rc, "decode_workspace_bytes")
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+        ws.fill_(0xAB)                    # stale contents everywhere ...
+        H.check(H.hetis_attn_workspace_init(ws, nbytes), "workspace_init")   # ... then the init call
+        return ws
+
+    def decode_ws(self, head_ids, ws, out=None, stream=None, sync=True, hid=None):
+        """`hid`: the (tensor, count) of self.heads(head_ids), which a caller that does not
+        synchronise must keep alive until the stream has passed the call."""
+        hid, n = self.heads(head_ids) if hid is None else hid
+        out = self.new_out() if out is None else out
+        H.check(H.hetis_attn_decode_ws(self.shape, self.q, self.k, self.v, self.bt, self.sl, hid, n,
+                                       self.scale, out, ws, ws.numel(), stream), "hetis_attn_decode_ws")
+        if sync:
+            torch.cuda.synchronize()
+            no_expired_wait(ws)
         return out
 
     def split(self, head_ids, chunk_tokens, max_seq_len, fill=float("nan")):
@@ -67,6 +89,7 @@ class Dev:
                                           hid, n, self.scale, chunk_tokens, max_seq_len, o_p,
                                           lse_p), "hetis_attn_decode_split")
         torch.cuda.synchronize()
+        no_expired_wait()
         return o_p, lse_p
 
     def merge(self, o_p, lse_p, head_ids, chunk_tokens, max_seq_len, out=None):
@@ -76,6 +99,13 @@ class Dev:
                                    max_seq_len, out), "hetis_attn_merge")
         torch.cuda.synchronize()
         return out
+
+
+def no_expired_wait(ws=None):
+    """The workspace's error word is zero: no bounded wait inside a kernel gave up (ws None: the
+    library-owned workspace)."""
+    rc, flags = H.hetis_attn_workspace_status(ws)
+    assert rc == 0 and flags == 0, f"a wait inside a kernel expired: status {rc}, flags {flags:#x}"
 
 
 def partials_as_rows(o_p: torch.Tensor, lse_p: torch.Tensor):

@@ -36,8 +36,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert H.hetis_attn_version() >= 100
-    seen = {H.hetis_attn_status_string(s) for s in range(0, -10, -1)}
-    assert len(seen) == 10 and "unknown status" not in seen
+    seen = {H.hetis_attn_status_string(s) for s in range(0, -11, -1)}
+    assert len(seen) == 11 and "unknown status" not in seen
     assert H.hetis_attn_status_string(-99) == "unknown status"
 
 
@@ -142,6 +142,69 @@ def test_validate_argument_errors(lib):
 
 def test_release_workspace_without_gpu_is_ok(lib):
     assert H.hetis_attn_release_workspace() == binding.HETIS_OK
+    # nothing was ever allocated: the status of the library-owned workspace needs no HIP call
+    assert H.hetis_attn_workspace_status(None, 0) == (binding.HETIS_OK, 0)
+
+
+WS = 0x10000    # a fake, 256-byte aligned workspace address
+
+
+def test_workspace_sizes(lib):
+    # c3's shape: 128 sequences x 13 heads x 16 chunks of 256 tokens x (128 + 1) floats, each
+    # area rounded up to 256 bytes, plus the control words
+    s = H.make_shape(128, 40, 40, 128, 256)
+    rows = 128 * 13 * 16
+    rc, n = H.hetis_attn_decode_workspace_bytes(s, 13)
+    assert rc == 0 and n == 256 + rows * 128 * 4 + rows * 4 and n % 256 == 0
+    # one chunk at most: only the control words
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 64, 16), 4) == (0, 256)
+    # grouped-query shapes use 768-token chunks
+    g = H.make_shape(256, 64, 8, 128, 256)
+    rows = 256 * 3 * 8 * 6
+    assert H.hetis_attn_decode_workspace_bytes(g, 3) == (0, 256 + rows * 128 * 4 + rows * 4)
+    assert H.hetis_attn_decode_pairs_workspace_bytes(s, 0) == (0, 256)
+    rows = 1721 * 16
+    up = lambda x: (x + 255) // 256 * 256
+    assert H.hetis_attn_decode_pairs_workspace_bytes(s, 1721) == (0, 256 + rows * 128 * 4 + up(rows * 4))
+    assert H.hetis_attn_decode_workspace_bytes(s, 0)[0] == binding.HETIS_ERR_BAD_HEADS
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 96, 16), 4)[0] == binding.HETIS_ERR_UNSUPPORTED
+    assert H.hetis_attn_decode_pairs_workspace_bytes(s, -1)[0] == binding.HETIS_ERR_BAD_SHAPE
+    assert H.hetis_attn_decode_pairs_workspace_bytes(s, 65536)[0] == binding.HETIS_ERR_UNSUPPORTED
+    assert lib.hetis_attn_decode_workspace_bytes(C.byref(s), 13, None) == binding.HETIS_ERR_NULL
+
+
+def test_ws_entry_points_argument_errors(lib):
+    s = good()
+    rc, need = H.hetis_attn_decode_workspace_bytes(s, 4)
+    assert rc == 0
+
+    def call(ws=WS, nbytes=need, shape=s, n_sel=4, q=P):
+        return H.hetis_attn_decode_ws(shape, q, P, P, P, P, P, n_sel, 0.125, P, ws, nbytes, 0)
+    assert call(ws=None) == binding.HETIS_ERR_NULL
+    assert call(q=None) == binding.HETIS_ERR_NULL
+    assert call(nbytes=need - 1) == binding.HETIS_ERR_WORKSPACE
+    assert call(ws=WS + 64) == binding.HETIS_ERR_WORKSPACE              # not 256-byte aligned
+    assert call(n_sel=9) == binding.HETIS_ERR_BAD_HEADS
+    assert call(shape=H.make_shape(4, 8, 8, 96, 16)) == binding.HETIS_ERR_UNSUPPORTED
+
+    def pairs(ws=WS, nbytes=1 << 20, n_pairs=5, ps=P):
+        return H.hetis_attn_decode_pairs_ws(s, P, P, P, P, P, ps, P, n_pairs, 0.125, P, ws, nbytes, 0)
+    assert pairs(ws=None) == binding.HETIS_ERR_NULL
+    assert pairs(ps=None) == binding.HETIS_ERR_NULL
+    assert pairs(nbytes=128) == binding.HETIS_ERR_WORKSPACE
+    assert pairs(n_pairs=-1) == binding.HETIS_ERR_BAD_SHAPE
+    assert pairs(n_pairs=0) == binding.HETIS_OK                         # nothing to do, no HIP call
+
+    def split(control=WS, o=P):
+        return H.hetis_attn_decode_split_ws(s, P, P, P, P, P, P, 4, 0.125, 48, 256, o, P, control, 0)
+    assert split(control=None) == binding.HETIS_ERR_NULL
+    assert split(o=None) == binding.HETIS_ERR_NULL
+    assert split(control=WS + 8) == binding.HETIS_ERR_WORKSPACE
+
+    assert H.hetis_attn_workspace_init(None, 256, 0) == binding.HETIS_ERR_NULL
+    assert H.hetis_attn_workspace_init(WS, 128, 0) == binding.HETIS_ERR_WORKSPACE
+    assert H.hetis_attn_workspace_init(WS, 264, 0) == binding.HETIS_ERR_WORKSPACE   # not a multiple of 16
+    assert H.hetis_attn_workspace_init(WS + 16, 256, 0) == binding.HETIS_ERR_WORKSPACE
 
 
 def test_product_never_imports_the_checker():

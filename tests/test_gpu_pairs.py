@@ -8,7 +8,7 @@ import oracle
 import paper_2509_08309_amd as H
 from paper_2509_08309_amd import workloads as W
 
-from gpu_harness import SENTINEL, TOL, Dev, as_f64, bits, check_mask
+from gpu_harness import SENTINEL, TOL, Dev, as_f64, bits, check_mask, no_expired_wait
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -38,6 +38,7 @@ def run_pairs(pw, order=None, out=None):
     H.check(H.hetis_attn_decode_pairs(shape, pw.q, pw.k_tiles, pw.v_tiles, bt, sl, ps, ph,
                                       len(idx), s.scale, out), "hetis_attn_decode_pairs")
     torch.cuda.synchronize()
+    no_expired_wait()
     return out
 
 

@@ -11,7 +11,7 @@ import oracle
 import paper_2509_08309_amd as H
 from paper_2509_08309_amd import workloads as W
 
-from gpu_harness import (SENTINEL, TOL, Dev, as_f64, bits, check_rows, host_copy, partials_as_rows,
+from gpu_harness import (SENTINEL, TOL, Dev, as_f64, bits, check_rows, host_copy, no_expired_wait, partials_as_rows,
                          rows_as_partials, selected_rows, unselected_rows)
 
 pytestmark = pytest.mark.gpu
@@ -344,8 +344,8 @@ def test_graph_capture_and_replay():
 
 
 def test_two_streams_with_their_own_buffers():
-    """Split-KV calls on two streams at once (each with its own partial buffers and outputs)
-    give what the same calls give one after the other."""
+    """Split-KV calls on two streams at once (each with its own partial buffers, control words
+    and outputs) give what the same calls give one after the other."""
     w1 = W.make_custom([2000, 900, 3000, 64], 8, 8, 128, [0, 3, 5, 7], seed=93, device="cuda:0")
     w2 = W.make_custom([1200, 2500, 300], 16, 2, 128, [1, 0], seed=94, device="cuda:0")
     devs = [Dev(w1), Dev(w2)]
@@ -363,15 +363,17 @@ def test_two_streams_with_their_own_buffers():
         bufs.append((torch.empty((s.batch, len(h), C, s.group_size, s.head_dim), dtype=torch.float32,
                                  device="cuda:0"),
                      torch.empty((s.batch, len(h), C, s.group_size), dtype=torch.float32,
-                                 device="cuda:0"), d.new_out(), d.heads(h)))
+                                 device="cuda:0"), d.new_out(), d.heads(h),
+                     torch.zeros(H.binding.HETIS_ATTN_CONTROL_BYTES, dtype=torch.uint8, device="cuda:0")))
     torch.cuda.synchronize()
     for rep in range(6):
-        for d, h, m, st, (o_p, lse_p, out, (hid, n)) in zip(devs, heads, msl, streams, bufs):
-            H.check(H.hetis_attn_decode_split(d.shape, d.q, d.k, d.v, d.bt, d.sl, hid, n, d.scale, 512,
-                                              m, o_p, lse_p, st))
+        for d, h, m, st, (o_p, lse_p, out, (hid, n), ctl) in zip(devs, heads, msl, streams, bufs):
+            H.check(H.hetis_attn_decode_split_ws(d.shape, d.q, d.k, d.v, d.bt, d.sl, hid, n, d.scale,
+                                                 512, m, o_p, lse_p, ctl, st))
             H.check(H.hetis_attn_merge(d.shape, o_p, lse_p, d.sl, hid, n, 512, m, out, st))
     torch.cuda.synchronize()
-    for (o_p, lse_p, out, _), ref in zip(bufs, serial):
+    for (o_p, lse_p, out, _, ctl), ref in zip(bufs, serial):
+        no_expired_wait(ctl)
         assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
 
 
