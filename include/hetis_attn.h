@@ -152,6 +152,24 @@ int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const voi
                          float scale, void *out, void *workspace, size_t workspace_bytes,
                          void *stream);
 
+/*
+ * hetis_attn_decode for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and bit-identical results; the workspace is a static device
+ * array of HETIS_ATTN_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on
+ * holds it from the first use until the process ends).  The call makes no hipMalloc / hipFree
+ * and uses no allocating routine; it enqueues one small clearing kernel and the Attention
+ * kernels on `stream`.  A shape whose workspace (hetis_attn_decode_workspace_bytes) exceeds the
+ * array is refused with HETIS_ERR_WORKSPACE before anything is launched.  All calls on one GPU
+ * share that GPU's array: calls that may overlap (different streams) race; serialise them, or
+ * use hetis_attn_decode_ws.  Errors: NULL, BAD_SHAPE, UNSUPPORTED, BAD_HEADS, WORKSPACE, LAUNCH.
+ */
+#define HETIS_ATTN_STATIC_SCRATCH_BYTES (32u << 20)
+int hetis_attn_decode_static(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                             const void *v_cache, const int32_t *block_table,
+                             const int32_t *seq_lens, const int32_t *head_ids,
+                             int32_t n_sel_heads, float scale, void *out, void *stream);
+
 /* Workspace size in bytes (host out-pointer) of hetis_attn_decode_ws for this shape and
  * head count, and of hetis_attn_decode_pairs_ws for this shape and pair count (n_pairs >= 0). */
 int hetis_attn_decode_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,

@@ -28,6 +28,7 @@ HETIS_ERR_BAD_CONTENT = -8
 HETIS_ERR_INFEASIBLE = -9
 HETIS_ERR_DEVICE_WAIT = -10
 HETIS_ATTN_CONTROL_BYTES = 256
+HETIS_ATTN_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class hetis_attn_shape(C.Structure):
@@ -86,6 +87,8 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_reserve_workspace.argtypes = [C.c_size_t]
     lib.hetis_attn_decode_ws.restype = C.c_int
     lib.hetis_attn_decode_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, C.c_size_t, vp]
+    lib.hetis_attn_decode_static.restype = C.c_int
+    lib.hetis_attn_decode_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
     lib.hetis_attn_decode_workspace_bytes.restype = C.c_int
     lib.hetis_attn_decode_workspace_bytes.argtypes = [shp, i32, C.POINTER(C.c_size_t)]
     lib.hetis_attn_decode_pairs_workspace_bytes.restype = C.c_int
@@ -188,6 +191,14 @@ def hetis_attn_decode_ws(shape, q, k_cache, v_cache, block_table, seq_lens, head
                                        _ptr(block_table), _ptr(seq_lens), _ptr(head_ids),
                                        int(n_sel_heads), float(scale), _ptr(out), _ptr(workspace),
                                        int(workspace_bytes), _stream(stream))
+
+
+def hetis_attn_decode_static(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids,
+                             n_sel_heads, scale, out, stream=None) -> int:
+    return load().hetis_attn_decode_static(C.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                           _ptr(block_table), _ptr(seq_lens), _ptr(head_ids),
+                                           int(n_sel_heads), float(scale), _ptr(out),
+                                           _stream(stream))
 
 
 def hetis_attn_decode_workspace_bytes(shape, n_sel_heads):

@@ -323,6 +323,37 @@ static int owned_workspace(size_t need, hipStream_t st, bool may_be_capturing, v
     return HETIS_OK;
 }
 
+// ---- static scratch of hetis_attn_decode_static: a workspace that exists from the moment the
+// code object is loaded, so the entry point never allocates.  Every device the library runs on
+// holds its own copy at its own address; `scratch` itself is only a host-side handle of the
+// symbol and must never be passed to a kernel: host code uses the per-device address that
+// hipGetSymbolAddress returned.
+constexpr size_t kStaticScratchBytes = (size_t)HETIS_ATTN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];      // per device: address of its copy of `scratch`
+
+// Device address of the current device's copy of `scratch` (looked up once per device, with
+// that device current).
+static int static_scratch(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HETIS_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return HETIS_ERR_LAUNCH;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return HETIS_OK;
+}
+
 static AttnParams make_params(const hetis_attn_shape *s, const Checked &c, const void *q,
                               const void *k, const void *v, const int32_t *bt,
                               const int32_t *sl, const int32_t *hid, int32_t n_sel, float scale,
@@ -430,6 +461,32 @@ int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const voi
     if (!workspace) return HETIS_ERR_NULL;
     return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
                          scale, out, workspace, workspace_bytes, false, stream);
+}
+
+int hetis_attn_decode_static(const hetis_attn_shape *shape, const void *q, const void *k_cache,
+                             const void *v_cache, const int32_t *block_table,
+                             const int32_t *seq_lens, const int32_t *head_ids,
+                             int32_t n_sel_heads, float scale, void *out, void *stream)
+{
+    Checked c;
+    if (!shape || !q || !k_cache || !v_cache || !block_table || !seq_lens || !head_ids || !out)
+        return HETIS_ERR_NULL;
+    int rc = check_shape(shape, n_sel_heads, &c);
+    if (rc != HETIS_OK) return rc;
+    const WsLayout lay = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
+                                          decode_max_chunks(shape, c.group));
+    if (lay.total > kStaticScratchBytes) return HETIS_ERR_WORKSPACE;   // before any HIP call
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != HETIS_OK) return rc;
+    // The array keeps what the last call left.  Partial results are always written before they
+    // are read; the control words must start at zero, and although every launch re-arms them,
+    // they are cleared here (with a kernel, so that the call can be captured) to make each
+    // call independent of how an earlier one ended.
+    rc = zero_fill(ws, kControlBytes, (hipStream_t)stream);
+    if (rc != HETIS_OK) return rc;
+    return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
+                         scale, out, ws, kStaticScratchBytes, false, stream);
 }
 
 int hetis_attn_decode_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,

@@ -173,6 +173,19 @@ def test_workspace_sizes(lib):
     assert lib.hetis_attn_decode_workspace_bytes(C.byref(s), 13, None) == binding.HETIS_ERR_NULL
 
 
+def test_static_scratch_entry_point_argument_errors(lib):
+    s = good()
+    call = lambda shape=s, n_sel=4, q=P: H.hetis_attn_decode_static(shape, q, P, P, P, P, P, n_sel,
+                                                                    0.125, P, 0)
+    assert call(q=None) == binding.HETIS_ERR_NULL
+    assert call(n_sel=9) == binding.HETIS_ERR_BAD_HEADS
+    assert call(shape=H.make_shape(4, 8, 8, 96, 16)) == binding.HETIS_ERR_UNSUPPORTED
+    # a shape whose workspace exceeds the static array is refused before any HIP call
+    big = H.make_shape(2048, 40, 40, 128, 256)
+    assert H.hetis_attn_decode_workspace_bytes(big, 40)[1] > binding.HETIS_ATTN_STATIC_SCRATCH_BYTES
+    assert call(shape=big, n_sel=40) == binding.HETIS_ERR_WORKSPACE
+
+
 def test_ws_entry_points_argument_errors(lib):
     s = good()
     rc, need = H.hetis_attn_decode_workspace_bytes(s, 4)
