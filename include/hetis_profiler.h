@@ -35,6 +35,16 @@ extern "C" {
 int hetis_profiler_fit(const double *h, const double *g, const double *tau, int32_t n,
                        double *abc, double *accuracy);
 
+/*
+ * The same fit under a >= 0 and b >= 0.  Eq. (7) uses a and b as the cost of one more head
+ * and one more unit of cache on a device, so a fit whose slope came out slightly negative
+ * (a kernel whose time does not grow with the head count, plus measurement noise) must not
+ * reach the Dispatcher as it is.  When the unconstrained solution already has both slopes
+ * non-negative it is returned unchanged.  Arguments, accuracy and errors as above.
+ */
+int hetis_profiler_fit_nonneg(const double *h, const double *g, const double *tau, int32_t n,
+                              double *abc, double *accuracy);
+
 /* tau_out[i] = a * h[i] + b * g[i] + c for i < n (n >= 0). */
 int hetis_profiler_predict(const double *abc, const double *h, const double *g, int32_t n,
                            double *tau_out);

@@ -264,6 +264,23 @@ def profiler_fit(h, g, tau):
     return abc, acc
 
 
+def profiler_fit_nonneg(h, g, tau):
+    """The same least-squares problem under a >= 0 and b >= 0 (the Dispatcher of Section 5.2
+    uses a and b as costs), handed to scipy's bounded least-squares routine on columns scaled
+    to unit size.  Returns ((a, b, c), accuracy)."""
+    from scipy.optimize import lsq_linear
+    h, g, tau = (np.asarray(x, dtype=np.float64) for x in (h, g, tau))
+    X = np.stack([h, g, np.ones_like(h)], axis=1)
+    scale = np.abs(X).max(axis=0)
+    if not (scale > 0).all():
+        raise ValueError("samples do not determine a, b, c")
+    res = lsq_linear(X / scale, tau, bounds=([0.0, 0.0, -np.inf], [np.inf, np.inf, np.inf]),
+                     method="bvls", tol=1e-14)
+    abc = res.x / scale
+    acc = 1.0 - float(np.mean(np.abs(X @ abc - tau) / tau))
+    return abc, acc
+
+
 # ---------------------------------------------------------------- Dispatcher (Eq. (7))
 
 def dispatch(devices, lengths, n_heads, r):

@@ -16,6 +16,6 @@ from .binding import (  # noqa: F401
     hetis_attn_release_workspace, hetis_attn_shape, hetis_attn_split_num_chunks,
     hetis_attn_split_workspace_bytes, hetis_attn_status_string, hetis_attn_validate,
     hetis_attn_version, hetis_dispatch_device, hetis_dispatch_solve, hetis_kv_append, hetis_kv_append_pairs, hetis_kv_copy_tiles, hetis_kv_fetch, hetis_kv_pool,
-    hetis_kv_profile_events, hetis_kv_store, hetis_profiler_fit, hetis_profiler_predict, make_pool,
+    hetis_kv_profile_events, hetis_kv_store, hetis_profiler_fit, hetis_profiler_fit_nonneg, hetis_profiler_predict, make_pool,
     make_shape,
 )

@@ -125,6 +125,8 @@ def load(build_if_missing: bool = False):
     lib.hetis_dispatch_solve.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.hetis_profiler_fit.restype = C.c_int
     lib.hetis_profiler_fit.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.hetis_profiler_fit_nonneg.restype = C.c_int
+    lib.hetis_profiler_fit_nonneg.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.hetis_profiler_predict.restype = C.c_int
     lib.hetis_profiler_predict.argtypes = [vp, vp, vp, i32, vp]
     pool = C.POINTER(hetis_kv_pool)
@@ -368,6 +370,13 @@ def hetis_profiler_fit(h, g, tau, n, abc, accuracy=None) -> int:
     acc = None if accuracy is None else C.byref(accuracy)
     return load().hetis_profiler_fit(_ptr(h), _ptr(g), _ptr(tau), int(n), _ptr(abc),
                                      C.cast(acc, C.c_void_p) if acc is not None else None)
+
+
+def hetis_profiler_fit_nonneg(h, g, tau, n, abc, accuracy=None) -> int:
+    """As hetis_profiler_fit, under a >= 0 and b >= 0."""
+    acc = None if accuracy is None else C.byref(accuracy)
+    return load().hetis_profiler_fit_nonneg(_ptr(h), _ptr(g), _ptr(tau), int(n), _ptr(abc),
+                                            C.cast(acc, C.c_void_p) if acc is not None else None)
 
 
 def hetis_profiler_predict(abc, h, g, n, tau_out) -> int:

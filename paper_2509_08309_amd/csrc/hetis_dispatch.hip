@@ -147,7 +147,10 @@ extern "C" int hetis_dispatch_solve(const hetis_dispatch_device *devices, int32_
         const double v[8] = {d.a, d.b, d.c, d.gamma, d.beta, d.h, d.g, d.capacity};
         for (double q : v)
             if (!std::isfinite(q)) return HETIS_ERR_BAD_SHAPE;
-        if (d.h < 0 || d.g < 0 || d.capacity < 0) return HETIS_ERR_BAD_SHAPE;
+        // a negative cost per head or per cache unit would make a device look faster the more it
+        // is given: such a model (e.g. a fit dominated by noise) is refused, not optimised
+        for (double q : v)
+            if (q < 0) return HETIS_ERR_BAD_SHAPE;
     }
     for (int j = 0; j < J; ++j)
         if (!std::isfinite(lengths[j]) || !(lengths[j] > 0)) return HETIS_ERR_BAD_SHAPE;

@@ -87,6 +87,75 @@ int hetis_profiler_fit(const double *h, const double *g, const double *tau, int3
     return HETIS_OK;
 }
 
+// Least squares with (a, b) held at zero where `free_a` / `free_b` is false.  Returns the sum of
+// squared residuals, or a negative value when the free parameters are not determined.
+static double fit_subset(const double *h, const double *g, const double *tau, int n, bool free_a,
+                         bool free_b, double *abc)
+{
+    if (free_a && free_b) {
+        if (hetis_profiler_fit(h, g, tau, n, abc, nullptr) != HETIS_OK) return -1.0;
+    } else {
+        abc[0] = abc[1] = 0.0;
+        double mt = 0.0;
+        for (int i = 0; i < n; ++i) mt += tau[i];
+        mt /= n;
+        abc[2] = mt;
+        if (free_a || free_b) {                      // one slope: simple regression
+            const double *x = free_a ? h : g;
+            double mx = 0.0;
+            for (int i = 0; i < n; ++i) mx += x[i];
+            mx /= n;
+            double sxx = 0.0, sxy = 0.0;
+            for (int i = 0; i < n; ++i) {
+                sxx += (x[i] - mx) * (x[i] - mx);
+                sxy += (x[i] - mx) * (tau[i] - mt);
+            }
+            if (!(sxx > 0.0)) return -1.0;
+            const double slope = sxy / sxx;
+            abc[free_a ? 0 : 1] = slope;
+            abc[2] = mt - slope * mx;
+        }
+    }
+    double ss = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const double e = abc[0] * h[i] + abc[1] * g[i] + abc[2] - tau[i];
+        ss += e * e;
+    }
+    return ss;
+}
+
+int hetis_profiler_fit_nonneg(const double *h, const double *g, const double *tau, int32_t n,
+                              double *abc, double *accuracy)
+{
+    double best[3];
+    int rc = hetis_profiler_fit(h, g, tau, n, best, nullptr);     // also validates the samples
+    if (rc != HETIS_OK) return rc;
+    if (best[0] < 0.0 || best[1] < 0.0) {
+        // two sign constraints: the constrained optimum is the best feasible one among the
+        // least-squares solutions with some of the constrained parameters held at zero
+        double best_ss = -1.0;
+        const bool sets[3][2] = {{false, true}, {true, false}, {false, false}};
+        for (const auto &set : sets) {
+            double cand[3];
+            const double ss = fit_subset(h, g, tau, n, set[0], set[1], cand);
+            if (ss < 0.0 || cand[0] < 0.0 || cand[1] < 0.0) continue;
+            if (best_ss < 0.0 || ss < best_ss) {
+                best_ss = ss;
+                for (int k = 0; k < 3; ++k) best[k] = cand[k];
+            }
+        }
+        if (best_ss < 0.0) return HETIS_ERR_BAD_SHAPE;
+    }
+    for (int k = 0; k < 3; ++k) abc[k] = best[k];
+    if (accuracy) {
+        double err = 0.0;
+        for (int i = 0; i < n; ++i)
+            err += std::fabs(abc[0] * h[i] + abc[1] * g[i] + abc[2] - tau[i]) / tau[i];
+        *accuracy = 1.0 - err / n;
+    }
+    return HETIS_OK;
+}
+
 int hetis_profiler_predict(const double *abc, const double *h, const double *g, int32_t n,
                            double *tau_out)
 {

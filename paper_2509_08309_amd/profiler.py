@@ -128,6 +128,16 @@ def fit(h, g, tau):
     return abc, acc.value
 
 
+def fit_nonneg(h, g, tau):
+    """The fit under a >= 0, b >= 0: the coefficients in the form the Dispatcher accepts."""
+    import paper_2509_08309_amd as H
+    arr = lambda x: np.ascontiguousarray(x, dtype=np.float64)
+    h, g, tau = arr(h), arr(g), arr(tau)
+    abc, acc = np.zeros(3), C.c_double(0)
+    H.check(H.hetis_profiler_fit_nonneg(h, g, tau, len(h), abc, acc), "hetis_profiler_fit_nonneg")
+    return abc, acc.value
+
+
 def predict(abc, h, g):
     import paper_2509_08309_amd as H
     arr = lambda x: np.ascontiguousarray(x, dtype=np.float64)
@@ -159,12 +169,14 @@ def run(model: str = "13b", reps: int = 7, h_values=None, g_values=G_VALUES) -> 
             hs.append(h)
             gs.append((g // (h // r)) * (h // r))           # what was actually cached
     abc, acc = fit(hs, gs, taus)
+    abc_nn, acc_nn = fit_nonneg(hs, gs, taus)
     pred = predict(abc, hs, gs)
     rel = np.abs(pred - np.asarray(taus)) / np.asarray(taus)
     rec = {"model": model, "n_points": len(taus), "a_us_per_query_head": abc[0],
            "b_us_per_token_head": abc[1], "c_us": abc[2], "accuracy": acc,
            "worst_point_accuracy": 1.0 - float(rel.max()),
            "b_as_GBps": 2 * bench.D * 2 / abc[1] / 1e3 if abc[1] > 0 else None,
+           "dispatcher_abc": [float(v) for v in abc_nn], "dispatcher_abc_accuracy": acc_nn,
            "points": [{"h": int(a), "g": int(b), "tau_us": round(c, 2), "pred_us": round(float(d), 2)}
                       for a, b, c, d in zip(hs, gs, taus, pred)]}
     # Fig. 7 (a): the number of requests does not matter at fixed (h, g)

@@ -225,3 +225,20 @@ def test_library_argument_errors():
     assert lib_dispatch([dev(capacity=-1.0)], [100.0], 8, 1)[0] == binding.HETIS_ERR_BAD_SHAPE
     assert lib_dispatch([dev(g=50.0, capacity=10.0)], [100.0], 8, 1)[0] == binding.HETIS_ERR_INFEASIBLE
     assert lib.hetis_dispatch_solve(None, 1, None, 1, 8, 1, None, None, None, None) == binding.HETIS_ERR_NULL
+
+
+def test_library_refuses_negative_model_parameters():
+    """A cost per head or per cache unit below zero (a fit dominated by noise) would make a
+    device look faster the more it is given; the solver refuses it."""
+    import ctypes as C
+    import paper_2509_08309_amd as H
+    from paper_2509_08309_amd import binding
+    binding.load(build_if_missing=True)
+    for field in ("a", "b", "c", "gamma", "beta"):
+        devs = (H.hetis_dispatch_device * 2)()
+        for i in range(2):
+            devs[i] = H.hetis_dispatch_device(0.001, 1e-4, 10.0, 0.0, 0.0, 0.0, 0.0, 1e9, 1, 0)
+        setattr(devs[1], field, -1e-6)
+        l = np.array([500.0])
+        xh = np.zeros((1, 2), dtype=np.int32)
+        assert H.hetis_dispatch_solve(devs, 2, l, 1, 8, 1, None, xh) == binding.HETIS_ERR_BAD_SHAPE

@@ -127,3 +127,64 @@ def test_library_fit_errors():
     assert lib.hetis_profiler_fit(None, None, None, 9, None, None) == binding.HETIS_ERR_NULL
     assert H.hetis_profiler_predict(np.zeros(3), None, None, 0, None) == 0
     assert H.hetis_profiler_predict(np.zeros(3), None, None, 4, None) == binding.HETIS_ERR_NULL
+
+
+# ---------------------------------------------------------------- fit under a >= 0, b >= 0
+
+def lib_fit_nonneg(h, g, tau):
+    binding.load(build_if_missing=True)
+    arr = lambda x: np.ascontiguousarray(x, dtype=np.float64)
+    h, g, tau = arr(h), arr(g), arr(tau)
+    abc, acc = np.zeros(3), C.c_double(0)
+    rc = H.hetis_profiler_fit_nonneg(h, g, tau, len(h), abc, acc)
+    return rc, abc, acc.value
+
+
+def test_checker_nonneg_equals_plain_fit_when_both_slopes_are_positive():
+    rng = np.random.default_rng(74)
+    h, g = grid()
+    tau = 0.004 * h + 1e-4 * g + 9 + rng.normal(0, 1, size=h.shape)
+    plain, acc = oracle.profiler_fit(h, g, tau)
+    con, acc2 = oracle.profiler_fit_nonneg(h, g, tau)
+    assert plain[0] > 0 and plain[1] > 0
+    assert np.allclose(con, plain, rtol=1e-7, atol=1e-10) and abs(acc - acc2) < 1e-9
+
+
+def test_checker_nonneg_by_hand_on_a_balanced_design():
+    # tau = -h + 2 g + 5 on the 2 x 2 design: with a held at 0 the regressors stay orthogonal,
+    # so b keeps its value and c absorbs the mean of -h: (0, 2, 4.5)
+    h = np.array([0.0, 1.0, 0.0, 1.0])
+    g = np.array([0.0, 0.0, 1.0, 1.0])
+    abc, _ = oracle.profiler_fit_nonneg(h, g, -h + 2 * g + 5)
+    assert np.allclose(abc, [0.0, 2.0, 4.5], atol=1e-9)
+    # both slopes negative: the mean
+    abc, _ = oracle.profiler_fit_nonneg(h, g, -h - 3 * g + 9)
+    assert np.allclose(abc, [0.0, 0.0, 7.0], atol=1e-9)
+
+
+def test_checker_nonneg_satisfies_the_optimality_conditions():
+    """At the constrained optimum the gradient of the squared error is zero in every free
+    direction and points into the feasible side for a parameter held at its bound."""
+    rng = np.random.default_rng(75)
+    h, g = grid()
+    tau = -6e-4 * h + 8.8e-5 * g + 27 + rng.normal(0, 2, size=h.shape)
+    assert oracle.profiler_fit(h, g, tau)[0][0] < 0
+    abc, _ = oracle.profiler_fit_nonneg(h, g, tau)
+    assert abc[0] == 0.0 and abc[1] > 0
+    res = abc[0] * h + abc[1] * g + abc[2] - tau
+    scale = np.linalg.norm(res)
+    assert abs(res @ g) <= 1e-8 * np.linalg.norm(g) * scale and abs(res.sum()) <= 1e-8 * 8 * scale
+    assert res @ h >= 0          # raising a from 0 would raise the error
+
+
+@pytest.mark.parametrize("a_true,b_true", [(3e-3, 9e-5), (-6e-4, 8.8e-5), (2e-3, -1e-6), (-1e-3, -1e-6)])
+def test_library_nonneg_fit_matches_checker(a_true, b_true):
+    rng = np.random.default_rng(76)
+    h, g = grid()
+    tau = a_true * h + b_true * g + 30 + rng.normal(0, 0.5, size=h.shape)
+    rc, abc, acc = lib_fit_nonneg(h, g, tau)
+    ref, ref_acc = oracle.profiler_fit_nonneg(h, g, tau)
+    assert rc == 0 and abc[0] >= 0 and abc[1] >= 0
+    assert np.allclose(abc, ref, rtol=1e-6, atol=1e-9)
+    assert abs(acc - ref_acc) < 1e-8
+    assert (abc[0] == 0) == (a_true < 0) and (abc[1] == 0) == (b_true < 0)
