@@ -25,17 +25,22 @@ struct AttnParams {
     const int32_t *pair_seq;    // [batch] or nullptr
     const int32_t *pair_head;   // [batch] or nullptr
     __half *out;                // [B, Hq, D]
-    float *o_partial;           // [B, n_sel, max_chunks, r, D]
-    float *lse_partial;         // [B, n_sel, max_chunks, r]
+    float *o_partial;           // [rows, n_sel, max_segs, r, D]
+    float *lse_partial;         // [rows, n_sel, max_segs, r]
     int64_t stride_block;       // elements
     int64_t stride_head;        // elements
     int32_t n_q_heads;
     int32_t n_sel;
     int32_t max_blocks_per_seq;
-    int32_t chunk_tokens;       // multiple of 16
-    int32_t max_chunks;
-    int32_t direct_single;      // 1: a sequence of <= 1 chunk is written to `out` by the partial pass
+    int32_t chunk_tokens;       // tokens one wave processes at a time: multiple of 16, <= 1024
+    int32_t seg_tokens;         // tokens whose result leaves a workgroup as one (partial) result:
+                                // a multiple of chunk_tokens, at most 32 chunks
+    int32_t max_segs;           // segments of the longest row the buffers provide for
+    int32_t direct_single;      // 1: a row of <= 1 segment is written to `out` by the chunk kernel
     unsigned int *control;      // device words of the call's workspace (see kCtl* below)
+    unsigned int *arrivals;     // [rows * n_sel] segments of a row whose partial results are stored,
+                                // zero between launches; nullptr: partial results are left for a
+                                // separate merge (the split-KV entry points)
     float scale_log2;           // scale * log2(e): scores are kept in the base-2 domain
 };
 
@@ -103,6 +108,18 @@ __device__ __forceinline__ uint4 buffer_load_u4(__amdgpu_buffer_rsrc_t r, int by
 {
     const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, kStreamingLoad);
     return make_uint4(x.x, x.y, x.z, x.w);
+}
+
+// One word to / from device memory, coherent across the whole device (all XCDs): these
+// accesses go past the per-XCD L2, so a word stored by one wave can be read by any other wave
+// once the store has completed, without invalidating or writing back whole caches.
+__device__ __forceinline__ void coherent_store(float *ptr, float v)
+{
+    __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float *ptr)
+{
+    return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 union Pack16 {

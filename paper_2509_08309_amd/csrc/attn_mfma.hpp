@@ -192,7 +192,7 @@ struct MfmaPolicy {
             st.acc[mb] = __builtin_amdgcn_mfma_f32_16x16x16f16(vt[mb].h, pb, st.acc[mb], 0, 0, 0);
     }
 
-    // normalised rows and their log-sum-exp -> LDS (the wave's mailbox)
+    // normalised rows and their base-2 log-sum-exp -> LDS (the wave's mailbox)
     __device__ static __forceinline__ void finish(State &st, float (&o)[R][D], float (&lse)[R],
                                                   int lane)
     {
@@ -208,7 +208,7 @@ struct MfmaPolicy {
                                              st.acc[mb][2] * inv, st.acc[mb][3] * inv);
                 *reinterpret_cast<float4 *>(&o[j][mb * 16 + grp * 4]) = v;
             }
-            if (grp == 0) lse[j] = (st.m + fast_log2(l)) * kLn2;
+            if (grp == 0) lse[j] = st.m + fast_log2(l);
         }
     }
 };

@@ -1,107 +1,163 @@
-// Persistent chunk kernel: work enumeration, tile streaming and chunk results for Eq. (2b),
-// independent of how a tile is turned into scores and sums (that is the Policy: vector ALU
-// arithmetic for small query groups, MFMA for grouped-query attention).
+// Persistent kernel of head-subset decode Attention: work enumeration, tile streaming and
+// the combination of chunk results for Eq. (2b), independent of how a tile is turned into
+// scores and sums (that is the Policy: vector ALU arithmetic for small query groups, MFMA
+// for grouped-query attention).
 //
-// Work enumeration: every workgroup loads the sequence lengths and scans them into tables of
-// running counts (LDS): whole chunks per sequence, and ragged last chunks per sequence in four
-// classes by size.  A flat item number then decodes into (sequence, chunk, selected head) by binary
-// search, whole chunks first, then the ragged ones from the longest class to the shortest,
-// without launching a workgroup per possible chunk; the items handed out last are the
-// shortest, which keeps the tail of the launch short.  An item is one chunk of one
-// (sequence, selected head) and is processed by ONE wave.
-// Work distribution: the first two items of a streaming wave are fixed by its number; the
-// rest come from a global ticket counter, so that waves which drew short chunks simply take
-// more of them.  Tickets are drawn by the workgroup's writer wave, eight per device atomic
-// while plenty of work is left and fewer towards the end, decoded there (one ticket per
-// lane), and put into a small LDS pool from which the streaming waves take them, ready to
-// use, with an LDS atomic shortly before they finish an item.  Which wave computes an item has no
-// influence on the item's arithmetic.  The ticket counter and a counter of finished
-// workgroups are control words of the call's workspace (AttnParams::control); the workgroup
-// that finishes last sets both back to zero for the next launch.
+// Units of work.  A ROW is one (enumeration row, selected KV head): a sequence (or, in pairs
+// mode, a (sequence, head) pair) and one of the heads computed for it.  The tokens of a row
+// are cut into SEGMENTS of seg_tokens tokens from token 0; a segment is cut into CHUNKS of
+// chunk_tokens tokens.  A chunk is processed by ONE wave; a segment is processed by ONE
+// workgroup, whose waves take its chunks and whose writer wave folds the chunk results
+// together in LDS, in ascending chunk order, so a segment leaves the workgroup as a single
+// result: the finished fp16 row when the segment is the whole row, an fp32 partial result
+// (normalised sum and log-sum-exp) otherwise.  With seg_tokens = chunk_tokens every chunk is
+// its own segment (the split-KV entry points); with seg_tokens = 4096 a row of up to 4096
+// tokens never touches global memory between its first tile and its output row.
+//
+// Work enumeration: every workgroup loads the row lengths and builds two tables in LDS: the
+// running count of whole segments per row, and the list of the rows that end in a shorter
+// segment, sorted by the size class of that segment (kClasses classes, a counting sort inside
+// one wave).  A flat segment number then decodes into (row, segment, head): whole segments
+// first (binary search in the running counts), then the shorter ones from the largest class
+// to the smallest (a look-up in the sorted list), so the segments handed out last are the
+// short ones, which keeps the end of the launch short.
+// Work distribution: segment number blockIdx.x belongs to the workgroup without asking (when
+// every segment is a single chunk: one such segment per streaming wave); the rest are tickets from a device counter, drawn by the workgroup's writer wave, which decodes
+// a segment, reserves a fold slot for it and puts its chunks, ready to use, into an LDS pool;
+// the streaming waves take chunks from the pool with an LDS atomic shortly before they finish
+// the chunk at hand.  Which wave or workgroup computes a chunk has no influence on the
+// arithmetic: a row's result is a function of its length and the compile-time constants alone.
+// The ticket counter and a counter of finished workgroups are control words of the call's
+// workspace (AttnParams::control); the workgroup that finishes last sets both back to zero
+// for the next launch.
 //
 // A workgroup is NW streaming waves plus one writer wave; after the prologue they never
 // meet at a barrier.
-//   - Streaming waves stream the tiles of their item through a register ring of
+//   - Streaming waves stream the tiles of their chunk through a register ring of
 //     Policy::kRing slots; a slot is refilled right after it has been consumed, so up to
-//     kRing tile pairs (8 KB each) per wave are in flight, and the ring runs on into the
-//     first tiles of the next item before the current item is finished off.  Every global load is issued
+//     kRing tile pairs per wave are in flight, and the ring runs on into the first tiles of
+//     the next chunk before the current one is finished off.  Every global load is issued
 //     unconditionally (indices clamped, tiles that do not exist turned into zero-length
 //     buffer descriptors), so the in-order load counter is known exactly at every wait.
 //     These waves never store to global memory: on gfx9-class hardware loads and stores
 //     share one counter that is in order only among loads, so a single pending store would
-//     force every later wait to drain all loads.  A finished item (normalised rows and
-//     their log-sum-exp) is handed over through one of the wave's two LDS mailboxes.
-//   - The writer wave polls the mailboxes and copies full ones to global memory (fp16 row,
-//     fp32 partial, or zeros for an empty sequence), and keeps the ticket pool filled.
+//     force every later wait to drain all loads.  A finished chunk (normalised rows and
+//     their base-2 log-sum-exp) is handed over through one of the wave's two LDS mailboxes.
+//   - The writer wave polls the mailboxes.  A chunk that is a whole segment goes straight to
+//     global memory (fp16 row, fp32 partial, or zeros for an empty sequence).  A chunk of a
+//     longer segment is folded into the segment's slot: running maximum M, weight sum W and
+//     weighted sum A with  M' = max(M, lse_c), A' = A 2^(M-M') + o_c 2^(lse_c-M'), W likewise;
+//     chunk c is folded only after chunks 0..c-1 (a mailbox whose turn has not come stays
+//     full), so the order of the floating-point operations is fixed.  After the last chunk
+//     A / W leaves as the segment's result.
 // Mailbox protocol (flag is a workgroup-scope atomic in LDS): EMPTY -> the producer fills
-// data and header -> FULL -> the writer copies it out -> EMPTY.  A producer that has no more
-// items marks its next mailbox DONE; the writer leaves when all NW are DONE.  All waits are
-// polling loops with an iteration bound, so every wave reaches its end whatever happens; a
-// wait that runs into its bound sets a flag in the workspace's error word, which the host
-// reads with hetis_attn_workspace_status (the launch may then have lost a result).
-// Dynamic LDS: int lens[batch], int firstF[batch + 1], int firstT[4][batch + 1], int
-// hids[n_sel] (pairs mode: hids[batch], pseq[batch]); NW x 2 mailboxes; NW per-wave staging
-// areas of Policy::kWaveLdsBytes.
+// data and header -> FULL -> the writer consumes it -> EMPTY.  A producer that has no more
+// chunks marks its next mailbox DONE; the writer leaves when all NW are DONE.
+// No wait can last for ever: chunks enter the pool in order, a wave's two mailboxes hold
+// only chunks it took earlier, so the earliest chunk not yet folded can always be deposited
+// and is always next in its segment.  All the same every wait is a polling loop with an
+// iteration bound, so that every wave reaches its end whatever happens; a wait that runs
+// into its bound sets a flag in the workspace's error word, which the host reads with
+// hetis_attn_workspace_status (the launch may then have lost a result).
+// Dynamic LDS: int lens[rows], int firstF[rows + 1], uint16 order[rows], uint8 cls[rows], int
+// hids[n_sel] (pairs mode: hids[rows], pseq[rows]); NW x 2 mailboxes; fold slots; NW per-wave
+// staging areas of Policy::kWaveLdsBytes.
 // Pairs mode (per-request head subsets, Section 4.2 / 5.2.1): the rows of the enumeration are
 // (sequence, KV head) pairs instead of sequences, each with its own block-table row over a
-// pool of single-head tiles; everything else, the arithmetic of an item included, is shared.
-// Nothing depends on how many heads were selected or on the grid size: the result for one
-// (sequence, head) is a function of that sequence's length alone.
+// pool of single-head tiles; everything else, the arithmetic included, is shared.
 #pragma once
 #include "attn_common.hpp"
 
 namespace hetis {
 
 enum : int { kMailEmpty = 0, kMailFull = 1, kMailDone = 2 };
-enum : int { kKindOut = 0, kKindPartial = 1, kKindZero = 2 };
+enum : int { kKindOut = 0, kKindPartial = 1, kKindZero = 2, kKindFold = 3 };
 constexpr int kSpinLimit = 1 << 22;     // polls before a wait gives up (far beyond any real wait)
-constexpr int kPoolSize = 32;           // item numbers the LDS ticket pool can hold
-constexpr int kTicketBatch = 8;         // tickets per device atomic
+// Size classes of a row's last, shorter segment, largest first: fifteen of one sixteenth of a
+// whole segment each, then the last sixteenth split at 1/32, 1/64 and 1/128 of a segment.
+constexpr int kLinClasses = 15;
+constexpr int kClasses = kLinClasses + 4;
+constexpr int kMaxSegChunks = 32;       // chunks of a segment, at most (one writer lane each)
+constexpr int kPoolSize = 2 * kMaxSegChunks;   // chunk descriptors the LDS pool can hold
+constexpr int kTicketBatch = 8;         // tickets per device atomic while segments are single chunks
+// Segments of at most 1/HETIS_FINE_CHUNK_BELOW of a whole one are cut into chunks of half the
+// size, those of at most a quarter of that into chunks of a quarter of the size.
+#ifndef HETIS_FINE_CHUNK_BELOW
+#define HETIS_FINE_CHUNK_BELOW 4
+#endif
+// Chunks of multi-chunk segments a workgroup keeps waiting in its pool before it draws the
+// next segment.
+#ifndef HETIS_POOL_AHEAD
+#define HETIS_POOL_AHEAD 4
+#endif
+enum : int { kItemExists = 1 };
 
-// An item, decoded: what a streaming wave needs to start on it.
-struct ItemDesc {
-    int b, c, si, g;    // enumeration row (sequence, or pair), chunk, position in head_ids, KV head
-    int seq;            // sequence whose query rows and output rows the item uses
+// A chunk, decoded: what a streaming wave needs to start on it and to label its result.
+struct ChunkDesc {
+    int b, g, seq;      // enumeration row (sequence, or pair), KV head, sequence of q / out rows
+    int t0;             // first token of the chunk in its sequence
     int n_tok;          // tokens of the chunk
-    int flags;          // kItemExists | kItemToOut | kItemZero
+    int flags;          // kItemExists, or 0: no work is left, the wave may finish
+    int kind;           // kKindOut / kKindPartial / kKindZero (whole segment) or kKindFold
+    int dest;           // Out / Zero: first of the R rows in `out`; Partial: slot in the partial
+                        // buffers; Fold: the segment's fold slot
+    int cs;             // Fold: index of the chunk in its segment
+    int nseg;           // segments of the chunk's row
+    int out_row;        // first of the R rows of the chunk's (sequence, head) in `out`
     int pad;
 };
-enum : int { kItemExists = 1, kItemToOut = 2, kItemZero = 4 };
 
-// Items waiting to be taken by the streaming waves of one workgroup, already decoded by the
-// writer wave.
-struct TicketPool {
+// Chunks waiting to be taken by the streaming waves of one workgroup, in order.
+struct ChunkPool {
     int next;                   // entries taken so far  (LDS atomic, streaming waves)
     int end;                    // entries published so far (written by the writer wave)
-    ItemDesc desc[kPoolSize];   // ring: entry i lives in desc[i % kPoolSize]
+    ChunkDesc desc[kPoolSize];  // ring: entry i lives in desc[i % kPoolSize]
 };
 
-// One finished item on its way to global memory.
+// One finished chunk on its way to the writer wave.
 template <int D, int R>
-struct Mailbox {
+struct alignas(16) Mailbox {
     float o[R][D];      // normalised output rows
-    float lse[R];       // natural-log log-sum-exp of each row (partial results only)
-    int out_row;        // first of the item's R rows in `out`: sequence * n_q_heads + KV head * R
-    int item;           // index of the item's slot in the partial buffers
-    int kind;           // kKindOut / kKindPartial / kKindZero
+    float lse[R];       // base-2 log-sum-exp of each row: m + log2(sum_t 2^(s_t - m))
+    int kind, dest, cs; // as in the chunk's descriptor
+    int nseg, out_row;
     int flag;           // kMailEmpty / kMailFull / kMailDone
 };
 
-// Mailbox -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
+// Running combination of the chunks of one segment (writer wave only).
 template <int D, int R>
-__device__ __forceinline__ void flush_mailbox(const Mailbox<D, R> &mb, const AttnParams &p, int lane)
+struct alignas(16) FoldSlot {
+    float acc[R][D];    // sum over folded chunks of o_c 2^(lse_c - M)
+    float M[R];         // running maximum of lse_c (base 2); at the end M + log2 W
+    float W[R];         // sum over folded chunks of 2^(lse_c - M)
+    int next;           // chunk to fold next
+    int ns;             // chunks of the segment
+    int kind, dest;     // where the finished segment goes: kKindOut / kKindPartial
+    int nseg, out_row;  // of the segment's row
+};
+
+template <int R>
+__host__ __device__ constexpr int fold_slots() { return R >= 4 ? 5 : 8; }
+
+// Result rows in LDS -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a
+// lane.  `lse2`: base-2 log-sum-exp per row; `w`: when not null, row r is divided by w[r] on
+// the way out (the weight sum of a fold slot).
+template <int D, int R>
+__device__ __forceinline__ void store_result(const float (&o)[R][D], const float *lse2,
+                                             const float *w, int kind, int64_t dest,
+                                             const AttnParams &p, int lane)
 {
-    const int64_t out_row = __builtin_amdgcn_readfirstlane(mb.out_row);
-    const int kind = __builtin_amdgcn_readfirstlane(mb.kind);
-    // the r rows of one (sequence, head, chunk) are contiguous in the partial buffers, so an
-    // item leaves as one run of r*D floats plus one run of r floats
-    const int64_t item = __builtin_amdgcn_readfirstlane(mb.item);
 #pragma unroll
     for (int idx = lane * 4; idx < R * D; idx += 256) {
         const int r = idx / D, d = idx % D;
-        float4 v = *reinterpret_cast<const float4 *>(&mb.o[r][d]);
+        float4 v = *reinterpret_cast<const float4 *>(&o[r][d]);
+        if (w) {
+            const float s = __builtin_amdgcn_rcpf(w[r]);
+            v = make_float4(v.x * s, v.y * s, v.z * s, v.w * s);
+        }
         if (kind == kKindPartial) {
-            *reinterpret_cast<float4 *>(p.o_partial + item * (R * D) + idx) = v;
+            // the r rows of one (row, head, segment) are contiguous in the partial buffers
+            *reinterpret_cast<float4 *>(p.o_partial + dest * (R * D) + idx) = v;
         } else {
             if (kind == kKindZero) v = make_float4(0.f, 0.f, 0.f, 0.f);
             union {
@@ -110,36 +166,126 @@ __device__ __forceinline__ void flush_mailbox(const Mailbox<D, R> &mb, const Att
             } pk;
             pk.h[0] = __floats2half2_rn(v.x, v.y);
             pk.h[1] = __floats2half2_rn(v.z, v.w);
-            *reinterpret_cast<uint2 *>(p.out + (out_row + r) * D + d) = pk.u;
+            *reinterpret_cast<uint2 *>(p.out + (dest + r) * D + d) = pk.u;
         }
     }
-    if (kind == kKindPartial && lane < R) p.lse_partial[item * R + lane] = mb.lse[lane];
+    // partial results carry the natural-log log-sum-exp
+    if (kind == kKindPartial && lane < R) p.lse_partial[dest * R + lane] = lse2[lane] * kLn2;
+}
+
+// Partial result of a segment that is merged inside this launch (AttnParams::arrivals): by
+// whichever wave stores the row's last segment, possibly on another XCD, so the words are
+// stored device-coherently, one per lane and step.
+template <int D, int R>
+__device__ __forceinline__ void store_partial_coherent(const float (&o)[R][D], const float *lse2,
+                                                       const float *w, int64_t dest,
+                                                       const AttnParams &p, int lane)
+{
+#pragma unroll
+    for (int idx = lane; idx < R * D; idx += 64) {
+        float v = (&o[0][0])[idx];
+        if (w) v *= __builtin_amdgcn_rcpf(w[idx / D]);
+        coherent_store(p.o_partial + dest * (R * D) + idx, v);
+    }
+    if (lane < R) coherent_store(p.lse_partial + dest * R + lane, lse2[lane] * kLn2);
+}
+
+// Log-sum-exp merge of the n_segs partial results of one row, ascending segment order, by one
+// wave: M = max_c lse_c, w_c = exp(lse_c - M), out = fp16(sum_c w_c o_c / sum_c w_c).  Lane l
+// owns dims l and l + 64 (D = 128) of each of the R query rows.  `first` is the index of
+// segment 0 of the row in the partial buffers.  The partial results may come from other
+// XCDs: they are read with device-coherent loads.
+template <int D, int R>
+__device__ __forceinline__ void merge_partials(const AttnParams &p, int64_t first, int n_segs,
+                                               int64_t out_row, int lane)
+{
+    constexpr int V = D / 64;                        // words per lane and row: 1 or 2
+    const float *lse = p.lse_partial + first * R;    // [segment][r]
+    const float *op = p.o_partial + first * (R * D) + lane;
+    float M[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) M[r] = coherent_load(lse + r);
+    for (int c = 1; c < n_segs; ++c) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) M[r] = fmaxf(M[r], coherent_load(lse + c * R + r));
+    }
+    float W[R], acc[R][V];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        W[r] = 0.f;
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[r][v] = 0.f;
+    }
+    for (int c = 0; c < n_segs; ++c) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float w = fast_exp2((coherent_load(lse + c * R + r) - M[r]) * kLog2e);
+            W[r] += w;
+            const float *src = op + ((int64_t)c * R + r) * D;
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[r][v] = fmaf(w, coherent_load(src + v * 64), acc[r][v]);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        __half *dst = p.out + (out_row + r) * D + lane;
+#pragma unroll
+        for (int v = 0; v < V; ++v) dst[v * 64] = __float2half_rn(acc[r][v] / W[r]);
+    }
+}
+
+// After the partial result of a segment has been stored: count it in; the wave that stores
+// the last segment of a row merges all of them into `out` and rearms the counter.
+// Ordering across waves and XCDs without cache-wide write-backs or invalidations (which were
+// measured to cost several times the merge launch they replace): the partial results are
+// written with device-coherent stores, this wave waits until its stores have completed, then
+// bumps the counter with a device-scope atomic; the merging wave reads the partial results
+// with device-coherent loads issued after its own atomic has returned.
+template <int D, int R>
+__device__ __forceinline__ void arrive_and_merge(const AttnParams &p, int64_t dest, int n_segs,
+                                                 int64_t out_row, int lane)
+{
+    const int64_t row = dest / p.max_segs;           // (enumeration row, head) of the segment
+    unsigned old = 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);                   // every store of this wave has completed
+    if (lane == 0)
+        old = __hip_atomic_fetch_add(p.arrivals + row, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if ((int)old + 1 != n_segs) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    merge_partials<D, R>(p, row * p.max_segs, n_segs, out_row, lane);
+    if (lane == 0)
+        __hip_atomic_store(p.arrivals + row, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 struct ItemHdr {
-    int b, si, c, g;    // enumeration row (sequence, or pair), position in head_ids, chunk, KV head
-    int seq;            // sequence whose query rows and output rows the item uses
+    int b, g, seq;  // enumeration row (sequence, or pair), KV head, sequence of q / out rows
     int nblk;       // blocks of this chunk
     int rem;        // tokens in the ragged last block (0: none)
     int t0;         // first token of the chunk
-    bool to_out;    // result goes to `out` (fp16), not to the partial buffers
-    bool zero;      // length-0 sequence whose zeros this pass writes
+    int kind, dest, cs;
+    int nseg, out_row;
 };
 
 __host__ __device__ constexpr size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
-// Table words after the six per-row tables: the selected heads, or in pairs mode the head and
-// the sequence of every pair.
-__host__ __device__ constexpr int persist_id_words(int batch, int n_sel, bool pairs)
+// Table bytes: lens, firstF (int), order (uint16), cls (uint8), then the selected heads, or in
+// pairs mode the head and the sequence of every pair.
+__host__ __device__ constexpr size_t persist_table_bytes(int rows, int n_sel, bool pairs)
 {
-    return pairs ? 2 * batch : n_sel;
+    return align16((size_t)(2 * rows + 2) * sizeof(int)) +
+           align16((size_t)rows * sizeof(unsigned short)) + align16((size_t)rows) +
+           align16((size_t)(pairs ? 2 * rows : n_sel) * sizeof(int));
 }
 
 template <class Policy, int NW>
-__host__ __device__ constexpr size_t persist_lds_bytes(int batch, int n_sel, bool pairs)
+__host__ __device__ constexpr size_t persist_lds_bytes(int rows, int n_sel, bool pairs)
 {
-    return align16((size_t)(6 * batch + 5 + persist_id_words(batch, n_sel, pairs)) * sizeof(int)) +
-           2 * NW * sizeof(Mailbox<Policy::D, Policy::R>) + (size_t)NW * Policy::kWaveLdsBytes;
+    return persist_table_bytes(rows, n_sel, pairs) +
+           2 * NW * sizeof(Mailbox<Policy::D, Policy::R>) +
+           fold_slots<Policy::R>() * sizeof(FoldSlot<Policy::D, Policy::R>) +
+           (size_t)NW * Policy::kWaveLdsBytes;
 }
 
 __device__ __forceinline__ int mail_load(const int *flag)
@@ -149,6 +295,14 @@ __device__ __forceinline__ int mail_load(const int *flag)
 __device__ __forceinline__ void mail_store(int *flag, int v)
 {
     __hip_atomic_store(flag, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+// Orders the LDS accesses of one wave around a point where lanes read what other lanes of
+// the same wave wrote (the hardware keeps a wave's LDS operations in order; this keeps the
+// compiler from moving them).
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 template <class Policy, int NW, bool PAIRS>
@@ -160,41 +314,54 @@ __global__ __launch_bounds__((NW + 1) * 64)
     constexpr int R = Policy::R;
     constexpr int NT = (NW + 1) * 64;
     constexpr int kTileBytes = kBlockTokens * D * 2;
+    constexpr int NS = fold_slots<R>();
     using Mail = Mailbox<D, R>;
+    using Fold = FoldSlot<D, R>;
     using Tile = typename Policy::Tile;
     extern __shared__ __align__(16) unsigned char smem[];
     int *lens = reinterpret_cast<int *>(smem);
-    int *firstF = lens + batch;               // whole chunks before sequence b
-    int *firstT = firstF + batch + 1;         // [4][batch + 1]: ragged last chunks of size class
-                                              // k before sequence b (class 3 also holds the
-                                              // items that write zeros)
-    int *hids = firstT + 4 * (batch + 1);     // KV head of position si in head_ids / of pair b
-    int *pseq = hids + batch;                 // pairs mode: sequence of pair b
-    const int n_sel = PAIRS ? 1 : p.n_sel;    // items per (row, chunk)
+    int *firstF = lens + batch;               // whole segments before row b; one spare word after
+    // rows that end in a shorter segment (or, empty, in the segment that writes zeros), sorted
+    // by the size class of that segment, largest first
+    unsigned short *order =
+        reinterpret_cast<unsigned short *>(smem + align16((size_t)(2 * batch + 2) * sizeof(int)));
+    unsigned char *cls_of = reinterpret_cast<unsigned char *>(order) +
+                            align16((size_t)batch * sizeof(unsigned short));   // class + 1, 0: none
+    // KV head of position si in head_ids / of pair b; pairs mode: then the sequence of pair b
+    int *hids = reinterpret_cast<int *>(cls_of + align16((size_t)batch));
+    int *pseq = hids + batch;
+    const int n_sel = PAIRS ? 1 : p.n_sel;    // heads per enumeration row
     const int n_ids = PAIRS ? batch : p.n_sel;
-    unsigned char *after_tables =
-        smem + align16((size_t)(6 * batch + 5 + persist_id_words(batch, p.n_sel, PAIRS)) * sizeof(int));
-    __shared__ TicketPool pool;
+    unsigned char *after_tables = smem + persist_table_bytes(batch, p.n_sel, PAIRS);
+    __shared__ ChunkPool pool;
     Mail *mail = reinterpret_cast<Mail *>(after_tables);             // [NW][2]
-    unsigned char *staging = after_tables + 2 * NW * sizeof(Mail);
+    Fold *fold = reinterpret_cast<Fold *>(after_tables + 2 * NW * sizeof(Mail));
+    unsigned char *staging = reinterpret_cast<unsigned char *>(fold + NS);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int seg_tokens = p.seg_tokens;
+    const int chunk_tokens = p.chunk_tokens;
 
     // ---- work enumeration.  All threads fetch the lengths and work out the counts of their
-    // rows (whole chunks; size class of the ragged last chunk), four rows a thread and round
-    // so that the loads of a round are in flight together.  Wave 0 then turns the counts into
-    // running counts in place: lane l owns `per` consecutive rows, adds up their counts, the
-    // 64 lane totals go through one in-wave scan, and a second pass over the lane's rows
-    // writes the tables.  `per` is odd so that the lanes' LDS accesses (stride `per` words)
-    // fall into different banks.
+    // rows (whole segments; size class of the last, shorter segment), four rows a thread and
+    // round so that the loads of a round are in flight together.  Wave 0 then turns the counts
+    // into running counts: lane l owns `per` consecutive rows, adds up their counts, the 64
+    // lane totals go through one in-wave scan, and a second pass over the lane's rows writes
+    // the tables.  `per` is odd so that the lanes' LDS accesses (stride `per` words) fall into
+    // different banks.
     for (int i = tid; i < n_ids; i += NT) {
         hids[i] = PAIRS ? p.pair_head[i] : p.head_ids[i];
         if (PAIRS) pseq[i] = p.pair_seq[i];
     }
-    // size class of a ragged last chunk of `rt` tokens: 0 = longest quarter ... 3 = shortest
-    auto ragged_class = [&](int rt) { return 3 - min(3, (4 * rt - 1) / p.chunk_tokens); };
+    // size class of a last segment of `rt` tokens (0 < rt <= seg_tokens): 0 = the largest
+    auto size_class = [&](int rt) {
+        const int j = (16 * rt - 1) / seg_tokens;       // rt in (j/16, (j+1)/16] of a segment
+        if (j >= 1) return kLinClasses - j;
+        return kLinClasses + (rt <= (seg_tokens >> 5) ? 1 : 0) + (rt <= (seg_tokens >> 6) ? 1 : 0) +
+               (rt <= (seg_tokens >> 7) ? 1 : 0);
+    };
     for (int i0 = tid; i0 < batch; i0 += 4 * NT) {
         int row[4], L[4];
 #pragma unroll
@@ -208,14 +375,14 @@ __global__ __launch_bounds__((NW + 1) * 64)
         for (int u = 0; u < 4; ++u) {
             const int i = i0 + u * NT;
             if (i >= batch) continue;
-            const int nF = L[u] > 0 ? L[u] / p.chunk_tokens : 0;
-            const int rt = L[u] > 0 ? L[u] - nF * p.chunk_tokens : 0;
+            const int nF = L[u] > 0 ? L[u] / seg_tokens : 0;
+            const int rt = L[u] > 0 ? L[u] - nF * seg_tokens : 0;
             int cls = -1;
-            if (rt > 0) cls = ragged_class(rt);
-            if (L[u] <= 0 && p.direct_single) cls = 3;      // the item that writes the zeros
+            if (rt > 0) cls = size_class(rt);
+            if (L[u] <= 0 && p.direct_single) cls = kClasses - 1;   // the segment that writes the zeros
             lens[i] = L[u];
-            firstF[i] = nF;                 // counts for now; running counts after the scan
-            firstT[i] = cls;
+            firstF[i] = nF;                             // counts for now; running counts after the scan
+            cls_of[i] = (unsigned char)(cls + 1);
         }
     }
     if (tid < 2 * NW) mail[tid].flag = kMailEmpty;
@@ -225,72 +392,80 @@ __global__ __launch_bounds__((NW + 1) * 64)
     }
     __syncthreads();
     if (wave == 0) {
-        // classes 0,1 and 2,3 travel packed in 16-bit halves (batch < 65536)
-        auto class_counts = [&](int cls, int &n01, int &n23) {
-            n01 = cls == 0 ? 1 : (cls == 1 ? 1 << 16 : 0);
-            n23 = cls == 2 ? 1 : (cls == 3 ? 1 << 16 : 0);
-        };
+        // Running count of whole segments, and a counting sort of the rows by class.  Class
+        // counts travel packed, two to an int (rows < 65536): classes 2j and 2j + 1.
+        constexpr int NP = (kClasses + 1) / 2;
         const int per = ((batch + 63) / 64) | 1;
         const int lo = min(lane * per, batch), hi = min(lo + per, batch);
-        int sumF = 0, sum01 = 0, sum23 = 0;
+        auto one_of = [](int cls, int j) { return cls == 2 * j ? 1 : (cls == 2 * j + 1 ? 1 << 16 : 0); };
+        int sumF = 0, sumC[NP];
+#pragma unroll
+        for (int j = 0; j < NP; ++j) sumC[j] = 0;
         for (int b = lo; b < hi; ++b) {
-            int n01, n23;
-            class_counts(firstT[b], n01, n23);
+            const int cls = (int)cls_of[b] - 1;
             sumF += firstF[b];
-            sum01 += n01;
-            sum23 += n23;
+#pragma unroll
+            for (int j = 0; j < NP; ++j) sumC[j] += one_of(cls, j);
         }
-        int inclF = sumF, incl01 = sum01, incl23 = sum23;
+        int inclF = sumF, inclC[NP];
+#pragma unroll
+        for (int j = 0; j < NP; ++j) inclC[j] = sumC[j];
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int upF = __shfl_up(inclF, off, 64);
-            const int up01 = __shfl_up(incl01, off, 64);
-            const int up23 = __shfl_up(incl23, off, 64);
+            int upC[NP];
+#pragma unroll
+            for (int j = 0; j < NP; ++j) upC[j] = __shfl_up(inclC[j], off, 64);
             if (lane >= off) {
                 inclF += upF;
-                incl01 += up01;
-                incl23 += up23;
+#pragma unroll
+                for (int j = 0; j < NP; ++j) inclC[j] += upC[j];
             }
         }
-        int runF = inclF - sumF, run01 = incl01 - sum01, run23 = incl23 - sum23;
+        // where this lane's rows of class k go: rows of larger classes (all lanes), then rows
+        // of class k in lower lanes
+        int runF = inclF - sumF, runC[NP];
+        {
+            int before = 0;                         // rows of the classes handled so far
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {
+                const int tot = __builtin_amdgcn_readlane(inclC[j], 63);
+                const int excl = inclC[j] - sumC[j];
+                const int lo_half = before + (excl & 0xffff);
+                before += tot & 0xffff;
+                const int hi_half = before + (int)((unsigned)excl >> 16);
+                before += (int)((unsigned)tot >> 16);
+                runC[j] = lo_half | (hi_half << 16);
+            }
+            if (lane == 63) {
+                firstF[batch] = inclF;
+                // number of listed rows, kept in the table's spare word
+                lens[2 * batch + 1] = before;
+            }
+        }
         for (int b = lo; b < hi; ++b) {
-            int n01, n23;
-            class_counts(firstT[b], n01, n23);
+            const int cls = (int)cls_of[b] - 1;
             const int nF = firstF[b];
             firstF[b] = runF;
-            firstT[0 * (batch + 1) + b] = run01 & 0xffff;
-            firstT[1 * (batch + 1) + b] = run01 >> 16;
-            firstT[2 * (batch + 1) + b] = run23 & 0xffff;
-            firstT[3 * (batch + 1) + b] = run23 >> 16;
             runF += nF;
-            run01 += n01;
-            run23 += n23;
-        }
-        if (lane == 63) {
-            firstF[batch] = inclF;
-            firstT[0 * (batch + 1) + batch] = incl01 & 0xffff;
-            firstT[1 * (batch + 1) + batch] = incl01 >> 16;
-            firstT[2 * (batch + 1) + batch] = incl23 & 0xffff;
-            firstT[3 * (batch + 1) + batch] = incl23 >> 16;
+            if (cls >= 0) {
+                int pos = 0;
+#pragma unroll
+                for (int j = 0; j < NP; ++j) {
+                    if (cls == 2 * j) pos = runC[j] & 0xffff;
+                    if (cls == 2 * j + 1) pos = (int)((unsigned)runC[j] >> 16);
+                    runC[j] += one_of(cls, j);
+                }
+                order[pos] = (unsigned short)b;
+            }
         }
     }
     __syncthreads();
-    const int totalF = firstF[batch];                         // whole chunks of all sequences
-    int class_end[4];                                         // running ends of the ragged classes
-    {
-        int run = totalF;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            run += firstT[k * (batch + 1) + batch];
-            class_end[k] = run;
-        }
-    }
-    const int total = class_end[3] * n_sel;
-    const int stride = gridDim.x * NW;                        // streaming waves in the grid
+    const int totalF = firstF[batch];                         // whole segments of all rows
+    const int total = (totalF + lens[2 * batch + 1]) * n_sel; // segments of this launch
 
-    // item number -> (row, chunk, head): whole chunks come first, ragged last chunks after
-    // them by size class; binary search in the matching running-count table.  Works per lane
-    // (the writer wave decodes a batch of tickets at once, one per lane).
+    // segment number -> (row, segment, head): whole segments come first (binary search in the
+    // running counts), last segments after them by size class (sorted list).  Works per lane.
     auto upper = [&](const int *tab, int key) {               // last b with tab[b] <= key
         int lo = 0, hi = batch - 1;
         while (lo < hi) {
@@ -302,39 +477,87 @@ __global__ __launch_bounds__((NW + 1) * 64)
         }
         return lo;
     };
-    auto decode = [&](int item) {
-        ItemDesc d;
-        d.flags = item < total ? kItemExists : 0;
-        const int w = min(item, max(total - 1, 0));
-        const int cg = PAIRS ? w : w / n_sel;
-        d.si = PAIRS ? 0 : w - cg * n_sel;
-        int L;
-        if (cg < totalF) {
-            d.b = upper(firstF, cg);
-            d.c = cg - firstF[d.b];
-            L = lens[d.b];
-            d.n_tok = p.chunk_tokens;
-        } else {
-            int k = 0, begin = totalF;
-#pragma unroll
-            for (int j = 0; j < 3; ++j)
-                if (cg >= class_end[j]) {
-                    k = j + 1;
-                    begin = class_end[j];
-                }
-            d.b = upper(firstT + k * (batch + 1), cg - begin);
-            L = lens[d.b];
-            d.c = L > 0 ? L / p.chunk_tokens : 0;
-            d.n_tok = L > 0 ? L - d.c * p.chunk_tokens : 0;
+    struct Segment {
+        int b, g, seq;      // enumeration row, KV head, sequence
+        int t0, n_tok;      // first token, tokens
+        int ct, ns;         // tokens per chunk, chunks
+        int kind, dest;     // where the whole segment goes
+        int nseg, out_row;  // segments of the row; first of its R rows in `out`
+    };
+    // Tokens per chunk of a segment of n_tok tokens: the shorter the segment, the later it is
+    // handed out and the finer it is cut, so that the chunks still running when the work runs
+    // out are short ones.  A function of the row's length only, like everything that shapes
+    // the arithmetic.
+    auto chunk_for = [&](int n_tok) {
+        int ct = chunk_tokens;
+        if (seg_tokens > chunk_tokens) {
+            if (n_tok <= seg_tokens / HETIS_FINE_CHUNK_BELOW) ct = chunk_tokens / 2;
+            if (n_tok <= seg_tokens / (4 * HETIS_FINE_CHUNK_BELOW)) ct = chunk_tokens / 4;
+            ct = max(ct, 2 * kBlockTokens);
         }
-        d.g = hids[PAIRS ? d.b : d.si];
-        d.seq = PAIRS ? pseq[d.b] : d.b;
-        const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-        if (p.direct_single && n_chunks <= 1) d.flags |= kItemToOut;
-        if (L <= 0) d.flags |= kItemZero;
+        return ct;
+    };
+    auto decode = [&](int segno) {
+        Segment s;
+        const int w = min(segno, max(total - 1, 0));
+        const int cg = PAIRS ? w : w / n_sel;
+        const int si = PAIRS ? 0 : w - cg * n_sel;
+        int L, j;
+        if (cg < totalF) {
+            s.b = upper(firstF, cg);
+            j = cg - firstF[s.b];
+            L = lens[s.b];
+            s.n_tok = seg_tokens;
+        } else {
+            s.b = order[cg - totalF];
+            L = lens[s.b];
+            j = L > 0 ? L / seg_tokens : 0;
+            s.n_tok = L > 0 ? L - j * seg_tokens : 0;
+        }
+        s.t0 = j * seg_tokens;
+        s.ct = chunk_for(s.n_tok);
+        s.ns = max(1, (s.n_tok + s.ct - 1) / s.ct);
+        s.g = hids[PAIRS ? s.b : si];
+        s.seq = PAIRS ? pseq[s.b] : s.b;
+        const int n_segs = (L + seg_tokens - 1) / seg_tokens;
+        s.nseg = n_segs;
+        s.out_row = s.seq * p.n_q_heads + s.g * R;
+        if (L <= 0) {
+            s.kind = kKindZero;
+            s.dest = s.out_row;
+        } else if (p.direct_single && n_segs <= 1) {
+            s.kind = kKindOut;
+            s.dest = s.out_row;
+        } else {
+            s.kind = kKindPartial;
+            s.dest = (s.b * n_sel + si) * p.max_segs + j;
+        }
+        return s;
+    };
+    // chunk i of a segment; `slot`: the segment's fold slot (segments of several chunks)
+    auto chunk_of = [&](const Segment &s, int i, int slot) {
+        ChunkDesc d;
+        d.b = s.b;
+        d.g = s.g;
+        d.seq = s.seq;
+        d.t0 = s.t0 + i * s.ct;
+        d.n_tok = max(0, min(s.ct, s.n_tok - i * s.ct));
+        d.flags = kItemExists;
+        d.kind = s.ns > 1 ? (int)kKindFold : s.kind;
+        d.dest = s.ns > 1 ? slot : s.dest;
+        d.cs = i;
+        d.nseg = s.nseg;
+        d.out_row = s.out_row;
         d.pad = 0;
         return d;
     };
+    // Work a workgroup has without a ticket.  When segments have several chunks: segment number
+    // blockIdx.x, whose first NW chunks the streaming waves take directly (wave v takes chunk
+    // v) and which owns fold slot 0.  When every segment is a single chunk: segments blockIdx.x
+    // + v * gridDim.x, one per streaming wave v.  Tickets number the segments after these.
+    const bool single_mode = seg_tokens == chunk_tokens;
+    const bool have_first = (int)blockIdx.x < total;
+    const long long n_fixed = (long long)gridDim.x * (single_mode ? NW : 1);
 
     if (wave == NW) {
         // ------------------------------------------------------------ writer wave
@@ -344,49 +567,210 @@ __global__ __launch_bounds__((NW + 1) * 64)
         int done_mask = 0;
         int idle = 0;
         int pool_end = 0;                 // entries published so far
-        long long last_base = 2ll * stride;   // item number of the last ticket drawn here
-        bool exhausted = total <= 2 * stride;    // no item left beyond the fixed ones
+        unsigned busy = 0;                // fold slots in use
+        bool exhausted = total <= n_fixed;            // no segment left to draw
+        bool first = have_first && !single_mode;      // the next segment to publish is the workgroup's first
+        bool closed = false;              // the "no work left" entries have been published
+        // Segments drawn and decoded (one per lane, lanes [pend_i, pend_n) still to publish)
+        Segment mine{};
+        int pend_i = 0, pend_n = 0;
+        if (first) {
+            mine = decode(blockIdx.x);
+            pend_n = 1;
+        }
+        long long last_base = n_fixed;    // number of the last segment drawn here
+        int last_ns = single_mode ? 1 : 2;    // chunks of the last segment published
+        const long long wave_round = (long long)gridDim.x * NW;
+        auto bcast = [&](const Segment &s, int k) {
+            Segment r;
+            r.b = __builtin_amdgcn_readlane(s.b, k);
+            r.g = __builtin_amdgcn_readlane(s.g, k);
+            r.seq = __builtin_amdgcn_readlane(s.seq, k);
+            r.t0 = __builtin_amdgcn_readlane(s.t0, k);
+            r.n_tok = __builtin_amdgcn_readlane(s.n_tok, k);
+            r.ct = __builtin_amdgcn_readlane(s.ct, k);
+            r.ns = __builtin_amdgcn_readlane(s.ns, k);
+            r.kind = __builtin_amdgcn_readlane(s.kind, k);
+            r.dest = __builtin_amdgcn_readlane(s.dest, k);
+            r.nseg = __builtin_amdgcn_readlane(s.nseg, k);
+            r.out_row = __builtin_amdgcn_readlane(s.out_row, k);
+            return r;
+        };
         while (done_mask != (1 << NW) - 1 && idle < kSpinLimit) {
             bool progressed = false;
-            // keep the ticket pool ahead of the streaming waves
+            // ---- keep the chunk pool ahead of the streaming waves
             const int taken = __builtin_amdgcn_readfirstlane(
                 __hip_atomic_load(&pool.next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-            // batch size shrinks as the work runs out (judged by the last ticket seen), so
-            // that the last items are not parked in one workgroup's pool
+            // Draw.  Segments of several chunks are drawn one at a time and late, when fewer
+            // than HETIS_POOL_AHEAD chunks are waiting (they are handed out longest first, and
+            // work parked in one workgroup's pool cannot be taken by another that has run
+            // dry).  Once the segments are single chunks, tickets are drawn in batches that
+            // shrink as the work runs out (a same-address device atomic costs about as much
+            // as a short chunk).
             const long long left = (long long)total - last_base;
-            const int n_draw = left > 8ll * stride ? kTicketBatch : (left > 2ll * stride ? 2 : 1);
-            if (pool_end - taken < n_draw) {
-                long long base = total;   // past the last item: "no more work"
-                if (!exhausted) {
-                    unsigned t = 0;
-                    if (lane == 0)
-                        t = __hip_atomic_fetch_add(p.control + kCtlTickets, (unsigned)n_draw,
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    base = 2ll * stride + __builtin_amdgcn_readfirstlane(t);
-                    last_base = base;
-                    if (base + n_draw >= total) exhausted = true;
-                }
-                if (lane < n_draw)
-                    pool.desc[(pool_end + lane) % kPoolSize] =
-                        decode((int)min(base + lane, (long long)total));
-                pool_end += n_draw;
-                __hip_atomic_store(&pool.end, pool_end, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const int n_draw = last_ns > 1 ? 1
+                               : (left > 8 * wave_round ? kTicketBatch : (left > 2 * wave_round ? 2 : 1));
+            // (multi-chunk segments) look-ahead in chunks: HETIS_POOL_AHEAD while plenty of
+            // segments are left, one when about a round of them is left, none at the very end
+            // (a segment is then drawn only when a wave is already waiting for a chunk)
+            const int ahead_multi = left > 4 * (long long)gridDim.x
+                                        ? HETIS_POOL_AHEAD
+                                        : (left > (long long)gridDim.x ? min(HETIS_POOL_AHEAD, 1) : 0);
+            const int ahead = last_ns > 1 ? ahead_multi : n_draw;
+            if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
+                unsigned t = 0;
+                if (lane == 0)
+                    t = __hip_atomic_fetch_add(p.control + kCtlTickets, (unsigned)n_draw,
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const long long base = n_fixed + __builtin_amdgcn_readfirstlane(t);
+                last_base = base;
+                if (base + n_draw >= total) exhausted = true;
+                pend_i = 0;
+                pend_n = (int)max(0ll, min((long long)n_draw, (long long)total - base));
+                if (pend_n > 0) mine = decode((int)min(base + lane, (long long)total - 1));
                 progressed = true;
             }
+            if (pend_i < pend_n) {
+                // all remaining drawn segments are single chunks: publish them together
+                const bool single = __builtin_amdgcn_ballot_w64(lane >= pend_i && lane < pend_n &&
+                                                                mine.ns != 1) == 0;
+                if (single && !first) {
+                    const int cnt = pend_n - pend_i;
+                    if (pool_end + cnt - taken <= kPoolSize) {
+                        if (lane >= pend_i && lane < pend_n)
+                            pool.desc[(pool_end + lane - pend_i) % kPoolSize] = chunk_of(mine, 0, 0);
+                        pool_end += cnt;
+                        __hip_atomic_store(&pool.end, pool_end, __ATOMIC_RELEASE,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                        pend_i = pend_n;
+                        last_ns = 1;
+                        progressed = true;
+                    }
+                } else {
+                    const Segment seg = bcast(mine, pend_i);
+                    if (pool_end + seg.ns - taken <= kPoolSize &&
+                        (seg.ns == 1 || busy != (1u << NS) - 1)) {
+                        int slot = 0;
+                        if (seg.ns > 1) {
+                            slot = __builtin_ctz(~busy);
+                            busy |= 1u << slot;
+                            if (lane == 0) {
+                                fold[slot].next = 0;
+                                fold[slot].ns = seg.ns;
+                                fold[slot].kind = seg.kind;
+                                fold[slot].dest = seg.dest;
+                                fold[slot].nseg = seg.nseg;
+                                fold[slot].out_row = seg.out_row;
+                            }
+                        }
+                        // the first NW chunks of the first segment are taken without the pool
+                        const int skip = first ? min(NW, seg.ns) : 0;
+                        if (lane >= skip && lane < seg.ns)
+                            pool.desc[(pool_end + lane - skip) % kPoolSize] = chunk_of(seg, lane, slot);
+                        pool_end += seg.ns - skip;
+                        __hip_atomic_store(&pool.end, pool_end, __ATOMIC_RELEASE,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                        ++pend_i;
+                        first = false;
+                        last_ns = seg.ns;
+                        progressed = true;
+                    }
+                }
+            }
+            if (exhausted && pend_i == pend_n && !closed && pool_end + NW - taken <= kPoolSize) {
+                // one "no work left" entry per streaming wave
+                if (lane < NW) {
+                    ChunkDesc none{};
+                    pool.desc[(pool_end + lane) % kPoolSize] = none;
+                }
+                pool_end += NW;
+                __hip_atomic_store(&pool.end, pool_end, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                closed = true;
+                progressed = true;
+            }
+            // ---- results
 #pragma unroll
             for (int v = 0; v < NW; ++v) {
                 if (done_mask & (1 << v)) continue;
                 Mail &mb = mail[v * 2 + next_box[v]];
                 const int f = __builtin_amdgcn_readfirstlane(mail_load(&mb.flag));
-                if (f == kMailFull) {
-                    flush_mailbox<D, R>(mb, p, lane);
-                    mail_store(&mb.flag, kMailEmpty);
-                    next_box[v] ^= 1;
-                    progressed = true;
-                } else if (f == kMailDone) {
+                if (f == kMailDone) {
                     done_mask |= 1 << v;
                     progressed = true;
+                    continue;
                 }
+                if (f != kMailFull) continue;
+                const int kind = __builtin_amdgcn_readfirstlane(mb.kind);
+                const int dest = __builtin_amdgcn_readfirstlane(mb.dest);
+                // a partial result that this launch merges itself: stored, then counted in once
+                // the mailbox has been handed back
+                bool arrive = false;
+                int arrive_dest = 0, arrive_nseg = 0, arrive_out = 0;
+                if (kind != kKindFold) {
+                    if (kind == kKindPartial && p.arrivals) {
+                        store_partial_coherent<D, R>(mb.o, mb.lse, nullptr, dest, p, lane);
+                        arrive = true;
+                        arrive_dest = dest;
+                        arrive_nseg = __builtin_amdgcn_readfirstlane(mb.nseg);
+                        arrive_out = __builtin_amdgcn_readfirstlane(mb.out_row);
+                    } else {
+                        store_result<D, R>(mb.o, mb.lse, nullptr, kind, dest, p, lane);
+                    }
+                } else {
+                    Fold &fs = fold[dest];
+                    const int cs = __builtin_amdgcn_readfirstlane(mb.cs);
+                    if (cs != __builtin_amdgcn_readfirstlane(fs.next)) continue;   // not its turn yet
+                    const bool last = cs + 1 == __builtin_amdgcn_readfirstlane(fs.ns);
+                    // fold chunk cs into the slot; a lane owns the same elements every time
+#pragma unroll
+                    for (int idx = lane * 4; idx < R * D; idx += 256) {
+                        const int r = idx / D, d = idx % D;
+                        const float4 x = *reinterpret_cast<const float4 *>(&mb.o[r][d]);
+                        float4 a = x;
+                        if (cs > 0) {
+                            const float Mo = fs.M[r], lc = mb.lse[r];
+                            const float Mn = fmaxf(Mo, lc);
+                            const float so = fast_exp2(Mo - Mn), sc = fast_exp2(lc - Mn);
+                            const float4 y = *reinterpret_cast<const float4 *>(&fs.acc[r][d]);
+                            a = make_float4(fmaf(y.x, so, x.x * sc), fmaf(y.y, so, x.y * sc),
+                                            fmaf(y.z, so, x.z * sc), fmaf(y.w, so, x.w * sc));
+                        }
+                        *reinterpret_cast<float4 *>(&fs.acc[r][d]) = a;
+                    }
+                    wave_lds_fence();       // every lane has read M before lane r rewrites it
+                    if (lane < R) {
+                        const float lc = mb.lse[lane];
+                        float Mn = lc, Wn = 1.f;
+                        if (cs > 0) {
+                            const float Mo = fs.M[lane];
+                            Mn = fmaxf(Mo, lc);
+                            Wn = fs.W[lane] * fast_exp2(Mo - Mn) + fast_exp2(lc - Mn);
+                        }
+                        fs.W[lane] = Wn;
+                        // after the last chunk the slot holds the segment's log-sum-exp
+                        fs.M[lane] = last ? Mn + fast_log2(Wn) : Mn;
+                    }
+                    if (lane == 0) fs.next = cs + 1;
+                    wave_lds_fence();
+                    if (last) {
+                        const int fkind = __builtin_amdgcn_readfirstlane(fs.kind);
+                        const int fdest = __builtin_amdgcn_readfirstlane(fs.dest);
+                        if (fkind == kKindPartial && p.arrivals) {
+                            store_partial_coherent<D, R>(fs.acc, fs.M, fs.W, fdest, p, lane);
+                            arrive = true;
+                            arrive_dest = fdest;
+                            arrive_nseg = __builtin_amdgcn_readfirstlane(fs.nseg);
+                            arrive_out = __builtin_amdgcn_readfirstlane(fs.out_row);
+                        } else {
+                            store_result<D, R>(fs.acc, fs.M, fs.W, fkind, fdest, p, lane);
+                        }
+                        busy &= ~(1u << dest);
+                    }
+                }
+                mail_store(&mb.flag, kMailEmpty);
+                next_box[v] ^= 1;
+                progressed = true;
+                if (arrive) arrive_and_merge<D, R>(p, arrive_dest, arrive_nseg, arrive_out, lane);
             }
             if (progressed) {
                 idle = 0;
@@ -414,23 +798,24 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // ---------------------------------------------------------------- streaming waves
     struct Slot {
         ItemHdr h;
-        int ids;            // lane i: physical block of the item's i-th tile
+        int ids;            // lane i: physical block of the chunk's i-th tile
         int64_t head_off;
         bool exists;
     };
-    // decoded item -> the wave's (uniform) bookkeeping, and the load of its block ids
-    auto fill = [&](const ItemDesc &d, Slot &s) {
+    // chunk descriptor -> the wave's (uniform) bookkeeping, and the load of its block ids
+    auto fill = [&](const ChunkDesc &d, Slot &s) {
         const int flags = __builtin_amdgcn_readfirstlane(d.flags);
         const int n_tok = __builtin_amdgcn_readfirstlane(d.n_tok);
         s.h.b = __builtin_amdgcn_readfirstlane(d.b);
-        s.h.c = __builtin_amdgcn_readfirstlane(d.c);
-        s.h.si = __builtin_amdgcn_readfirstlane(d.si);
         s.h.g = __builtin_amdgcn_readfirstlane(d.g);
         s.h.seq = __builtin_amdgcn_readfirstlane(d.seq);
+        s.h.t0 = __builtin_amdgcn_readfirstlane(d.t0);
+        s.h.kind = __builtin_amdgcn_readfirstlane(d.kind);
+        s.h.dest = __builtin_amdgcn_readfirstlane(d.dest);
+        s.h.cs = __builtin_amdgcn_readfirstlane(d.cs);
+        s.h.nseg = __builtin_amdgcn_readfirstlane(d.nseg);
+        s.h.out_row = __builtin_amdgcn_readfirstlane(d.out_row);
         s.exists = (flags & kItemExists) != 0;
-        s.h.to_out = (flags & kItemToOut) != 0;
-        s.h.zero = (flags & kItemZero) != 0;
-        s.h.t0 = s.h.c * p.chunk_tokens;
         s.h.nblk = s.exists ? (n_tok + kBlockTokens - 1) / kBlockTokens : 0;
         s.h.rem = n_tok & (kBlockTokens - 1);
         s.head_off = PAIRS ? 0 : (int64_t)s.h.g * p.stride_head;   // pairs: single-head tiles
@@ -455,8 +840,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
         }
         if (lane == 0) report_error(p.control, kErrMailboxWait);
     };
-    // next item from the workgroup's pool, decoded by the writer wave (flags 0 = none left)
-    auto take_ticket = [&]() {
+    // next chunk from the workgroup's pool (flags 0 = none left)
+    auto take_chunk = [&]() {
         int i = 0;
         if (lane == 0)
             i = __hip_atomic_fetch_add(&pool.next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -468,31 +853,49 @@ __global__ __launch_bounds__((NW + 1) * 64)
             __builtin_amdgcn_s_sleep(2);
         }
         if (lane == 0) report_error(p.control, kErrTicketWait);
-        ItemDesc none{};
+        ChunkDesc none{};
         return none;
     };
 
-    const int w = blockIdx.x * NW + wave;
     unsigned char *my_staging = staging + (size_t)wave * Policy::kWaveLdsBytes;
     Mail *my_mail = mail + wave * 2;
-    if (total <= 0 || w >= total) {
-        mail_store(&my_mail[0].flag, kMailDone);
-        return;
-    }
 
     constexpr int RING = Policy::kRing;             // tile pairs a wave keeps in flight, at most
     Slot cur, nxt;
     typename Policy::Query q;
     typename Policy::QueryPrefetch q_pre;
     Tile ring[RING];
-    fill(decode(w), cur);           // items w and w + stride are this wave's without a ticket
+    {
+        // first chunk: of the work the workgroup has without a ticket, else from the pool
+        ChunkDesc d{};
+        bool direct = false;
+        if (single_mode) {
+            const long long mine = (long long)blockIdx.x + (long long)wave * gridDim.x;
+            if (mine < total) {
+                d = chunk_of(decode((int)mine), 0, 0);
+                direct = true;
+            }
+        } else if (have_first) {
+            const Segment s0 = decode(blockIdx.x);
+            if (wave < s0.ns) {
+                d = chunk_of(s0, wave, 0);
+                direct = true;
+            }
+        }
+        if (!direct) d = take_chunk();
+        fill(d, cur);
+    }
+    if (!cur.exists) {
+        mail_store(&my_mail[0].flag, kMailDone);
+        return;
+    }
     nxt = cur;
     Policy::q_prefetch(q_pre, q_rows(cur), lane);
 #pragma unroll
     for (int s = 0; s < RING; ++s) issue(ring[s], cur.ids, s, cur.head_off, s < cur.h.nblk);
     int n = 0;
     for (;; ++n) {
-        Policy::q_commit(q, q_pre, my_staging, lane);   // this item's query operand
+        Policy::q_commit(q, q_pre, my_staging, lane);   // this chunk's query operand
 
         typename Policy::State st;
         Policy::reset(st);
@@ -501,7 +904,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // The scheduling fences keep "consume a slot, refill it at once" in program order;
         // without them the compiler batches the tiles' arithmetic ahead of the refills and
         // the wave ends up waiting with nothing in flight.
-        auto steady_turn = [&](int i) {                 // whole tiles; refills stay in this item
+        auto steady_turn = [&](int i) {                 // whole tiles; refills stay in this chunk
 #pragma unroll
             for (int s = 0; s < RING; ++s) {
                 Policy::template update<false>(st, ring[s], q, p.scale_log2, lane, kBlockTokens,
@@ -511,16 +914,16 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        // The next item is chosen as late as its block ids allow (three ring turns before
-        // the end of this one), so that little undone work is held back when the tickets run
+        // The next chunk is taken as late as its block ids allow (three ring turns before
+        // the end of this one), so that little undone work is held back when the work runs
         // out.
         int i = 0;
         for (; i + 4 * RING < lim; i += RING) steady_turn(i);
-        fill(n == 0 ? decode(w + stride) : take_ticket(), nxt);
-        Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next item's query rows
+        fill(take_chunk(), nxt);
+        Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next chunk's query rows
         for (; i + RING < lim; i += RING) steady_turn(i);
-        // last turn of this item (the only place a ragged block can be): its refills are the
-        // first tiles of the next item
+        // last turn of this chunk (the only place a ragged block can be): its refills are the
+        // first tiles of the next chunk
 #pragma unroll
         for (int s = 0; s < RING; ++s) {
             if (i + s < n_my) {
@@ -532,14 +935,16 @@ __global__ __launch_bounds__((NW + 1) * 64)
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        // hand the finished item to the writer
+        // hand the finished chunk to the writer
         Mail &mb = my_mail[n & 1];
         wait_empty(mb);
-        if (!cur.h.zero) Policy::finish(st, mb.o, mb.lse, lane);
+        if (cur.h.kind != kKindZero) Policy::finish(st, mb.o, mb.lse, lane);
         if (lane == 0) {
-            mb.out_row = cur.h.seq * p.n_q_heads + cur.h.g * R;
-            mb.item = (cur.h.b * n_sel + cur.h.si) * p.max_chunks + cur.h.c;
-            mb.kind = cur.h.zero ? kKindZero : (cur.h.to_out ? kKindOut : kKindPartial);
+            mb.kind = cur.h.kind;
+            mb.dest = cur.h.dest;
+            mb.cs = cur.h.cs;
+            mb.nseg = cur.h.nseg;
+            mb.out_row = cur.h.out_row;
         }
         mail_store(&mb.flag, kMailFull);
         if (!nxt.exists) break;

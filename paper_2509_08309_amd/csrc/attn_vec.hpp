@@ -7,8 +7,8 @@
 //   - q.k is a v_dot2 chain per lane followed by a DPP sum over the D/8 lanes of a row;
 //   - each group of D/8 lanes runs its own online softmax over the tokens it sees
 //     (exp2 domain, fp32), so p never leaves registers between q.k and p.v;
-//   - the lane groups of a wave, then the waves of the workgroup, are merged once per
-//     chunk, in a fixed order, through shuffles and LDS.
+//   - the lane groups of a wave are merged once per chunk, in a fixed order, through
+//     shuffles.
 // Nothing depends on how many heads were selected: the result for one (sequence, head)
 // is a function of that sequence's length alone.
 #pragma once
@@ -41,26 +41,6 @@ struct TileRegs {
     uint4 k[NI];
     uint4 v[NI];
 };
-
-// Issue the 128-bit loads of one K tile and one V tile (no wait).
-template <int D>
-__device__ __forceinline__ void tile_issue(TileRegs<D> &t, const __half *k_cache,
-                                           const __half *v_cache, int64_t base, int lane)
-{
-    // non-temporal like the buffer loads of the persistent kernel: a tile is read once
-    const u32x4 *kp = reinterpret_cast<const u32x4 *>(k_cache + base) + lane;
-    const u32x4 *vp = reinterpret_cast<const u32x4 *>(v_cache + base) + lane;
-#pragma unroll
-    for (int i = 0; i < TileRegs<D>::NI; ++i) {
-        const u32x4 x = __builtin_nontemporal_load(kp + i * 64);
-        t.k[i] = make_uint4(x.x, x.y, x.z, x.w);
-    }
-#pragma unroll
-    for (int i = 0; i < TileRegs<D>::NI; ++i) {
-        const u32x4 x = __builtin_nontemporal_load(vp + i * 64);
-        t.v[i] = make_uint4(x.x, x.y, x.z, x.w);
-    }
-}
 
 // One tile (16 tokens) of K and V held in registers -> update of the running state.
 template <int D, int R, bool MASKED>
@@ -155,165 +135,6 @@ __device__ __forceinline__ void vec_wave_merge(VecState<D, R> &st)
     }
 }
 
-// ---- helpers of the simple (non-persistent) kernel: cross-wave merge through LDS
-template <int D, int R, int NW>
-struct WaveMergeLds {
-    float o[NW][R][D];
-    float m[NW][R];
-    float l[NW][R];
-};
-
-template <int D, int R>
-struct ResultLds {
-    float o[R][D];      // normalised output rows
-    float lse[R];       // natural-log log-sum-exp of each row (used by partial results only)
-};
-
-// After a barrier: combine the NW wave results (ascending wave order) into the result area.
-template <int D, int R, int NW, int NTHREADS>
-__device__ __forceinline__ void lds_combine(const WaveMergeLds<D, R, NW> &sm, ResultLds<D, R> &res,
-                                            int tid)
-{
-    for (int idx = tid; idx < R * D; idx += NTHREADS) {
-        const int r = idx / D, d = idx % D;
-        float M = sm.m[0][r];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm.m[w][r]);
-        float acc = 0.f, lsum = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float a = fast_exp2(sm.m[w][r] - M);
-            acc += sm.o[w][r][d] * a;
-            lsum += sm.l[w][r] * a;
-        }
-        res.o[r][d] = acc * __builtin_amdgcn_rcpf(lsum);
-        if (d == 0) res.lse[r] = (M + fast_log2(lsum)) * kLn2;
-    }
-}
-
-// Result area -> `out` (fp16) or the partial buffers (fp32); one wave, four elements a lane.
-template <int D, int R>
-__device__ __forceinline__ void flush_result(const ResultLds<D, R> &res, const AttnParams &p,
-                                             int lane, int seq, int b, int g, int si, int c,
-                                             bool to_out)
-{
-    const int n_sel = p.pair_seq ? 1 : p.n_sel;
-    for (int idx = lane * 4; idx < R * D; idx += 256) {
-        const int r = idx / D, d = idx % D;
-        const float4 v = *reinterpret_cast<const float4 *>(&res.o[r][d]);
-        if (to_out) {
-            union {
-                __half2 h[2];
-                uint2 u;
-            } pk;
-            pk.h[0] = __floats2half2_rn(v.x, v.y);
-            pk.h[1] = __floats2half2_rn(v.z, v.w);
-            *reinterpret_cast<uint2 *>(p.out + ((int64_t)seq * p.n_q_heads + g * R + r) * D + d) = pk.u;
-        } else {
-            const int64_t row = (((int64_t)b * n_sel + si) * p.max_chunks + c) * R + r;
-            *reinterpret_cast<float4 *>(p.o_partial + row * D + d) = v;
-            if (d == 0) p.lse_partial[row] = res.lse[r];
-        }
-    }
-}
-
-template <int D, int R, int NTHREADS>
-__device__ __forceinline__ void write_zero_rows(const AttnParams &p, int tid, int seq, int g)
-{
-    for (int idx = tid; idx < R * D; idx += NTHREADS) {
-        const int r = idx / D, d = idx % D;
-        p.out[((int64_t)seq * p.n_q_heads + g * R + r) * D + d] = __float2half_rn(0.f);
-    }
-}
-
-template <int D, int R, int NW>
-__device__ __forceinline__ void vec_lds_put(WaveMergeLds<D, R, NW> &sm, const VecState<D, R> &st,
-                                            int wave, int gid, int sub)
-{
-    if (gid == 0) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-#pragma unroll
-            for (int x = 0; x < 8; ++x) sm.o[wave][r][sub * 8 + x] = st.o[r][x];
-            if (sub == 0) {
-                sm.m[wave][r] = st.m[r];
-                sm.l[wave][r] = st.l[r];
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// Simple form: one workgroup per (chunk slot, selected head, sequence); slots past the end
-// of a sequence exit at once.  Used when the batch is too large for the persistent form.
-// Pairs mode: blockIdx.z is the pair, blockIdx.y is 0.
-// ---------------------------------------------------------------------------------------
-template <int D, int R, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_chunk_vec_kernel(const AttnParams p)
-{
-    constexpr int LPR = D / 8;
-    const int c = blockIdx.x;
-    const int si = blockIdx.y;
-    const int b = blockIdx.z;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int gid = lane / LPR;
-    const int sub = lane % LPR;
-
-    const bool pairs = p.pair_seq != nullptr;
-    const int seq = pairs ? p.pair_seq[b] : b;
-    const int L = p.seq_lens[seq];
-    const int g = pairs ? p.pair_head[b] : p.head_ids[si];
-    const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-    const bool to_out = p.direct_single && n_chunks <= 1;
-
-    if (L <= 0) {
-        if (to_out && c == 0) write_zero_rows<D, R, NW * 64>(p, tid, seq, g);
-        return;
-    }
-    if (c >= n_chunks) return;
-
-    const int t0 = c * p.chunk_tokens;
-    const int n_tok = min(L, t0 + p.chunk_tokens) - t0;
-    const int nblk = (n_tok + kBlockTokens - 1) / kBlockTokens;
-    const int rem = n_tok & (kBlockTokens - 1);
-    const int32_t *bt = p.block_table + (int64_t)b * p.max_blocks_per_seq + t0 / kBlockTokens;
-    const int64_t head_off = pairs ? 0 : (int64_t)g * p.stride_head;
-
-    __half2 qh[R][4];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        Pack16 t;
-        t.u = *reinterpret_cast<const uint4 *>(p.q + ((int64_t)seq * p.n_q_heads + g * R + r) * D + sub * 8);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) qh[r][x] = t.h2[x];
-    }
-
-    VecState<D, R> st;
-    st.reset();
-    TileRegs<D> cur, nxt;
-    int j = wave;
-    if (j < nblk) tile_issue<D>(cur, p.k_cache, p.v_cache, (int64_t)bt[j] * p.stride_block + head_off, lane);
-    while (j < nblk) {
-        const int jn = j + NW;
-        if (jn < nblk)
-            tile_issue<D>(nxt, p.k_cache, p.v_cache, (int64_t)bt[jn] * p.stride_block + head_off, lane);
-        const int n_valid = (rem != 0 && j == nblk - 1) ? rem : kBlockTokens;
-        vec_tile_update_any<D, R>(st, cur, qh, p.scale_log2, gid, n_valid);
-        cur = nxt;
-        j = jn;
-    }
-    vec_wave_merge<D, R>(st);
-    __shared__ WaveMergeLds<D, R, NW> sm;
-    vec_lds_put<D, R, NW>(sm, st, wave, gid, sub);
-    __syncthreads();
-    __shared__ ResultLds<D, R> res;
-    lds_combine<D, R, NW, NW * 64>(sm, res, tid);
-    __syncthreads();
-    if (wave == 0) flush_result<D, R>(res, p, lane, seq, b, g, si, c, to_out);
-}
-
 // ---------------------------------------------------------------------------------------
 // Policy through which the persistent kernel (attn_persist.hpp) uses the vector arithmetic.
 // ---------------------------------------------------------------------------------------
@@ -371,7 +192,7 @@ struct VecPolicy {
         else
             vec_tile_update<D, R, false>(st, t, q.h, scale_log2, lane / (D / 8), kBlockTokens);
     }
-    // normalised rows and their log-sum-exp -> LDS (the wave's mailbox)
+    // normalised rows and their base-2 log-sum-exp -> LDS (the wave's mailbox)
     __device__ static __forceinline__ void finish(State &st, float (&o)[R][D], float (&lse)[R],
                                                   int lane)
     {
@@ -387,14 +208,14 @@ struct VecPolicy {
                                         st.o[r][7] * inv);
                 *reinterpret_cast<float4 *>(&o[r][sub * 8]) = lo;
                 *reinterpret_cast<float4 *>(&o[r][sub * 8 + 4]) = hi;
-                if (sub == 0) lse[r] = (st.m[r] + fast_log2(st.l[r])) * kLn2;
+                if (sub == 0) lse[r] = st.m[r] + fast_log2(st.l[r]);
             }
         }
     }
 };
 
-// Log-sum-exp merge of chunk partials: one workgroup of D threads per (sequence, selected row);
-// in pairs mode per (pair, row of the group).
+// Log-sum-exp merge of the partial results of a row's segments: one workgroup of D threads per
+// (sequence, selected query row); in pairs mode per (pair, row of the group).
 template <int D>
 __global__ __launch_bounds__(D) void attn_merge_kernel(const AttnParams p, int group)
 {
@@ -405,23 +226,23 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(const AttnParams p, int g
     const int seq = pairs ? p.pair_seq[b] : b;
     const int n_sel = pairs ? 1 : p.n_sel;
     const int L = p.seq_lens[seq];
-    const int n_chunks = (L + p.chunk_tokens - 1) / p.chunk_tokens;
-    if (p.direct_single && n_chunks <= 1) return;      // already written by the partial pass
+    const int n_segs = (L + p.seg_tokens - 1) / p.seg_tokens;
+    if (p.direct_single && n_segs <= 1) return;        // already written by the chunk kernel
     const int h = (pairs ? p.pair_head[b] : p.head_ids[j / group]) * group + j % group;
     __half *o = p.out + ((int64_t)seq * p.n_q_heads + h) * D;
-    if (n_chunks <= 0) {
+    if (n_segs <= 0) {
         o[d] = __float2half_rn(0.f);
         return;
     }
-    // partial of chunk c of this row: index ((b*n_sel + i)*max_chunks + c)*group + rr
-    const int64_t base = ((int64_t)b * n_sel + j / group) * p.max_chunks * group + j % group;
+    // partial of segment c of this row: index ((b*n_sel + i)*max_segs + c)*group + rr
+    const int64_t base = ((int64_t)b * n_sel + j / group) * p.max_segs * group + j % group;
     const float *lse = p.lse_partial + base;
     const float *op = p.o_partial + base * D + d;
     float M = lse[0];
-    for (int c = 1; c < n_chunks; ++c) M = fmaxf(M, lse[(int64_t)c * group]);
+    for (int c = 1; c < n_segs; ++c) M = fmaxf(M, lse[(int64_t)c * group]);
     float W = 0.f, acc = 0.f;
 #pragma unroll 4
-    for (int c = 0; c < n_chunks; ++c) {
+    for (int c = 0; c < n_segs; ++c) {
         const float w = fast_exp2((lse[(int64_t)c * group] - M) * kLog2e);
         W += w;
         acc = fmaf(w, op[(int64_t)c * group * D], acc);

@@ -15,26 +15,43 @@
 
 namespace hetis {
 
-// Tokens per chunk of hetis_attn_decode.  Compile-time constants chosen by the query-group
-// size only: the chunking of a sequence must depend on its length and the model shape alone,
-// or a head-subset call could not reproduce the all-heads call bit for bit.  Grouped-query
-// shapes write r rows of partials per chunk, so they take longer chunks.
+// Cut of the token axis in hetis_attn_decode.  Compile-time constants chosen by the query-group
+// size only: how a row is cut must depend on its length and the model shape alone, or a
+// head-subset call could not reproduce the all-heads call bit for bit.  A chunk is what one
+// wave processes at a time; a segment is what leaves a workgroup as one result (rows of up to
+// one segment never produce partial results in global memory).
 #ifndef HETIS_DECODE_CHUNK_TOKENS
 #define HETIS_DECODE_CHUNK_TOKENS 256
 #endif
 #ifndef HETIS_DECODE_CHUNK_TOKENS_GQA
-#define HETIS_DECODE_CHUNK_TOKENS_GQA 768
+#define HETIS_DECODE_CHUNK_TOKENS_GQA 256
+#endif
+#ifndef HETIS_DECODE_SEG_TOKENS
+#define HETIS_DECODE_SEG_TOKENS 4096
+#endif
+#ifndef HETIS_DECODE_SEG_TOKENS_GQA
+#define HETIS_DECODE_SEG_TOKENS_GQA 2048
 #endif
 constexpr int decode_chunk_tokens(int group)
 {
     return group >= 4 ? HETIS_DECODE_CHUNK_TOKENS_GQA : HETIS_DECODE_CHUNK_TOKENS;
 }
+constexpr int decode_seg_tokens(int group)
+{
+    return group >= 4 ? HETIS_DECODE_SEG_TOKENS_GQA : HETIS_DECODE_SEG_TOKENS;
+}
+static_assert(HETIS_DECODE_SEG_TOKENS % HETIS_DECODE_CHUNK_TOKENS == 0 &&
+              HETIS_DECODE_SEG_TOKENS_GQA % HETIS_DECODE_CHUNK_TOKENS_GQA == 0 &&
+              HETIS_DECODE_SEG_TOKENS / HETIS_DECODE_CHUNK_TOKENS <= kMaxSegChunks &&
+              HETIS_DECODE_SEG_TOKENS_GQA / HETIS_DECODE_CHUNK_TOKENS_GQA <= kMaxSegChunks,
+              "a segment is a whole number of chunks, at most kMaxSegChunks");
 #ifndef HETIS_STREAM_WAVES
 #define HETIS_STREAM_WAVES 4
 #endif
 constexpr int kVecWaves = HETIS_STREAM_WAVES;
 constexpr int kWgsPerCu = 1;    // persistent workgroups per compute unit
-// Largest batch whose length scan fits the persistent kernel's LDS table.
+// Rows (sequences, or pairs) per launch: what the persistent kernel's LDS tables hold.  Larger
+// batches run as several launches over slices of the rows.
 constexpr int kMaxPersistBatch = 2048;
 constexpr int kMaxPersistHeads = 1024;
 // A wave keeps the block ids of one chunk in one register (64 lanes).
@@ -57,7 +74,7 @@ static int check_shape(const hetis_attn_shape *s, int32_t n_sel, Checked *c)
     if (s->block_size != kBlockTokens) return HETIS_ERR_UNSUPPORTED;
     const int r = s->n_q_heads / s->n_kv_heads;
     if (r != 1 && r != 2 && r != 4 && r != 8) return HETIS_ERR_UNSUPPORTED;
-    if (s->batch > 65535) return HETIS_ERR_UNSUPPORTED;
+    if (s->batch > 65535 || s->n_kv_heads > kMaxPersistHeads) return HETIS_ERR_UNSUPPORTED;
     const int64_t tile = (int64_t)s->block_size * s->head_dim;
     c->group = r;
     c->stride_head = s->kv_stride_head ? s->kv_stride_head : tile;
@@ -159,48 +176,56 @@ static int launch_persistent(AttnParams p, int batch, hipStream_t st)
         return v > 0 ? v : kWgsPerCu;
     }();
     if (occ > env_wgs) occ = env_wgs;
-    const int64_t max_items = (int64_t)batch * p.max_chunks * p.n_sel;
     int64_t G = (int64_t)cus * occ;
-    const int64_t enough = (max_items + NW - 1) / NW;     // one item per streaming wave
-    if (G > enough) G = enough;
+    const int64_t most = (int64_t)batch * p.max_segs * p.n_sel;    // segments, at most
+    if (G > most) G = most;
     launch_timed(kernel, dim3((unsigned)G), dim3((NW + 1) * 64), lds, st, p, batch);
     return HETIS_OK;
 }
 
 // Kernel choice depends on the shape only (never on the head subset): vector arithmetic for
-// query groups of 1 or 2, MFMA for groups of 4 or 8; batches too large for the persistent
-// kernel's LDS tables take the simple one-workgroup-per-chunk-slot kernel.  `batch` is the
-// number of rows of the enumeration: sequences, or (sequence, head) pairs in pairs mode.
-static bool takes_simple_kernel(int rows, int n_kv_heads, int max_chunks)
-{
-    // judged by the shape (all KV heads), not by how many heads this call selects
-    const int64_t max_items = (int64_t)rows * max_chunks * n_kv_heads;
-    return rows > kMaxPersistBatch || n_kv_heads > kMaxPersistHeads || max_items >= (int64_t)1 << 31;
-}
-
+// query groups of 1 or 2, MFMA for groups of 4 or 8.  `rows` is the number of rows of the
+// enumeration: sequences, or (sequence, head) pairs in pairs mode.  More rows than one launch's
+// tables hold run as several launches over slices of the rows, one after the other on the
+// stream (they share the control words, which every launch leaves at zero); a row's arithmetic
+// is the same wherever it runs.
 template <int D, int R>
-static int launch_chunk(const AttnParams &p, int batch, int n_kv_heads, hipStream_t st)
+static int launch_chunk(const AttnParams &p0, int rows, hipStream_t st)
 {
-    const bool pairs = p.pair_seq != nullptr;
-    if (takes_simple_kernel(batch, pairs ? 1 : n_kv_heads, p.max_chunks)) {
-        if (batch > 65535 || p.n_sel > 65535) return HETIS_ERR_UNSUPPORTED;   // grid limits
-        dim3 grid(p.max_chunks, p.n_sel, batch);
-        launch_timed(attn_chunk_vec_kernel<D, R, kVecWaves>, grid, dim3(kVecWaves * 64), 0, st, p);
-        return HETIS_OK;
+    const bool pairs = p0.pair_seq != nullptr;
+    const int n_sel = pairs ? 1 : p0.n_sel;
+    for (int row0 = 0; row0 < rows; row0 += kMaxPersistBatch) {
+        const int n = std::min(kMaxPersistBatch, rows - row0);
+        AttnParams p = p0;
+        p.block_table += (int64_t)row0 * p.max_blocks_per_seq;
+        const int64_t part0 = (int64_t)row0 * n_sel * p.max_segs * R;
+        if (p.o_partial) p.o_partial += part0 * D;
+        if (p.lse_partial) p.lse_partial += part0;
+        if (p.arrivals) p.arrivals += (int64_t)row0 * n_sel;
+        if (pairs) {
+            p.pair_seq += row0;
+            p.pair_head += row0;
+        } else {
+            p.seq_lens += row0;
+            p.q += (int64_t)row0 * p.n_q_heads * D;
+            if (p.out) p.out += (int64_t)row0 * p.n_q_heads * D;
+        }
+        int rc;
+        if constexpr (R >= 4)
+            rc = pairs ? launch_persistent<MfmaPolicy<D, R>, true>(p, n, st)
+                       : launch_persistent<MfmaPolicy<D, R>, false>(p, n, st);
+        else
+            rc = pairs ? launch_persistent<VecPolicy<D, R>, true>(p, n, st)
+                       : launch_persistent<VecPolicy<D, R>, false>(p, n, st);
+        if (rc != HETIS_OK) return rc;
     }
-    if constexpr (R >= 4)
-        return pairs ? launch_persistent<MfmaPolicy<D, R>, true>(p, batch, st)
-                     : launch_persistent<MfmaPolicy<D, R>, false>(p, batch, st);
-    else
-        return pairs ? launch_persistent<VecPolicy<D, R>, true>(p, batch, st)
-                     : launch_persistent<VecPolicy<D, R>, false>(p, batch, st);
+    return HETIS_OK;
 }
 
-static int launch_chunks(const AttnParams &p, int D, int r, int batch, int n_kv_heads,
-                         hipStream_t st)
+static int launch_chunks(const AttnParams &p, int D, int r, int rows, hipStream_t st)
 {
 #define HETIS_CASE(DD, RR) \
-    if (D == DD && r == RR) return launch_chunk<DD, RR>(p, batch, n_kv_heads, st);
+    if (D == DD && r == RR) return launch_chunk<DD, RR>(p, rows, st);
     HETIS_CASE(128, 1) HETIS_CASE(128, 2) HETIS_CASE(128, 4) HETIS_CASE(128, 8)
     HETIS_CASE(64, 1) HETIS_CASE(64, 2) HETIS_CASE(64, 4) HETIS_CASE(64, 8)
 #undef HETIS_CASE
@@ -219,30 +244,49 @@ static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream
 
 // ---- workspaces.  Layout of a decode workspace (all offsets multiples of 256 bytes):
 //   [0, kControlBytes)   control words (tickets drawn, workgroups finished, error word)
-//   o_partial            fp32 [rows, n_sel, max_chunks, r, D]
-//   lse_partial          fp32 [rows, n_sel, max_chunks, r]
-// rows = sequences, or pairs in pairs mode (n_sel = 1 there).
+//   arrivals             uint32 [kArrivalSlots]: entry row * n_sel + head counts the segments of
+//                        that row whose partial result is stored.  The area has a fixed size so
+//                        that it sits at the same place whatever the shape: calls of different
+//                        shapes can then share one workspace, since no call's partial results
+//                        ever land on another call's counters, and every launch leaves the
+//                        counters it used at zero.
+//   o_partial            fp32 [rows, n_sel, max_segs, r, D]
+//   lse_partial          fp32 [rows, n_sel, max_segs, r]
+// rows = sequences, or pairs in pairs mode (n_sel = 1 there); max_segs = segments of the
+// longest row the block table allows.  A shape whose rows fit one segment needs the control
+// words only.
+constexpr size_t kArrivalSlots = (size_t)1 << 18;
+constexpr size_t kArrivalBytes = kArrivalSlots * sizeof(unsigned int);
 struct WsLayout {
-    size_t o_partial = 0, lse_partial = 0, total = kControlBytes;
+    size_t arrivals = 0, o_partial = 0, lse_partial = 0, total = kControlBytes;
+    size_t zeroed = kControlBytes;     // leading bytes this shape needs to be zero between launches
+    bool fused = false;                // partial results are merged inside the launch
 };
 constexpr size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static WsLayout decode_ws_layout(int64_t rows, int n_sel, int group, int D, int max_chunks)
+static WsLayout decode_ws_layout(int64_t rows, int n_sel, int group, int D, int max_segs)
 {
     WsLayout w;
-    if (max_chunks <= 1 || rows <= 0) return w;      // every sequence is written directly
-    const size_t partial_rows = (size_t)rows * n_sel * group * max_chunks;
-    w.o_partial = kControlBytes;
+    if (max_segs <= 1 || rows <= 0) return w;        // every row is written directly
+    const size_t partial_rows = (size_t)rows * n_sel * group * max_segs;
+    w.arrivals = kControlBytes;
+    w.o_partial = kControlBytes + kArrivalBytes;
+    // more rows than counters: the partial results are merged by a separate launch
+#ifndef HETIS_FUSED_MERGE
+#define HETIS_FUSED_MERGE 1
+#endif
+    w.fused = HETIS_FUSED_MERGE && (size_t)rows * n_sel <= kArrivalSlots;
+    if (w.fused) w.zeroed = align256(w.arrivals + (size_t)rows * n_sel * sizeof(unsigned int));
     w.lse_partial = align256(w.o_partial + partial_rows * D * sizeof(float));
     w.total = align256(w.lse_partial + partial_rows * sizeof(float));
     return w;
 }
 
-static int decode_max_chunks(const hetis_attn_shape *s, int group)
+static int decode_max_segs(const hetis_attn_shape *s, int group)
 {
-    const int chunk = decode_chunk_tokens(group);
+    const int seg = decode_seg_tokens(group);
     const int64_t max_tokens = (int64_t)s->max_blocks_per_seq * kBlockTokens;
-    return (int)((max_tokens + chunk - 1) / chunk);
+    return (int)((max_tokens + seg - 1) / seg);
 }
 
 static int check_workspace(const void *ws, size_t have, size_t need)
@@ -416,9 +460,9 @@ static int decode_common(const hetis_attn_shape *shape, const void *q, const voi
         return HETIS_ERR_NULL;
     int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
-    const int max_chunks = decode_max_chunks(shape, c.group);
+    const int max_segs = decode_max_segs(shape, c.group);
     const WsLayout lay = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
-                                          max_chunks);
+                                          max_segs);
     hipStream_t st = (hipStream_t)stream;
     if (owned)
         rc = owned_workspace(lay.total, st, true, &workspace);
@@ -429,17 +473,21 @@ static int decode_common(const hetis_attn_shape *shape, const void *q, const voi
     AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
                                n_sel_heads, scale, out);
     p.chunk_tokens = decode_chunk_tokens(c.group);
-    p.max_chunks = max_chunks;
+    p.seg_tokens = decode_seg_tokens(c.group);
+    p.max_segs = max_segs;
     p.direct_single = 1;
     unsigned char *base = static_cast<unsigned char *>(workspace);
     p.control = reinterpret_cast<unsigned int *>(base);
-    if (max_chunks > 1) {
+    if (max_segs > 1) {
         p.o_partial = reinterpret_cast<float *>(base + lay.o_partial);
         p.lse_partial = reinterpret_cast<float *>(base + lay.lse_partial);
+        // rows longer than a segment leave one partial result per segment; the wave that
+        // stores a row's last one merges them, so there is no merge launch
+        if (lay.fused) p.arrivals = reinterpret_cast<unsigned int *>(base + lay.arrivals);
     }
-    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, shape->n_kv_heads, st);
+    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, st);
     if (rc != HETIS_OK) return rc;
-    if (max_chunks > 1) launch_merge(p, shape->head_dim, c.group, shape->batch, st);
+    if (max_segs > 1 && !lay.fused) launch_merge(p, shape->head_dim, c.group, shape->batch, st);
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
 
@@ -474,16 +522,16 @@ int hetis_attn_decode_static(const hetis_attn_shape *shape, const void *q, const
     int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
     const WsLayout lay = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
-                                          decode_max_chunks(shape, c.group));
+                                          decode_max_segs(shape, c.group));
     if (lay.total > kStaticScratchBytes) return HETIS_ERR_WORKSPACE;   // before any HIP call
     void *ws = nullptr;
     rc = static_scratch(&ws);
     if (rc != HETIS_OK) return rc;
     // The array keeps what the last call left.  Partial results are always written before they
-    // are read; the control words must start at zero, and although every launch re-arms them,
-    // they are cleared here (with a kernel, so that the call can be captured) to make each
+    // are read; the control words and arrival counters must start at zero, and although every
+    // launch re-arms them, they are cleared here (with a kernel, so that the call can be captured) to make each
     // call independent of how an earlier one ended.
-    rc = zero_fill(ws, kControlBytes, (hipStream_t)stream);
+    rc = zero_fill(ws, lay.zeroed, (hipStream_t)stream);
     if (rc != HETIS_OK) return rc;
     return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
                          scale, out, ws, kStaticScratchBytes, false, stream);
@@ -497,7 +545,7 @@ int hetis_attn_decode_workspace_bytes(const hetis_attn_shape *shape, int32_t n_s
     const int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
     *bytes = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
-                              decode_max_chunks(shape, c.group)).total;
+                              decode_max_segs(shape, c.group)).total;
     return HETIS_OK;
 }
 
@@ -523,7 +571,7 @@ int hetis_attn_decode_pairs_workspace_bytes(const hetis_attn_shape *shape, int32
     const int rc = check_pairs(shape, n_pairs, &c);
     if (rc != HETIS_OK) return rc;
     *bytes = decode_ws_layout(n_pairs, 1, c.group, shape->head_dim,
-                              decode_max_chunks(shape, c.group)).total;
+                              decode_max_segs(shape, c.group)).total;
     return HETIS_OK;
 }
 
@@ -539,8 +587,8 @@ static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, con
         return HETIS_ERR_NULL;
     int rc = check_pairs(shape, n_pairs, &c);
     if (rc != HETIS_OK) return rc;
-    const int max_chunks = decode_max_chunks(shape, c.group);
-    const WsLayout lay = decode_ws_layout(n_pairs, 1, c.group, shape->head_dim, max_chunks);
+    const int max_segs = decode_max_segs(shape, c.group);
+    const WsLayout lay = decode_ws_layout(n_pairs, 1, c.group, shape->head_dim, max_segs);
     if (!owned) {
         rc = check_workspace(workspace, workspace_bytes, lay.total);
         if (rc != HETIS_OK) return rc;
@@ -557,17 +605,19 @@ static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, con
     p.pair_seq = pair_seq;
     p.pair_head = pair_head;
     p.chunk_tokens = decode_chunk_tokens(c.group);
-    p.max_chunks = max_chunks;
+    p.seg_tokens = decode_seg_tokens(c.group);
+    p.max_segs = max_segs;
     p.direct_single = 1;
     unsigned char *base = static_cast<unsigned char *>(workspace);
     p.control = reinterpret_cast<unsigned int *>(base);
-    if (max_chunks > 1) {
+    if (max_segs > 1) {
         p.o_partial = reinterpret_cast<float *>(base + lay.o_partial);
         p.lse_partial = reinterpret_cast<float *>(base + lay.lse_partial);
+        if (lay.fused) p.arrivals = reinterpret_cast<unsigned int *>(base + lay.arrivals);
     }
-    rc = launch_chunks(p, shape->head_dim, c.group, n_pairs, shape->n_kv_heads, st);
+    rc = launch_chunks(p, shape->head_dim, c.group, n_pairs, st);
     if (rc != HETIS_OK) return rc;
-    if (max_chunks > 1) launch_merge(p, shape->head_dim, c.group, n_pairs, st);
+    if (max_segs > 1 && !lay.fused) launch_merge(p, shape->head_dim, c.group, n_pairs, st);
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
 
@@ -700,13 +750,14 @@ static int decode_split_common(const hetis_attn_shape *shape, const void *q, con
     if (rc != HETIS_OK) return rc;
     AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
                                n_sel_heads, scale, nullptr);
-    p.chunk_tokens = chunk_tokens;
-    p.max_chunks = hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
+    p.chunk_tokens = chunk_tokens;      // every chunk is a segment of its own
+    p.seg_tokens = chunk_tokens;
+    p.max_segs = hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
     p.direct_single = 0;
     p.o_partial = o_partial;
     p.lse_partial = lse_partial;
     p.control = static_cast<unsigned int *>(control);
-    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, shape->n_kv_heads, st);
+    rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, st);
     if (rc != HETIS_OK) return rc;
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
@@ -750,7 +801,8 @@ int hetis_attn_merge(const hetis_attn_shape *shape, const float *o_partial,
     AttnParams p = make_params(shape, c, nullptr, nullptr, nullptr, nullptr, seq_lens, head_ids,
                                n_sel_heads, 0.f, out);
     p.chunk_tokens = chunk_tokens;
-    p.max_chunks = hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
+    p.seg_tokens = chunk_tokens;
+    p.max_segs = hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
     p.direct_single = 0;
     p.o_partial = const_cast<float *>(o_partial);
     p.lse_partial = const_cast<float *>(lse_partial);

@@ -150,22 +150,33 @@ WS = 0x10000    # a fake, 256-byte aligned workspace address
 
 
 def test_workspace_sizes(lib):
-    # c3's shape: 128 sequences x 13 heads x 16 chunks of 256 tokens x (128 + 1) floats, each
-    # area rounded up to 256 bytes, plus the control words
-    s = H.make_shape(128, 40, 40, 128, 256)
-    rows = 128 * 13 * 16
-    rc, n = H.hetis_attn_decode_workspace_bytes(s, 13)
-    assert rc == 0 and n == 256 + rows * 128 * 4 + rows * 4 and n % 256 == 0
-    # one chunk at most: only the control words
-    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 64, 16), 4) == (0, 256)
-    # grouped-query shapes use 768-token chunks
-    g = H.make_shape(256, 64, 8, 128, 256)
-    rows = 256 * 3 * 8 * 6
-    assert H.hetis_attn_decode_workspace_bytes(g, 3) == (0, 256 + rows * 128 * 4 + rows * 4)
-    assert H.hetis_attn_decode_pairs_workspace_bytes(s, 0) == (0, 256)
-    rows = 1721 * 16
     up = lambda x: (x + 255) // 256 * 256
-    assert H.hetis_attn_decode_pairs_workspace_bytes(s, 1721) == (0, 256 + rows * 128 * 4 + up(rows * 4))
+    # rows of up to one segment (4096 tokens; 2048 for query groups of 4 or 8) are combined
+    # inside a workgroup: a shape whose block table allows no more needs the control words only
+    s = H.make_shape(128, 40, 40, 128, 256)
+    assert H.hetis_attn_decode_workspace_bytes(s, 13) == (0, 256)
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 64, 16), 4) == (0, 256)
+    assert H.hetis_attn_decode_pairs_workspace_bytes(s, 1721) == (0, 256)
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 128), 3) == (0, 256)
+    # longer rows: control words, a fixed area of 2^18 arrival counters, then one partial result
+    # of (D + 1) floats per segment and query row; each area rounded up to 256 bytes.
+    # c4's shape: up to 32768 tokens = 8 segments
+    long = H.make_shape(8, 40, 40, 128, 2048)
+    rows = 8 * 40 * 8
+    fixed = 256 + 4 * (1 << 18)
+    assert H.hetis_attn_decode_workspace_bytes(long, 40) == (0, fixed + rows * 128 * 4 + up(rows * 4))
+    # the grouped-query shape with up to 4096 tokens: 2 segments of 2048, r = 8 rows each
+    rows = 256 * 3 * 2 * 8
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 256), 3) \
+        == (0, fixed + rows * 128 * 4 + up(rows * 4))
+    # one block more than a whole number of segments: one more segment
+    rows = 3 * 5 * 2 * 1
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(3, 8, 8, 64, 257), 5) \
+        == (0, fixed + rows * 64 * 4 + up(rows * 4))
+    assert H.hetis_attn_decode_pairs_workspace_bytes(long, 0) == (0, 256)
+    rows = 77 * 8
+    assert H.hetis_attn_decode_pairs_workspace_bytes(long, 77) \
+        == (0, fixed + rows * 128 * 4 + up(rows * 4))
     assert H.hetis_attn_decode_workspace_bytes(s, 0)[0] == binding.HETIS_ERR_BAD_HEADS
     assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 96, 16), 4)[0] == binding.HETIS_ERR_UNSUPPORTED
     assert H.hetis_attn_decode_pairs_workspace_bytes(s, -1)[0] == binding.HETIS_ERR_BAD_SHAPE
@@ -181,15 +192,15 @@ def test_static_scratch_entry_point_argument_errors(lib):
     assert call(n_sel=9) == binding.HETIS_ERR_BAD_HEADS
     assert call(shape=H.make_shape(4, 8, 8, 96, 16)) == binding.HETIS_ERR_UNSUPPORTED
     # a shape whose workspace exceeds the static array is refused before any HIP call
-    big = H.make_shape(2048, 40, 40, 128, 256)
+    big = H.make_shape(2048, 40, 40, 128, 2048)
     assert H.hetis_attn_decode_workspace_bytes(big, 40)[1] > binding.HETIS_ATTN_STATIC_SCRATCH_BYTES
     assert call(shape=big, n_sel=40) == binding.HETIS_ERR_WORKSPACE
 
 
 def test_ws_entry_points_argument_errors(lib):
-    s = good()
+    s = H.make_shape(4, 8, 8, 64, 600)                                  # up to 9600 tokens: 3 segments
     rc, need = H.hetis_attn_decode_workspace_bytes(s, 4)
-    assert rc == 0
+    assert rc == 0 and need > 256
 
     def call(ws=WS, nbytes=need, shape=s, n_sel=4, q=P):
         return H.hetis_attn_decode_ws(shape, q, P, P, P, P, P, n_sel, 0.125, P, ws, nbytes, 0)
@@ -202,6 +213,7 @@ def test_ws_entry_points_argument_errors(lib):
 
     def pairs(ws=WS, nbytes=1 << 20, n_pairs=5, ps=P):
         return H.hetis_attn_decode_pairs_ws(s, P, P, P, P, P, ps, P, n_pairs, 0.125, P, ws, nbytes, 0)
+    s = good()
     assert pairs(ws=None) == binding.HETIS_ERR_NULL
     assert pairs(ps=None) == binding.HETIS_ERR_NULL
     assert pairs(nbytes=128) == binding.HETIS_ERR_WORKSPACE

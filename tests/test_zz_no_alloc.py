@@ -39,8 +39,8 @@ def test_static_scratch_matches_decode_on_two_calls_in_a_row():
 
 
 def test_static_scratch_refuses_what_does_not_fit():
-    # 2048 sequences x 40 heads x 16 chunks of partial rows need far more than the static array
-    s = H.make_shape(2048, 40, 40, 128, 256)
+    # 2048 sequences x 40 heads x 8 segments of partial rows need far more than the static array
+    s = H.make_shape(2048, 40, 40, 128, 2048)
     rc, need = H.hetis_attn_decode_workspace_bytes(s, 40)
     assert rc == 0 and need > H.binding.HETIS_ATTN_STATIC_SCRATCH_BYTES
     P = 0x1000                                    # never touched: the call fails before any launch
