@@ -88,7 +88,7 @@ constexpr int kTicketBatch = 8;         // tickets per device atomic while segme
 // Chunks of multi-chunk segments a workgroup keeps waiting in its pool before it draws the
 // next segment.
 #ifndef HETIS_POOL_AHEAD
-#define HETIS_POOL_AHEAD 4
+#define HETIS_POOL_AHEAD 2
 #endif
 enum : int { kItemExists = 1 };
 
@@ -553,11 +553,13 @@ __global__ __launch_bounds__((NW + 1) * 64)
     };
     // Work a workgroup has without a ticket.  When segments have several chunks: segment number
     // blockIdx.x, whose first NW chunks the streaming waves take directly (wave v takes chunk
-    // v) and which owns fold slot 0.  When every segment is a single chunk: segments blockIdx.x
-    // + v * gridDim.x, one per streaming wave v.  Tickets number the segments after these.
+    // v) and which owns fold slot 0.  When every segment is a single chunk: segments
+    // (blockIdx.x + k gridDim.x) * NW + v, k = 0, 1, two per streaming wave v (the waves of a
+    // workgroup work on neighbouring heads of one chunk position).  Tickets number the segments
+    // after these.
     const bool single_mode = seg_tokens == chunk_tokens;
     const bool have_first = (int)blockIdx.x < total;
-    const long long n_fixed = (long long)gridDim.x * (single_mode ? NW : 1);
+    const long long n_fixed = (long long)gridDim.x * (single_mode ? 2 * NW : 1);
 
     if (wave == NW) {
         // ------------------------------------------------------------ writer wave
@@ -610,12 +612,9 @@ __global__ __launch_bounds__((NW + 1) * 64)
             const long long left = (long long)total - last_base;
             const int n_draw = last_ns > 1 ? 1
                                : (left > 8 * wave_round ? kTicketBatch : (left > 2 * wave_round ? 2 : 1));
-            // (multi-chunk segments) look-ahead in chunks: HETIS_POOL_AHEAD while plenty of
-            // segments are left, one when about a round of them is left, none at the very end
-            // (a segment is then drawn only when a wave is already waiting for a chunk)
-            const int ahead_multi = left > 4 * (long long)gridDim.x
-                                        ? HETIS_POOL_AHEAD
-                                        : (left > (long long)gridDim.x ? min(HETIS_POOL_AHEAD, 1) : 0);
+            // (multi-chunk segments) look-ahead in chunks: HETIS_POOL_AHEAD, one when less than
+            // a quarter of a round of segments is left
+            const int ahead_multi = left > (long long)gridDim.x / 4 ? HETIS_POOL_AHEAD : 1;
             const int ahead = last_ns > 1 ? ahead_multi : n_draw;
             if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
                 unsigned t = 0;
@@ -870,7 +869,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         ChunkDesc d{};
         bool direct = false;
         if (single_mode) {
-            const long long mine = (long long)blockIdx.x + (long long)wave * gridDim.x;
+            const long long mine = (long long)blockIdx.x * NW + wave;
             if (mine < total) {
                 d = chunk_of(decode((int)mine), 0, 0);
                 direct = true;
@@ -919,7 +918,18 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // out.
         int i = 0;
         for (; i + 4 * RING < lim; i += RING) steady_turn(i);
-        fill(take_chunk(), nxt);
+        if (single_mode && n == 0) {
+            // the wave's second segment is its own as well
+            const long long mine = (long long)(gridDim.x + blockIdx.x) * NW + wave;
+            if (mine < total) {
+                fill(chunk_of(decode((int)mine), 0, 0), nxt);
+            } else {
+                ChunkDesc none{};
+                fill(none, nxt);
+            }
+        } else {
+            fill(take_chunk(), nxt);
+        }
         Policy::q_prefetch(q_pre, q_rows(nxt), lane);   // next chunk's query rows
         for (; i + RING < lim; i += RING) steady_turn(i);
         // last turn of this chunk (the only place a ragged block can be): its refills are the

@@ -151,13 +151,13 @@ WS = 0x10000    # a fake, 256-byte aligned workspace address
 
 def test_workspace_sizes(lib):
     up = lambda x: (x + 255) // 256 * 256
-    # rows of up to one segment (4096 tokens; 2048 for query groups of 4 or 8) are combined
-    # inside a workgroup: a shape whose block table allows no more needs the control words only
+    # rows of up to one segment (4096 tokens) are combined inside a workgroup: a shape whose
+    # block table allows no more needs the control words only
     s = H.make_shape(128, 40, 40, 128, 256)
     assert H.hetis_attn_decode_workspace_bytes(s, 13) == (0, 256)
     assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 64, 16), 4) == (0, 256)
     assert H.hetis_attn_decode_pairs_workspace_bytes(s, 1721) == (0, 256)
-    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 128), 3) == (0, 256)
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 256), 3) == (0, 256)
     # longer rows: control words, a fixed area of 2^18 arrival counters, then one partial result
     # of (D + 1) floats per segment and query row; each area rounded up to 256 bytes.
     # c4's shape: up to 32768 tokens = 8 segments
@@ -165,9 +165,9 @@ def test_workspace_sizes(lib):
     rows = 8 * 40 * 8
     fixed = 256 + 4 * (1 << 18)
     assert H.hetis_attn_decode_workspace_bytes(long, 40) == (0, fixed + rows * 128 * 4 + up(rows * 4))
-    # the grouped-query shape with up to 4096 tokens: 2 segments of 2048, r = 8 rows each
+    # a grouped-query shape with up to 8192 tokens: 2 segments, r = 8 rows each
     rows = 256 * 3 * 2 * 8
-    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 256), 3) \
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 512), 3) \
         == (0, fixed + rows * 128 * 4 + up(rows * 4))
     # one block more than a whole number of segments: one more segment
     rows = 3 * 5 * 2 * 1
