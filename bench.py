@@ -31,12 +31,26 @@ PROFILE_DIR = os.path.join(ROOT, "profiles")
 
 
 def read_traffic(workload: str):
-    """HBM bytes per step from the committed counter summary, or None."""
-    path = os.path.join(PROFILE_DIR, f"pmc_traffic_{workload}.txt")
+    """HBM bytes per step from the committed counter summary, or None.  The counters cannot be
+    read from inside this process: the figure is the one a rocprofv3 --pmc run of this same
+    command produced (see traffic_source in the output)."""
+    path = traffic_file(workload)
     if not os.path.exists(path):
         return None
     m = re.search(r"^traffic_bytes_per_step\s*=\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
     return float(m.group(1)) if m else None
+
+
+def traffic_file(workload: str) -> str:
+    return os.path.join(PROFILE_DIR, f"pmc_traffic_{workload}.txt")
+
+
+def traffic_source(workload: str):
+    path = traffic_file(workload)
+    if not os.path.exists(path):
+        return None
+    return ("stored figure, not measured in this run: profiles/" + os.path.basename(path) +
+            " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)")
 
 
 def cpu_baseline(w_host, budget_s: float):
@@ -72,9 +86,12 @@ def cpu_baseline(w_host, budget_s: float):
 
 
 def timed_steps(step, set_events, stream, steps, warmup):
-    """W untimed steps, then K timed ones between synchronisations.  Returns (wall seconds,
-    device ms per step from one event pair, per-step kernel ms from the pairs that the library
-    attaches to the dispatch of its main kernel)."""
+    """W untimed steps, then K timed ones between synchronisations: that is the step time.  The
+    duration of the main kernel alone comes from a second pass of K steps whose dispatches carry
+    event pairs that the library attaches to them; those steps are not part of the step time,
+    because a dispatch that carries events costs a few microseconds more.  Returns (wall seconds
+    of the K timed steps, device ms per step from one event pair around them, per-step kernel ms
+    of the second pass)."""
     import numpy as np
     import torch
     for _ in range(warmup):
@@ -90,14 +107,17 @@ def timed_steps(step, set_events, stream, steps, warmup):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev_region[0].record(stream)
-    for kb, ke in ev_kernel:
-        set_events(kb.cuda_event, ke.cuda_event)
+    for _ in range(steps):
         step()
     ev_region[1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    set_events(None, None)
     dev_ms = ev_region[0].elapsed_time(ev_region[1]) / steps
+    for kb, ke in ev_kernel:
+        set_events(kb.cuda_event, ke.cuda_event)
+        step()
+    torch.cuda.synchronize()
+    set_events(None, None)
     return wall, dev_ms, np.array([a.elapsed_time(b) for a, b in ev_kernel])
 
 
@@ -151,6 +171,7 @@ def bench_pairs(args):
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic(f"decode_pairs_{spec.name}"),
+                     "traffic_source": traffic_source(f"decode_pairs_{spec.name}"),
                      "algorithmic_bytes": kv_bytes},
     }
     if not args.no_cpu_baseline:
@@ -247,6 +268,7 @@ def bench_kv(args):
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic(f"{args.op}_{spec.name}"),
+                     "traffic_source": traffic_source(f"{args.op}_{spec.name}"),
                      "algorithmic_bytes": traffic_alg},
     }
     if not args.no_cpu_baseline:
@@ -322,6 +344,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     H.binding.load()                       # the HIP library must be built; no fallback exists
+    # everything runs on one stream of its own (not the null stream)
+    torch.cuda.set_stream(torch.cuda.Stream())
     if args.op == "decode_pairs":
         return bench_pairs(args)
     if args.op != "decode":
@@ -345,10 +369,15 @@ def main():
         o_p = torch.empty((spec.batch, n_sel, C, r, spec.head_dim), dtype=torch.float32, device=dev)
         lse_p = torch.empty((spec.batch, n_sel, C, r), dtype=torch.float32, device=dev)
 
+        merge_events = []
+
         def step():
             H.check(H.hetis_attn_decode_split(shape, w.q, w.k_cache, w.v_cache, bt, sl, hid, n_sel,
                                               spec.scale, spec.chunk_tokens, spec.max_seq_len,
                                               o_p, lse_p, stream), "decode_split")
+            if merge_events:                # second pass only: time the merge kernel as well
+                H.hetis_attn_profile_events(merge_events[-1][0].cuda_event,
+                                            merge_events[-1][1].cuda_event)
             H.check(H.hetis_attn_merge(shape, o_p, lse_p, sl, hid, n_sel, spec.chunk_tokens,
                                        spec.max_seq_len, out, stream), "merge")
         path = f"hetis_attn_decode_split(chunk={spec.chunk_tokens}) + hetis_attn_merge"
@@ -361,9 +390,17 @@ def main():
     # Events: one pair brackets the whole timed region on the launch stream; one pair per
     # step is handed to the library, which attaches it to the dispatch of the chunk kernel
     # (the kernel that streams the KV cache) inside the call.
-    wall, dev_ms_per_step, kern_ms = timed_steps(step, H.hetis_attn_profile_events, stream,
-                                                 args.steps, args.warmup)
+    def set_events(b, e):
+        if spec.chunk_tokens and b is not None:
+            pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            for ev in pair:
+                ev.record(stream)
+            merge_events.append(pair)
+        return H.hetis_attn_profile_events(b, e)
+
+    wall, dev_ms_per_step, kern_ms = timed_steps(step, set_events, stream, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
+    merge_ms = np.array([a.elapsed_time(b) for a, b in merge_events]) if spec.chunk_tokens else None
 
     if args.calibrate_copy:
         # a plain elementwise kernel of known traffic (1 GiB read, 1 GiB written) for scaling
@@ -375,7 +412,11 @@ def main():
         torch.cuda.synchronize()
 
     kv_bytes = w.kv_bytes()
+    # every kernel of a step counts: the decode entry point is one kernel; the split-KV form
+    # adds its merge kernel
     avg_kernel_s = float(kern_ms.mean()) * 1e-3
+    if merge_ms is not None:
+        avg_kernel_s += float(merge_ms.mean()) * 1e-3
     achieved = kv_bytes / avg_kernel_s / 1e9
     rec = {
         "metric": "decode-attention tokens/s (KV-read HBM GB/s in roofline), 1 GPU",
@@ -395,11 +436,20 @@ def main():
         "chunk_kernel_us": {"mean": float(kern_ms.mean() * 1e3),
                             "median": float(np.median(kern_ms) * 1e3),
                             "min": float(kern_ms.min() * 1e3)},
-        "roofline": {"bound": "hbm", "kernel": "attn_chunk_*_persistent_kernel",
+        "kernels_per_step": 1 if merge_ms is None else 2,
+        "roofline": {"bound": "hbm",
+                     "kernel": "attn_chunk_persistent_kernel" + ("" if merge_ms is None
+                                                                 else " + attn_merge_kernel"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(spec.name),
+                     "traffic_source": traffic_source(spec.name),
                      "algorithmic_bytes": kv_bytes},
     }
+    if merge_ms is not None:
+        rec["merge_kernel_us"] = {"mean": float(merge_ms.mean() * 1e3),
+                                  "median": float(np.median(merge_ms) * 1e3),
+                                  "min": float(merge_ms.min() * 1e3)}
+        rec["roofline"]["frac_chunk_kernel_only"] = kv_bytes / (float(kern_ms.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBPS
     if not args.no_cpu_baseline:
         w_host = W.Workload(spec, w.seq_lens, w.block_table, w.num_blocks, w.q.cpu(),
                             w.k_cache.cpu(), w.v_cache.cpu(), w.head_ids)

@@ -256,13 +256,15 @@ int hetis_attn_merge(const hetis_attn_shape *shape, const float *o_partial,
 
 /*
  * Measurement hook.  After hetis_attn_profile_events(begin, end) with two hipEvent_t
- * (passed as void*, created by the caller with timing enabled), every later
- * hetis_attn_decode / hetis_attn_decode_pairs / hetis_attn_decode_split call made by
- * the SAME host thread attaches the pair to the dispatch of its chunk kernel (the
- * kernel that streams the KV cache; the merge launch is outside the pair): `begin`
- * is stamped when that kernel begins to execute, `end` when it has finished, so
- * their difference is the kernel's duration as a profiler's kernel trace sees it.  Pass (NULL, NULL) to switch the hook off.  The state is
- * per host thread.  Returns HETIS_OK, or HETIS_ERR_NULL if exactly one is NULL.
+ * (passed as void*, created by the caller with timing enabled), the next kernel that an
+ * Attention entry point of this header dispatches on behalf of the SAME host thread (the
+ * kernel that streams the KV cache in the decode calls, the merge kernel in hetis_attn_merge)
+ * carries the pair: `begin` is stamped when that kernel begins to execute, `end` when it has
+ * finished, so their difference is the kernel's duration as a profiler's kernel trace sees it.
+ * The pair is used once; set it again before the next call.  A dispatch that carries events
+ * costs a few microseconds more than a plain one, so time whole steps without the hook.  Pass
+ * (NULL, NULL) to drop a pair that has not been used.  The state is per host thread.  Returns
+ * HETIS_OK, or HETIS_ERR_NULL if exactly one is NULL.
  */
 int hetis_attn_profile_events(void *begin, void *end);
 

@@ -149,11 +149,14 @@ template <class Kernel, class... Args>
 static void launch_timed(Kernel kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st,
                          Args... args)
 {
-    if (t_prof_begin)
-        hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)lds, st, t_prof_begin,
-                              t_prof_end, 0, args...);
-    else
+    if (t_prof_begin) {
+        // one shot: the pair goes with the first dispatch after it was set
+        hipEvent_t begin = t_prof_begin, end = t_prof_end;
+        t_prof_begin = t_prof_end = nullptr;
+        hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)lds, st, begin, end, 0, args...);
+    } else {
         kernel<<<grid, block, lds, st>>>(args...);
+    }
 }
 
 template <class Policy, bool PAIRS>
@@ -237,9 +240,9 @@ static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream
 {
     dim3 grid(p.n_sel * r, batch);
     if (D == 128)
-        attn_merge_kernel<128><<<grid, 128, 0, st>>>(p, r);
+        launch_timed(attn_merge_kernel<128>, grid, dim3(128), 0, st, p, r);
     else
-        attn_merge_kernel<64><<<grid, 64, 0, st>>>(p, r);
+        launch_timed(attn_merge_kernel<64>, grid, dim3(64), 0, st, p, r);
 }
 
 // ---- workspaces.  Layout of a decode workspace (all offsets multiples of 256 bytes):
