@@ -325,7 +325,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3_13b_subset")
-    ap.add_argument("--op", default="decode", choices=["decode", "decode_pairs", "kv_append", "kv_store", "kv_copy"])
+    ap.add_argument("--op", default="decode", choices=["decode", "decode_step", "decode_pairs", "kv_append", "kv_store", "kv_copy"])
     ap.add_argument("--cpu-seconds", type=float, default=1.5,
                     help="wall-clock budget of the CPU checker sample (x cores = CPU work)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -348,7 +348,7 @@ def main():
     torch.cuda.set_stream(torch.cuda.Stream())
     if args.op == "decode_pairs":
         return bench_pairs(args)
-    if args.op != "decode":
+    if args.op not in ("decode", "decode_step"):
         return bench_kv(args)
     spec = W.SPECS[args.workload]
     dev = torch.device("cuda:0")
@@ -363,7 +363,7 @@ def main():
     out = torch.zeros_like(w.q)
     stream = torch.cuda.current_stream()
 
-    if spec.chunk_tokens:
+    if spec.chunk_tokens and args.op == "decode":
         C = H.hetis_attn_split_num_chunks(spec.max_seq_len, spec.chunk_tokens)
         r = spec.group_size
         o_p = torch.empty((spec.batch, n_sel, C, r, spec.head_dim), dtype=torch.float32, device=dev)
@@ -381,6 +381,14 @@ def main():
             H.check(H.hetis_attn_merge(shape, o_p, lse_p, sl, hid, n_sel, spec.chunk_tokens,
                                        spec.max_seq_len, out, stream), "merge")
         path = f"hetis_attn_decode_split(chunk={spec.chunk_tokens}) + hetis_attn_merge"
+    elif args.op == "decode_step":
+        # the whole decode step of the layer: store of the new token's rows + Attention, one call
+        kn, vn = W.new_token_rows(w)
+
+        def step():
+            H.check(H.hetis_attn_decode_step(shape, w.q, kn, vn, w.k_cache, w.v_cache, bt, sl, hid,
+                                             n_sel, spec.scale, out, stream), "decode_step")
+        path = "hetis_attn_decode_step"
     else:
         def step():
             H.check(H.hetis_attn_decode(shape, w.q, w.k_cache, w.v_cache, bt, sl, hid, n_sel,
@@ -390,8 +398,10 @@ def main():
     # Events: one pair brackets the whole timed region on the launch stream; one pair per
     # step is handed to the library, which attaches it to the dispatch of the chunk kernel
     # (the kernel that streams the KV cache) inside the call.
+    split = bool(spec.chunk_tokens) and args.op == "decode"
+
     def set_events(b, e):
-        if spec.chunk_tokens and b is not None:
+        if split and b is not None:
             pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             for ev in pair:
                 ev.record(stream)
@@ -400,7 +410,7 @@ def main():
 
     wall, dev_ms_per_step, kern_ms = timed_steps(step, set_events, stream, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
-    merge_ms = np.array([a.elapsed_time(b) for a, b in merge_events]) if spec.chunk_tokens else None
+    merge_ms = np.array([a.elapsed_time(b) for a, b in merge_events]) if split else None
 
     if args.calibrate_copy:
         # a plain elementwise kernel of known traffic (1 GiB read, 1 GiB written) for scaling
@@ -430,7 +440,7 @@ def main():
                    "n_kv_heads": spec.n_kv_heads, "head_dim": spec.head_dim,
                    "selected_kv_heads": [int(x) for x in w.head_ids],
                    "total_cached_tokens": w.total_tokens, "block_size": spec.block_size,
-                   "seed": spec.seed, "entry_point": path},
+                   "seed": spec.seed, "op": args.op, "entry_point": path},
         "kv_gbps_step": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "device_us_per_step": dev_ms_per_step * 1e3,
         "chunk_kernel_us": {"mean": float(kern_ms.mean() * 1e3),

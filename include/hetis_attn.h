@@ -153,6 +153,31 @@ int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const voi
                          void *stream);
 
 /*
+ * One decode step of this device's head share in one call (Section 5.1: the new token's key
+ * and value are stored, then its query attends to all stored keys and values, its own
+ * included): hetis_kv_append (hetis_kv.h) followed by hetis_attn_decode, in a single kernel.
+ *   k_new, v_new  fp16 [B, Hkv, D]: the new token's rows, indexed by the model's KV head; the
+ *                 rows of the heads in head_ids are written to position seq_lens[b] - 1 of
+ *                 sequence b through the block table (seq_lens already counts the new token;
+ *                 length 0 stores nothing); rows of other heads are not read
+ *   k_cache, v_cache  read and written
+ * The cache ends up as hetis_kv_append leaves it and `out` as hetis_attn_decode computes it on
+ * that cache, bit for bit; unlike hetis_kv_append this call does not range-check what it reads
+ * from device memory (use hetis_attn_validate).  Workspace rules as for hetis_attn_decode /
+ * hetis_attn_decode_ws (same size).  Errors: those of hetis_attn_decode.
+ */
+int hetis_attn_decode_step(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                           const void *v_new, void *k_cache, void *v_cache,
+                           const int32_t *block_table, const int32_t *seq_lens,
+                           const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
+                           void *stream);
+int hetis_attn_decode_step_ws(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                              const void *v_new, void *k_cache, void *v_cache,
+                              const int32_t *block_table, const int32_t *seq_lens,
+                              const int32_t *head_ids, int32_t n_sel_heads, float scale,
+                              void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * hetis_attn_decode for callers that cannot allocate device memory and have no workspace to
  * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, same kernels and bit-identical results; the workspace is a static device

@@ -87,6 +87,11 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_reserve_workspace.argtypes = [C.c_size_t]
     lib.hetis_attn_decode_ws.restype = C.c_int
     lib.hetis_attn_decode_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, C.c_size_t, vp]
+    lib.hetis_attn_decode_step.restype = C.c_int
+    lib.hetis_attn_decode_step.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
+    lib.hetis_attn_decode_step_ws.restype = C.c_int
+    lib.hetis_attn_decode_step_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp,
+                                              C.c_size_t, vp]
     lib.hetis_attn_decode_static.restype = C.c_int
     lib.hetis_attn_decode_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
     lib.hetis_attn_decode_workspace_bytes.restype = C.c_int
@@ -193,6 +198,24 @@ def hetis_attn_decode_ws(shape, q, k_cache, v_cache, block_table, seq_lens, head
                                        _ptr(block_table), _ptr(seq_lens), _ptr(head_ids),
                                        int(n_sel_heads), float(scale), _ptr(out), _ptr(workspace),
                                        int(workspace_bytes), _stream(stream))
+
+
+def hetis_attn_decode_step(shape, q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, head_ids,
+                           n_sel_heads, scale, out, stream=None) -> int:
+    return load().hetis_attn_decode_step(C.byref(shape), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                         _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                         _ptr(seq_lens), _ptr(head_ids), int(n_sel_heads),
+                                         float(scale), _ptr(out), _stream(stream))
+
+
+def hetis_attn_decode_step_ws(shape, q, k_new, v_new, k_cache, v_cache, block_table, seq_lens,
+                              head_ids, n_sel_heads, scale, out, workspace, workspace_bytes,
+                              stream=None) -> int:
+    return load().hetis_attn_decode_step_ws(C.byref(shape), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                            _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                            _ptr(seq_lens), _ptr(head_ids), int(n_sel_heads),
+                                            float(scale), _ptr(out), _ptr(workspace),
+                                            int(workspace_bytes), _stream(stream))
 
 
 def hetis_attn_decode_static(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids,

@@ -24,6 +24,11 @@ struct AttnParams {
     // is unused.  Both null: every sequence uses the common head_ids.
     const int32_t *pair_seq;    // [batch] or nullptr
     const int32_t *pair_head;   // [batch] or nullptr
+    // Decode step with the store folded in: the new token's K and V rows [B, Hkv, D] of the
+    // selected heads are written to position seq_lens[b] - 1 of the cache by the kernel itself
+    // before it reads that position.  Both null: the cache is only read.
+    const __half *k_new;
+    const __half *v_new;
     __half *out;                // [B, Hq, D]
     float *o_partial;           // [rows, n_sel, max_segs, r, D]
     float *lse_partial;         // [rows, n_sel, max_segs, r]

@@ -62,6 +62,12 @@
 // Dynamic LDS: int lens[rows], int firstF[rows + 1], uint16 order[rows], uint8 cls[rows], int
 // hids[n_sel] (pairs mode: hids[rows], pseq[rows]); NW x 2 mailboxes; fold slots; NW per-wave
 // staging areas of Policy::kWaveLdsBytes.
+// Decode step with the store folded in (AttnParams::k_new): the new token's K and V rows go
+// to position L - 1 of the cache inside this launch.  The writer wave stores the rows of a
+// (sequence, head) right before it puts the chunk that contains position L - 1 into the pool,
+// and waits for the stores to complete; the wave that takes the chunk runs on the same
+// compute unit and takes it with an acquire, so it reads the new rows.  That chunk is never
+// one of those taken without the pool.
 // Pairs mode (per-request head subsets, Section 4.2 / 5.2.1): the rows of the enumeration are
 // (sequence, KV head) pairs instead of sequences, each with its own block-table row over a
 // pool of single-head tiles; everything else, the arithmetic included, is shared.
@@ -305,6 +311,22 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_wave_barrier();
 }
 
+// The new token's K row and V row of (sequence, KV head g) -> slot pos % 16 of the tile
+// (block, g); lanes [0, D/8) move the K row, the next D/8 lanes the V row, 16 bytes each.
+template <int D>
+__device__ __forceinline__ void store_new_rows(const AttnParams &p, int seq, int g, int64_t tile_off,
+                                               int slot, int n_kv_heads, int lane)
+{
+    constexpr int LR = D / 8;
+    if (lane < 2 * LR) {
+        const bool is_v = lane >= LR;
+        const int c = lane % LR;
+        const __half *src = (is_v ? p.v_new : p.k_new) + ((int64_t)seq * n_kv_heads + g) * D + c * 8;
+        __half *dst = const_cast<__half *>(is_v ? p.v_cache : p.k_cache) + tile_off + slot * D + c * 8;
+        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+    }
+}
+
 template <class Policy, int NW, bool PAIRS>
 __global__ __launch_bounds__((NW + 1) * 64)
     __attribute__((amdgpu_waves_per_eu(Policy::kWavesPerEu))) void attn_chunk_persistent_kernel(
@@ -483,6 +505,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         int ct, ns;         // tokens per chunk, chunks
         int kind, dest;     // where the whole segment goes
         int nseg, out_row;  // segments of the row; first of its R rows in `out`
+        int tail;           // 1: the segment ends with the row's last token
     };
     // Tokens per chunk of a segment of n_tok tokens: the shorter the segment, the later it is
     // handed out and the finer it is cut, so that the chunks still running when the work runs
@@ -522,6 +545,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         const int n_segs = (L + seg_tokens - 1) / seg_tokens;
         s.nseg = n_segs;
         s.out_row = s.seq * p.n_q_heads + s.g * R;
+        s.tail = L > 0 && s.t0 + s.n_tok == L;
         if (L <= 0) {
             s.kind = kKindZero;
             s.dest = s.out_row;
@@ -559,6 +583,23 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // after these.
     const bool single_mode = seg_tokens == chunk_tokens;
     const bool have_first = (int)blockIdx.x < total;
+    const bool step_mode = p.k_new != nullptr;      // never together with single_mode
+    // chunks of the first segment that are taken without the pool: the first NW, but not the
+    // one that holds the row's last position when the new token is stored in this launch
+    auto direct_chunks = [&](const Segment &s0) {
+        int n = min(NW, s0.ns);
+        if (step_mode && s0.tail && n == s0.ns) --n;
+        return n;
+    };
+    // store of the new token's rows of the segment's (sequence, head), done before the chunk
+    // that reads them becomes visible to the streaming waves
+    auto store_tail = [&](const Segment &sg) {
+        const int L = sg.t0 + sg.n_tok;             // tail segment: the row's length
+        const int pos = L - 1;
+        const int blk = p.block_table[(int64_t)sg.b * p.max_blocks_per_seq + pos / kBlockTokens];
+        const int64_t off = (int64_t)blk * p.stride_block + (PAIRS ? 0 : (int64_t)sg.g * p.stride_head);
+        store_new_rows<D>(p, sg.seq, sg.g, off, pos % kBlockTokens, p.n_q_heads / R, lane);
+    };
     const long long n_fixed = (long long)gridDim.x * (single_mode ? 2 * NW : 1);
 
     if (wave == NW) {
@@ -596,6 +637,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             r.dest = __builtin_amdgcn_readlane(s.dest, k);
             r.nseg = __builtin_amdgcn_readlane(s.nseg, k);
             r.out_row = __builtin_amdgcn_readlane(s.out_row, k);
+            r.tail = __builtin_amdgcn_readlane(s.tail, k);
             return r;
         };
         while (done_mask != (1 << NW) - 1 && idle < kSpinLimit) {
@@ -636,6 +678,14 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 if (single && !first) {
                     const int cnt = pend_n - pend_i;
                     if (pool_end + cnt - taken <= kPoolSize) {
+                        if (step_mode) {
+                            for (int e = pend_i; e < pend_n; ++e) {
+                                const Segment sg = bcast(mine, e);
+                                if (sg.tail) store_tail(sg);
+                            }
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                            __builtin_amdgcn_s_waitcnt(0);
+                        }
                         if (lane >= pend_i && lane < pend_n)
                             pool.desc[(pool_end + lane - pend_i) % kPoolSize] = chunk_of(mine, 0, 0);
                         pool_end += cnt;
@@ -662,8 +712,13 @@ __global__ __launch_bounds__((NW + 1) * 64)
                                 fold[slot].out_row = seg.out_row;
                             }
                         }
-                        // the first NW chunks of the first segment are taken without the pool
-                        const int skip = first ? min(NW, seg.ns) : 0;
+                        if (step_mode && seg.tail) {
+                            store_tail(seg);
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                            __builtin_amdgcn_s_waitcnt(0);
+                        }
+                        // some chunks of the first segment are taken without the pool
+                        const int skip = first ? direct_chunks(seg) : 0;
                         if (lane >= skip && lane < seg.ns)
                             pool.desc[(pool_end + lane - skip) % kPoolSize] = chunk_of(seg, lane, slot);
                         pool_end += seg.ns - skip;
@@ -876,7 +931,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             }
         } else if (have_first) {
             const Segment s0 = decode(blockIdx.x);
-            if (wave < s0.ns) {
+            if (wave < direct_chunks(s0)) {
                 d = chunk_of(s0, wave, 0);
                 direct = true;
             }

@@ -45,6 +45,9 @@ static_assert(HETIS_DECODE_SEG_TOKENS % HETIS_DECODE_CHUNK_TOKENS == 0 &&
               HETIS_DECODE_SEG_TOKENS / HETIS_DECODE_CHUNK_TOKENS <= kMaxSegChunks &&
               HETIS_DECODE_SEG_TOKENS_GQA / HETIS_DECODE_CHUNK_TOKENS_GQA <= kMaxSegChunks,
               "a segment is a whole number of chunks, at most kMaxSegChunks");
+static_assert(HETIS_DECODE_SEG_TOKENS > HETIS_DECODE_CHUNK_TOKENS &&
+              HETIS_DECODE_SEG_TOKENS_GQA > HETIS_DECODE_CHUNK_TOKENS_GQA,
+              "the decode path folds chunks inside a workgroup (the folded-in store relies on it)");
 #ifndef HETIS_STREAM_WAVES
 #define HETIS_STREAM_WAVES 4
 #endif
@@ -453,14 +456,16 @@ const char *hetis_attn_status_string(int status)
 
 // Shared body of hetis_attn_decode / hetis_attn_decode_ws.  `workspace` == nullptr: take the
 // library-owned one.
-static int decode_common(const hetis_attn_shape *shape, const void *q, const void *k_cache,
-                         const void *v_cache, const int32_t *block_table, const int32_t *seq_lens,
+static int decode_common(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                         const void *v_new, bool step, const void *k_cache, const void *v_cache,
+                         const int32_t *block_table, const int32_t *seq_lens,
                          const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
                          void *workspace, size_t workspace_bytes, bool owned, void *stream)
 {
     Checked c;
     if (!shape || !q || !k_cache || !v_cache || !block_table || !seq_lens || !head_ids || !out)
         return HETIS_ERR_NULL;
+    if (step && (!k_new || !v_new)) return HETIS_ERR_NULL;
     int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
     const int max_segs = decode_max_segs(shape, c.group);
@@ -479,6 +484,10 @@ static int decode_common(const hetis_attn_shape *shape, const void *q, const voi
     p.seg_tokens = decode_seg_tokens(c.group);
     p.max_segs = max_segs;
     p.direct_single = 1;
+    if (step) {
+        p.k_new = static_cast<const __half *>(k_new);
+        p.v_new = static_cast<const __half *>(v_new);
+    }
     unsigned char *base = static_cast<unsigned char *>(workspace);
     p.control = reinterpret_cast<unsigned int *>(base);
     if (max_segs > 1) {
@@ -499,8 +508,8 @@ int hetis_attn_decode(const hetis_attn_shape *shape, const void *q, const void *
                       const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
                       void *stream)
 {
-    return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
-                         scale, out, nullptr, 0, true, stream);
+    return decode_common(shape, q, nullptr, nullptr, false, k_cache, v_cache, block_table, seq_lens,
+                         head_ids, n_sel_heads, scale, out, nullptr, 0, true, stream);
 }
 
 int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const void *k_cache,
@@ -510,8 +519,30 @@ int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const voi
                          void *stream)
 {
     if (!workspace) return HETIS_ERR_NULL;
-    return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
-                         scale, out, workspace, workspace_bytes, false, stream);
+    return decode_common(shape, q, nullptr, nullptr, false, k_cache, v_cache, block_table, seq_lens,
+                         head_ids, n_sel_heads, scale, out, workspace, workspace_bytes, false, stream);
+}
+
+int hetis_attn_decode_step(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                           const void *v_new, void *k_cache, void *v_cache,
+                           const int32_t *block_table, const int32_t *seq_lens,
+                           const int32_t *head_ids, int32_t n_sel_heads, float scale, void *out,
+                           void *stream)
+{
+    return decode_common(shape, q, k_new, v_new, true, k_cache, v_cache, block_table, seq_lens,
+                         head_ids, n_sel_heads, scale, out, nullptr, 0, true, stream);
+}
+
+int hetis_attn_decode_step_ws(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                              const void *v_new, void *k_cache, void *v_cache,
+                              const int32_t *block_table, const int32_t *seq_lens,
+                              const int32_t *head_ids, int32_t n_sel_heads, float scale,
+                              void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return HETIS_ERR_NULL;
+    return decode_common(shape, q, k_new, v_new, true, k_cache, v_cache, block_table, seq_lens,
+                         head_ids, n_sel_heads, scale, out, workspace, workspace_bytes, false,
+                         stream);
 }
 
 int hetis_attn_decode_static(const hetis_attn_shape *shape, const void *q, const void *k_cache,
@@ -536,8 +567,8 @@ int hetis_attn_decode_static(const hetis_attn_shape *shape, const void *q, const
     // call independent of how an earlier one ended.
     rc = zero_fill(ws, lay.zeroed, (hipStream_t)stream);
     if (rc != HETIS_OK) return rc;
-    return decode_common(shape, q, k_cache, v_cache, block_table, seq_lens, head_ids, n_sel_heads,
-                         scale, out, ws, kStaticScratchBytes, false, stream);
+    return decode_common(shape, q, nullptr, nullptr, false, k_cache, v_cache, block_table, seq_lens,
+                         head_ids, n_sel_heads, scale, out, ws, kStaticScratchBytes, false, stream);
 }
 
 int hetis_attn_decode_workspace_bytes(const hetis_attn_shape *shape, int32_t n_sel_heads,

@@ -184,6 +184,22 @@ def test_workspace_sizes(lib):
     assert lib.hetis_attn_decode_workspace_bytes(C.byref(s), 13, None) == binding.HETIS_ERR_NULL
 
 
+def test_decode_step_argument_errors(lib):
+    s = good()
+
+    def call(kn=P, vn=P, q=P, n_sel=4, ws=None):
+        if ws is None:
+            return H.hetis_attn_decode_step(s, q, kn, vn, P, P, P, P, P, n_sel, 0.125, P, 0)
+        return H.hetis_attn_decode_step_ws(s, q, kn, vn, P, P, P, P, P, n_sel, 0.125, P, ws[0], ws[1], 0)
+    assert call(kn=None) == binding.HETIS_ERR_NULL
+    assert call(vn=None) == binding.HETIS_ERR_NULL
+    assert call(q=None) == binding.HETIS_ERR_NULL
+    assert call(n_sel=0) == binding.HETIS_ERR_BAD_HEADS
+    assert call(ws=(None, 256)) == binding.HETIS_ERR_NULL
+    assert call(ws=(WS, 128)) == binding.HETIS_ERR_WORKSPACE
+    assert call(kn=None, ws=(WS, 256)) == binding.HETIS_ERR_NULL
+
+
 def test_static_scratch_entry_point_argument_errors(lib):
     s = good()
     call = lambda shape=s, n_sel=4, q=P: H.hetis_attn_decode_static(shape, q, P, P, P, P, P, n_sel,
