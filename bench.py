@@ -41,8 +41,9 @@ def read_traffic(workload: str):
     return float(m.group(1)) if m else None
 
 
-def traffic_file(workload: str) -> str:
-    return os.path.join(PROFILE_DIR, f"pmc_traffic_{workload}.txt")
+def traffic_file(key: str) -> str:
+    """key = <op>_<workload>, e.g. decode_c3_13b_subset."""
+    return os.path.join(PROFILE_DIR, f"{key}.txt")
 
 
 def traffic_source(workload: str):
@@ -119,6 +120,17 @@ def timed_steps(step, set_events, stream, steps, warmup):
     torch.cuda.synchronize()
     set_events(None, None)
     return wall, dev_ms, np.array([a.elapsed_time(b) for a, b in ev_kernel])
+
+
+def calibrate_copy():
+    """A plain elementwise kernel of known traffic (1 GiB read, 1 GiB written) for scaling the
+    FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command."""
+    import torch
+    src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1, out=dst)
+    torch.cuda.synchronize()
 
 
 def bench_pairs(args):
@@ -347,9 +359,13 @@ def main():
     # everything runs on one stream of its own (not the null stream)
     torch.cuda.set_stream(torch.cuda.Stream())
     if args.op == "decode_pairs":
-        return bench_pairs(args)
+        bench_pairs(args)
+    elif args.op not in ("decode", "decode_step"):
+        bench_kv(args)
     if args.op not in ("decode", "decode_step"):
-        return bench_kv(args)
+        if args.calibrate_copy:
+            calibrate_copy()
+        return
     spec = W.SPECS[args.workload]
     dev = torch.device("cuda:0")
     w = W.make_workload(spec, device=dev)
@@ -413,13 +429,7 @@ def main():
     merge_ms = np.array([a.elapsed_time(b) for a, b in merge_events]) if split else None
 
     if args.calibrate_copy:
-        # a plain elementwise kernel of known traffic (1 GiB read, 1 GiB written) for scaling
-        # the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run
-        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1, out=dst)
-        torch.cuda.synchronize()
+        calibrate_copy()
 
     kv_bytes = w.kv_bytes()
     # every kernel of a step counts: the decode entry point is one kernel; the split-KV form
@@ -451,8 +461,8 @@ def main():
                      "kernel": "attn_chunk_persistent_kernel" + ("" if merge_ms is None
                                                                  else " + attn_merge_kernel"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(spec.name),
-                     "traffic_source": traffic_source(spec.name),
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(f"{args.op}_{spec.name}"),
+                     "traffic_source": traffic_source(f"{args.op}_{spec.name}"),
                      "algorithmic_bytes": kv_bytes},
     }
     if merge_ms is not None:

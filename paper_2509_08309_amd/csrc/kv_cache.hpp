@@ -30,8 +30,8 @@ struct KvRowParams {
 
 // One group of 2*D/8 lanes moves the K row and the V row of one (entry, head): lane c of the
 // first half moves bytes [16c, 16c+16) of the K row, the second half the V row.  blockIdx.y
-// strides over the selected heads, so the per-entry index loads are shared by the heads a
-// thread handles.
+// strides over the selected heads, so the per-entry index loads (the same words in all lanes
+// of the group: one access) are shared by the heads a thread handles.
 template <int D, bool FETCH>
 __global__ void __launch_bounds__(256) kv_rows_kernel(KvRowParams p)
 {
@@ -54,18 +54,34 @@ __global__ void __launch_bounds__(256) kv_rows_kernel(KvRowParams p)
     uint4 *rows = is_v ? p.rows_v : p.rows_k;
     const int64_t cache_row = blk * p.stride_block + (int64_t)slot * LR + c;
     const int64_t rows_row = n * p.n_kv_heads * LR + c;
-    for (int s = blockIdx.y; s < p.n_sel; s += gridDim.y) {
-        const int g = p.head_ids[s];
-        if (g < 0 || g >= p.n_kv_heads) continue;
-        uint4 *in_cache = cache + cache_row + (int64_t)g * p.stride_head;
-        uint4 *in_rows = rows + rows_row + (int64_t)g * LR;
-        // every byte is touched once: non-temporal both ways (+1 % on a prefill-sized store)
-        if (FETCH) {
-            const kv_u32x4 x = __builtin_nontemporal_load((const kv_u32x4 *)in_cache);
-            __builtin_nontemporal_store(x, (kv_u32x4 *)in_rows);
-        } else {
-            const kv_u32x4 x = __builtin_nontemporal_load((const kv_u32x4 *)in_rows);
-            __builtin_nontemporal_store(x, (kv_u32x4 *)in_cache);
+    // heads in batches of four: the four loads of a batch are in flight together before the
+    // first store (a thread that alternates one load and one store leaves the memory system
+    // with a single access per thread in flight)
+    constexpr int U = 4;
+    for (int s0 = blockIdx.y; s0 < p.n_sel; s0 += U * gridDim.y) {
+        int g[U];
+        bool ok[U];
+        kv_u32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + u * gridDim.y;
+            g[u] = s < p.n_sel ? p.head_ids[s] : -1;
+            ok[u] = g[u] >= 0 && g[u] < p.n_kv_heads;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!ok[u]) continue;
+            // every byte is touched once: non-temporal both ways
+            const uint4 *src = FETCH ? cache + cache_row + (int64_t)g[u] * p.stride_head
+                                     : rows + rows_row + (int64_t)g[u] * LR;
+            x[u] = __builtin_nontemporal_load((const kv_u32x4 *)src);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!ok[u]) continue;
+            uint4 *dst = FETCH ? rows + rows_row + (int64_t)g[u] * LR
+                               : cache + cache_row + (int64_t)g[u] * p.stride_head;
+            __builtin_nontemporal_store(x[u], (kv_u32x4 *)dst);
         }
     }
 }
