@@ -622,7 +622,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             pend_n = 1;
         }
         long long last_base = n_fixed;    // number of the last segment drawn here
-        int last_ns = single_mode ? 1 : 2;    // chunks of the last segment published
+        int last_tok = seg_tokens;        // tokens of the last segment seen
         const long long wave_round = (long long)gridDim.x * NW;
         auto bcast = [&](const Segment &s, int k) {
             Segment r;
@@ -645,19 +645,22 @@ __global__ __launch_bounds__((NW + 1) * 64)
             // ---- keep the chunk pool ahead of the streaming waves
             const int taken = __builtin_amdgcn_readfirstlane(
                 __hip_atomic_load(&pool.next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-            // Draw.  Segments of several chunks are drawn one at a time and late, when fewer
-            // than HETIS_POOL_AHEAD chunks are waiting (they are handed out longest first, and
-            // work parked in one workgroup's pool cannot be taken by another that has run
-            // dry).  Once the segments are single chunks, tickets are drawn in batches that
-            // shrink as the work runs out (a same-address device atomic costs about as much
-            // as a short chunk).
+            // Draw.  Work parked in one workgroup's pool cannot be taken by another that has run
+            // dry, so little is drawn at a time and late; but a same-address device atomic
+            // costs about as much as a short chunk, so short segments are drawn several at a
+            // time.  Every chunk its own segment (split-KV): batches that shrink as the work
+            // runs out.  Otherwise: about one full chunk's worth of tokens per draw, judged by
+            // the last segment seen (they come longest first), drawn when fewer than
+            // HETIS_POOL_AHEAD chunks (one, near the end) or than a draw's worth are waiting.
             const long long left = (long long)total - last_base;
-            const int n_draw = last_ns > 1 ? 1
-                               : (left > 8 * wave_round ? kTicketBatch : (left > 2 * wave_round ? 2 : 1));
-            // (multi-chunk segments) look-ahead in chunks: HETIS_POOL_AHEAD, one when less than
-            // a quarter of a round of segments is left
-            const int ahead_multi = left > (long long)gridDim.x / 4 ? HETIS_POOL_AHEAD : 1;
-            const int ahead = last_ns > 1 ? ahead_multi : n_draw;
+            int n_draw, ahead;
+            if (single_mode) {
+                n_draw = left > 8 * wave_round ? kTicketBatch : (left > 2 * wave_round ? 2 : 1);
+                ahead = n_draw;
+            } else {
+                n_draw = max(1, min(kTicketBatch, chunk_tokens / max(last_tok, 1)));
+                ahead = max(left > (long long)gridDim.x / 4 ? HETIS_POOL_AHEAD : 1, n_draw);
+            }
             if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
                 unsigned t = 0;
                 if (lane == 0)
@@ -691,8 +694,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
                         pool_end += cnt;
                         __hip_atomic_store(&pool.end, pool_end, __ATOMIC_RELEASE,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
+                        last_tok = __builtin_amdgcn_readlane(mine.n_tok, pend_n - 1);
                         pend_i = pend_n;
-                        last_ns = 1;
                         progressed = true;
                     }
                 } else {
@@ -726,7 +729,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
                         ++pend_i;
                         first = false;
-                        last_ns = seg.ns;
+                        last_tok = seg.n_tok;
                         progressed = true;
                     }
                 }
