@@ -40,14 +40,28 @@ struct AttnParams {
     int32_t chunk_tokens;       // tokens one wave processes at a time: multiple of 16, <= 1024
     int32_t seg_tokens;         // tokens whose result leaves a workgroup as one (partial) result:
                                 // a multiple of chunk_tokens, at most 32 chunks
-    int32_t max_segs;           // segments of the longest row the buffers provide for
+    int32_t max_segs;           // partial-result slots per row in the partial buffers
     int32_t direct_single;      // 1: a row of <= 1 segment is written to `out` by the chunk kernel
+    int32_t mode;               // kModeSegments / kModeSplit / kModeSpread
+    int32_t part_stride;        // kModeSpread: slots per segment (chunk c of segment j of a row
+                                // uses slot j * part_stride + c); otherwise 1
     unsigned int *control;      // device words of the call's workspace (see kCtl* below)
     unsigned int *arrivals;     // [rows * n_sel] segments of a row whose partial results are stored,
                                 // zero between launches; nullptr: partial results are left for a
                                 // separate merge (the split-KV entry points)
     float scale_log2;           // scale * log2(e): scores are kept in the base-2 domain
 };
+
+// How the work of a launch is cut for scheduling.  The arithmetic of a row is the same in
+// kModeSegments and kModeSpread.
+//   kModeSegments: a workgroup takes whole segments and folds their chunks in LDS.
+//   kModeSplit:    seg_tokens == chunk_tokens; every chunk leaves as a partial result in the
+//                  caller's buffers (natural-log log-sum-exp), merged by a separate launch.
+//   kModeSpread:   for launches with few rows: a wave takes single chunks wherever they are,
+//                  so the chunks of one segment run on many workgroups; chunk results go
+//                  through the partial buffers and the wave that stores a row's last one
+//                  folds them in the order and with the operations of kModeSegments.
+enum : int { kModeSegments = 0, kModeSplit = 1, kModeSpread = 2 };
 
 // Control words at the start of a call's workspace.  All are zero between launches: the last
 // workgroup to leave a launch sets the first two back; kCtlError is sticky (only the host

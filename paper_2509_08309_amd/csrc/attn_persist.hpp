@@ -98,6 +98,45 @@ constexpr int kTicketBatch = 8;         // tickets per device atomic while segme
 #endif
 enum : int { kItemExists = 1 };
 
+// Tokens per chunk of a segment of n_tok tokens: the shorter the segment, the later it is
+// handed out and the finer it is cut, so that the chunks still running when the work runs out
+// are short ones.  A function of the row's length and of constants only, like everything that
+// shapes the arithmetic.
+__device__ __forceinline__ int chunk_tokens_of(int n_tok, int chunk_tokens, int seg_tokens)
+{
+    int ct = chunk_tokens;
+    if (seg_tokens > chunk_tokens) {
+        if (n_tok <= seg_tokens / HETIS_FINE_CHUNK_BELOW) ct = chunk_tokens / 2;
+        if (n_tok <= seg_tokens / (4 * HETIS_FINE_CHUNK_BELOW)) ct = chunk_tokens / 4;
+        ct = max(ct, 2 * kBlockTokens);
+    }
+    return ct;
+}
+
+// One step of the running combination of chunk results (o_c normalised, lse_c base 2) into
+// (A, M, W): M' = max(M, lse_c), A' = A 2^(M-M') + o_c 2^(lse_c-M'), W' = W 2^(M-M') + 2^(lse_c-M').
+// Written once, with explicit fused multiply-adds, because two code paths (the fold in LDS and
+// the fold from the partial buffers) must produce the same bits.
+struct FoldCoef {
+    float Mn, so, sc;
+};
+__device__ __forceinline__ FoldCoef fold_coef(float Mo, float lc)
+{
+    FoldCoef f;
+    f.Mn = fmaxf(Mo, lc);
+    f.so = fast_exp2(Mo - f.Mn);
+    f.sc = fast_exp2(lc - f.Mn);
+    return f;
+}
+__device__ __forceinline__ float fold_weight(float Wo, const FoldCoef &f)
+{
+    return __builtin_fmaf(Wo, f.so, f.sc);
+}
+__device__ __forceinline__ float fold_elem(float y, float x, const FoldCoef &f)
+{
+    return __builtin_fmaf(y, f.so, x * f.sc);
+}
+
 // A chunk, decoded: what a streaming wave needs to start on it and to label its result.
 struct ChunkDesc {
     int b, g, seq;      // enumeration row (sequence, or pair), KV head, sequence of q / out rows
@@ -110,7 +149,7 @@ struct ChunkDesc {
     int cs;             // Fold: index of the chunk in its segment
     int nseg;           // segments of the chunk's row
     int out_row;        // first of the R rows of the chunk's (sequence, head) in `out`
-    int pad;
+    int len;            // tokens of the chunk's row
 };
 
 // Chunks waiting to be taken by the streaming waves of one workgroup, in order.
@@ -126,7 +165,7 @@ struct alignas(16) Mailbox {
     float o[R][D];      // normalised output rows
     float lse[R];       // base-2 log-sum-exp of each row: m + log2(sum_t 2^(s_t - m))
     int kind, dest, cs; // as in the chunk's descriptor
-    int nseg, out_row;
+    int nseg, out_row, len;
     int flag;           // kMailEmpty / kMailFull / kMailDone
 };
 
@@ -182,10 +221,12 @@ __device__ __forceinline__ void store_result(const float (&o)[R][D], const float
 // Partial result of a segment that is merged inside this launch (AttnParams::arrivals): by
 // whichever wave stores the row's last segment, possibly on another XCD, so the words are
 // stored device-coherently, one per lane and step.
+// `base2`: the log-sum-exp is stored as it is (chunk results of kModeSpread), otherwise as a
+// natural logarithm (segment results).
 template <int D, int R>
 __device__ __forceinline__ void store_partial_coherent(const float (&o)[R][D], const float *lse2,
                                                        const float *w, int64_t dest,
-                                                       const AttnParams &p, int lane)
+                                                       const AttnParams &p, int lane, bool base2)
 {
 #pragma unroll
     for (int idx = lane; idx < R * D; idx += 64) {
@@ -193,19 +234,21 @@ __device__ __forceinline__ void store_partial_coherent(const float (&o)[R][D], c
         if (w) v *= __builtin_amdgcn_rcpf(w[idx / D]);
         coherent_store(p.o_partial + dest * (R * D) + idx, v);
     }
-    if (lane < R) coherent_store(p.lse_partial + dest * R + lane, lse2[lane] * kLn2);
+    if (lane < R)
+        coherent_store(p.lse_partial + dest * R + lane, base2 ? lse2[lane] : lse2[lane] * kLn2);
 }
 
 // Log-sum-exp merge of the n_segs partial results of one row, ascending segment order, by one
 // wave: M = max_c lse_c, w_c = exp(lse_c - M), out = fp16(sum_c w_c o_c / sum_c w_c).  Lane l
 // owns dims l and l + 64 (D = 128) of each of the R query rows.  `first` is the index of
-// segment 0 of the row in the partial buffers.  The partial results may come from other
-// XCDs: they are read with device-coherent loads.
+// segment 0 of the row in the partial buffers, segment c sits `stride` * c slots further.  The
+// partial results may come from other XCDs: they are read with device-coherent loads.
 template <int D, int R>
 __device__ __forceinline__ void merge_partials(const AttnParams &p, int64_t first, int n_segs,
-                                               int64_t out_row, int lane)
+                                               int stride, int64_t out_row, int lane)
 {
     constexpr int V = D / 64;                        // words per lane and row: 1 or 2
+    const int64_t step = (int64_t)stride * R;        // rows of the buffers per segment
     const float *lse = p.lse_partial + first * R;    // [segment][r]
     const float *op = p.o_partial + first * (R * D) + lane;
     float M[R];
@@ -213,7 +256,7 @@ __device__ __forceinline__ void merge_partials(const AttnParams &p, int64_t firs
     for (int r = 0; r < R; ++r) M[r] = coherent_load(lse + r);
     for (int c = 1; c < n_segs; ++c) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) M[r] = fmaxf(M[r], coherent_load(lse + c * R + r));
+        for (int r = 0; r < R; ++r) M[r] = fmaxf(M[r], coherent_load(lse + c * step + r));
     }
     float W[R], acc[R][V];
 #pragma unroll
@@ -225,9 +268,9 @@ __device__ __forceinline__ void merge_partials(const AttnParams &p, int64_t firs
     for (int c = 0; c < n_segs; ++c) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const float w = fast_exp2((coherent_load(lse + c * R + r) - M[r]) * kLog2e);
+            const float w = fast_exp2((coherent_load(lse + c * step + r) - M[r]) * kLog2e);
             W[r] += w;
-            const float *src = op + ((int64_t)c * R + r) * D;
+            const float *src = op + (c * step + r) * D;
 #pragma unroll
             for (int v = 0; v < V; ++v) acc[r][v] = fmaf(w, coherent_load(src + v * 64), acc[r][v]);
         }
@@ -240,29 +283,170 @@ __device__ __forceinline__ void merge_partials(const AttnParams &p, int64_t firs
     }
 }
 
-// After the partial result of a segment has been stored: count it in; the wave that stores
-// the last segment of a row merges all of them into `out` and rearms the counter.
-// Ordering across waves and XCDs without cache-wide write-backs or invalidations (which were
-// measured to cost several times the merge launch they replace): the partial results are
-// written with device-coherent stores, this wave waits until its stores have completed, then
-// bumps the counter with a device-scope atomic; the merging wave reads the partial results
-// with device-coherent loads issued after its own atomic has returned.
+// kModeSpread: the ns chunk results of one segment lie in the partial buffers (chunk c in slot
+// slot0 + c, log-sum-exp base 2).  One wave combines them with the operations a workgroup
+// applies to the chunks of a segment in kModeSegments, in the same order: folded in ascending
+// order, then normalised.  `whole_row`: the segment is the whole row and the result goes to
+// `out`; otherwise it replaces the first chunk result in the buffers, as the partial result of
+// the segment (natural-log log-sum-exp) that merge_partials expects.  Lane l owns dims l, l + 64.
 template <int D, int R>
-__device__ __forceinline__ void arrive_and_merge(const AttnParams &p, int64_t dest, int n_segs,
-                                                 int64_t out_row, int lane)
+__device__ __forceinline__ void fold_segment_from_chunks(const AttnParams &p, int64_t slot0, int ns,
+                                                         bool whole_row, int64_t out_row, int lane)
 {
-    const int64_t row = dest / p.max_segs;           // (enumeration row, head) of the segment
-    unsigned old = 0;
+    constexpr int V = D / 64;
+    constexpr int U = 16 / R;                         // chunk results loaded together
+    float a[R][V], M[R], W[R];
+    for (int c0 = 0; c0 < ns; c0 += U) {
+        float x[U][R][V], lc[U][R];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t slot = slot0 + min(c0 + u, ns - 1);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                lc[u][r] = coherent_load(p.lse_partial + slot * R + r);
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    x[u][r][v] = coherent_load(p.o_partial + (slot * R + r) * D + v * 64 + lane);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (c0 + u >= ns) continue;
+                if (c0 + u == 0) {
+                    M[r] = lc[u][r];
+                    W[r] = 1.f;
+#pragma unroll
+                    for (int v = 0; v < V; ++v) a[r][v] = x[u][r][v];
+                } else {
+                    const FoldCoef f = fold_coef(M[r], lc[u][r]);
+                    W[r] = fold_weight(W[r], f);
+                    M[r] = f.Mn;
+#pragma unroll
+                    for (int v = 0; v < V; ++v) a[r][v] = fold_elem(a[r][v], x[u][r][v], f);
+                }
+            }
+        }
+    }
+    if (ns > 1) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float s = __builtin_amdgcn_rcpf(W[r]);
+            M[r] = M[r] + fast_log2(W[r]);
+#pragma unroll
+            for (int v = 0; v < V; ++v) a[r][v] *= s;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (whole_row) {
+            __half *dst = p.out + (out_row + r) * D + lane;
+#pragma unroll
+            for (int v = 0; v < V; ++v) dst[v * 64] = __float2half_rn(a[r][v]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                coherent_store(p.o_partial + (slot0 * R + r) * D + v * 64 + lane, a[r][v]);
+            if (lane == 0) coherent_store(p.lse_partial + slot0 * R + r, M[r] * kLn2);
+        }
+    }
+}
+
+// Partial results (of segments, or in kModeSpread of chunks) that a writer wave has stored in
+// one pass over its mailboxes and that still have to be counted in.  Ordering across waves and
+// XCDs without cache-wide write-backs or invalidations (which were measured to cost several
+// times the merge launch they replace): the partial results are written with device-coherent
+// stores; the wave waits once until all its stores have completed, then bumps the counters of
+// the rows concerned with device-scope atomics, one lane per result; the wave whose atomic
+// completes a row reads the partial results with device-coherent loads issued after that
+// atomic has returned, combines them into `out` and rearms the counter.  Waiting once per pass
+// instead of once per result matters: a store takes a few microseconds to complete, about as
+// long as the streaming waves of a workgroup need to produce the next results.
+template <int NW>
+struct Arrivals {
+    int n = 0;
+    int dest[NW], parts[NW], out_row[NW], len[NW];
+    __device__ __forceinline__ void add(int d, int np, int o, int l)
+    {
+#pragma unroll
+        for (int i = 0; i < NW; ++i)
+            if (i == n) {
+                dest[i] = d;
+                parts[i] = np;
+                out_row[i] = o;
+                len[i] = l;
+            }
+        ++n;
+    }
+    __device__ __forceinline__ int pick(const int (&a)[NW], int i) const
+    {
+        int v = a[0];
+#pragma unroll
+        for (int k = 1; k < NW; ++k) v = i == k ? a[k] : v;
+        return v;
+    }
+};
+
+// Counters (AttnParams::arrivals), n_rows = (enumeration rows) x (selected heads) of the launch:
+// entry row counts the stored segment results of that row; in kModeSpread entry
+// n_rows + row * (segments per row the buffers provide for) + j counts the stored chunk results
+// of segment j of that row.  There the wave that completes a segment folds its chunks, which
+// spreads the folding of a long row over as many waves as it has segments, stores the segment
+// result and counts it in for the row in turn.
+template <int D, int R, int NW>
+__device__ __forceinline__ void count_in_and_combine(const AttnParams &p, const Arrivals<NW> &arr,
+                                                     bool spread, int n_rows, int lane)
+{
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);                   // every store of this wave has completed
-    if (lane == 0)
-        old = __hip_atomic_fetch_add(p.arrivals + row, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    old = __builtin_amdgcn_readfirstlane(old);
-    if ((int)old + 1 != n_segs) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    merge_partials<D, R>(p, row * p.max_segs, n_segs, out_row, lane);
-    if (lane == 0)
-        __hip_atomic_store(p.arrivals + row, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int seg_slots = p.max_segs / p.part_stride;   // segments per row (kModeSpread)
+    unsigned old = 0;
+    if (lane < arr.n) {
+        const int d = arr.pick(arr.dest, lane);
+        const int64_t row = d / p.max_segs;          // (enumeration row, head)
+        const int64_t counter = spread ? n_rows + row * seg_slots + (d % p.max_segs) / p.part_stride : row;
+        old = __hip_atomic_fetch_add(p.arrivals + counter, 1u, __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+    }
+    for (int i = 0; i < arr.n; ++i) {
+        const int before = __builtin_amdgcn_readlane((int)old, i);
+        const int d = arr.pick(arr.dest, i);
+        const int64_t row = d / p.max_segs;
+        const int64_t out_row = arr.pick(arr.out_row, i);
+        int n_segs = arr.pick(arr.parts, i);
+        if (spread) {
+            const int L = arr.pick(arr.len, i);
+            const int j = (d % p.max_segs) / p.part_stride;
+            const int n_tok = min(p.seg_tokens, L - j * p.seg_tokens);
+            const int ct = chunk_tokens_of(n_tok, p.chunk_tokens, p.seg_tokens);
+            const int ns = (n_tok + ct - 1) / ct;
+            if (before + 1 != ns) continue;
+            n_segs = (L + p.seg_tokens - 1) / p.seg_tokens;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            fold_segment_from_chunks<D, R>(p, row * p.max_segs + (int64_t)j * p.part_stride, ns,
+                                           n_segs == 1, out_row, lane);
+            unsigned seen = 0;
+            if (n_segs > 1) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_s_waitcnt(0);       // the segment result is stored
+            }
+            if (lane == 0) {
+                __hip_atomic_store(p.arrivals + n_rows + row * seg_slots + j, 0u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                if (n_segs > 1)
+                    seen = __hip_atomic_fetch_add(p.arrivals + row, 1u, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (n_segs == 1 || (int)__builtin_amdgcn_readfirstlane(seen) + 1 != n_segs) continue;
+        } else if (before + 1 != n_segs) {
+            continue;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        merge_partials<D, R>(p, row * p.max_segs, n_segs, p.part_stride, out_row, lane);
+        if (lane == 0)
+            __hip_atomic_store(p.arrivals + row, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 struct ItemHdr {
@@ -271,7 +455,7 @@ struct ItemHdr {
     int rem;        // tokens in the ragged last block (0: none)
     int t0;         // first token of the chunk
     int kind, dest, cs;
-    int nseg, out_row;
+    int nseg, out_row, len;
 };
 
 __host__ __device__ constexpr size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
@@ -365,6 +549,14 @@ __global__ __launch_bounds__((NW + 1) * 64)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int seg_tokens = p.seg_tokens;
     const int chunk_tokens = p.chunk_tokens;
+    const bool spread = p.mode == kModeSpread;
+    // kModeSpread: chunks of a row of L tokens (a row without tokens has one, which writes zeros)
+    auto row_chunks = [&](int L) {
+        if (L <= 0) return 1;
+        const int nF = L / seg_tokens, rt = L - nF * seg_tokens;
+        const int ct = chunk_tokens_of(rt, chunk_tokens, seg_tokens);
+        return nF * p.part_stride + (rt + ct - 1) / ct;
+    };
 
     // ---- work enumeration.  All threads fetch the lengths and work out the counts of their
     // rows (whole segments; size class of the last, shorter segment), four rows a thread and
@@ -397,11 +589,16 @@ __global__ __launch_bounds__((NW + 1) * 64)
         for (int u = 0; u < 4; ++u) {
             const int i = i0 + u * NT;
             if (i >= batch) continue;
-            const int nF = L[u] > 0 ? L[u] / seg_tokens : 0;
+            int nF = L[u] > 0 ? L[u] / seg_tokens : 0;
             const int rt = L[u] > 0 ? L[u] - nF * seg_tokens : 0;
             int cls = -1;
-            if (rt > 0) cls = size_class(rt);
-            if (L[u] <= 0 && p.direct_single) cls = kClasses - 1;   // the segment that writes the zeros
+            if (spread) {
+                // chunks are counted instead of whole segments, and no row is listed
+                nF = row_chunks(L[u]);
+            } else {
+                if (rt > 0) cls = size_class(rt);
+                if (L[u] <= 0 && p.direct_single) cls = kClasses - 1;   // the segment that writes the zeros
+            }
             lens[i] = L[u];
             firstF[i] = nF;                             // counts for now; running counts after the scan
             cls_of[i] = (unsigned char)(cls + 1);
@@ -504,23 +701,57 @@ __global__ __launch_bounds__((NW + 1) * 64)
         int t0, n_tok;      // first token, tokens
         int ct, ns;         // tokens per chunk, chunks
         int kind, dest;     // where the whole segment goes
-        int nseg, out_row;  // segments of the row; first of its R rows in `out`
+        int nseg, out_row;  // segments of the row (kModeSpread: its chunks); first of its R rows in `out`
         int tail;           // 1: the segment ends with the row's last token
+        int len;            // tokens of the row
     };
-    // Tokens per chunk of a segment of n_tok tokens: the shorter the segment, the later it is
-    // handed out and the finer it is cut, so that the chunks still running when the work runs
-    // out are short ones.  A function of the row's length only, like everything that shapes
-    // the arithmetic.
-    auto chunk_for = [&](int n_tok) {
-        int ct = chunk_tokens;
-        if (seg_tokens > chunk_tokens) {
-            if (n_tok <= seg_tokens / HETIS_FINE_CHUNK_BELOW) ct = chunk_tokens / 2;
-            if (n_tok <= seg_tokens / (4 * HETIS_FINE_CHUNK_BELOW)) ct = chunk_tokens / 4;
-            ct = max(ct, 2 * kBlockTokens);
+    auto chunk_for = [&](int n_tok) { return chunk_tokens_of(n_tok, chunk_tokens, seg_tokens); };
+    // kModeSpread: item number -> (row, chunk, head); the item is returned as a segment of one chunk
+    auto decode_spread = [&](int itemno) {
+        Segment s;
+        const int w = min(itemno, max(total - 1, 0));
+        const int cg = PAIRS ? w : w / n_sel;
+        const int si = PAIRS ? 0 : w - cg * n_sel;
+        s.b = upper(firstF, cg);
+        const int k = cg - firstF[s.b];                 // chunk of the row
+        const int L = lens[s.b];
+        const int gc = p.part_stride;
+        const int nF = L > 0 ? L / seg_tokens : 0;
+        int j, c;
+        if (k < nF * gc) {
+            j = k / gc;
+            c = k - j * gc;
+            s.ct = chunk_tokens;
+            s.n_tok = chunk_tokens;
+        } else {
+            j = nF;
+            c = k - nF * gc;
+            const int rt = max(L, 0) - nF * seg_tokens;
+            s.ct = chunk_for(rt);
+            s.n_tok = max(0, min(s.ct, rt - c * s.ct));
         }
-        return ct;
+        s.t0 = j * seg_tokens + c * s.ct;
+        s.ns = 1;
+        s.g = hids[PAIRS ? s.b : si];
+        s.seq = PAIRS ? pseq[s.b] : s.b;
+        s.nseg = row_chunks(L);
+        s.out_row = s.seq * p.n_q_heads + s.g * R;
+        s.tail = L > 0 && s.t0 + s.n_tok == L;
+        s.len = L;
+        if (L <= 0) {
+            s.kind = kKindZero;
+            s.dest = s.out_row;
+        } else if (s.nseg == 1) {
+            s.kind = kKindOut;
+            s.dest = s.out_row;
+        } else {
+            s.kind = kKindPartial;
+            s.dest = (s.b * n_sel + si) * p.max_segs + j * gc + c;
+        }
+        return s;
     };
     auto decode = [&](int segno) {
+        if (spread) return decode_spread(segno);
         Segment s;
         const int w = min(segno, max(total - 1, 0));
         const int cg = PAIRS ? w : w / n_sel;
@@ -546,6 +777,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         s.nseg = n_segs;
         s.out_row = s.seq * p.n_q_heads + s.g * R;
         s.tail = L > 0 && s.t0 + s.n_tok == L;
+        s.len = L;
         if (L <= 0) {
             s.kind = kKindZero;
             s.dest = s.out_row;
@@ -572,7 +804,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         d.cs = i;
         d.nseg = s.nseg;
         d.out_row = s.out_row;
-        d.pad = 0;
+        d.len = s.len;
         return d;
     };
     // Work a workgroup has without a ticket.  When segments have several chunks: segment number
@@ -581,7 +813,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // (blockIdx.x + k gridDim.x) * NW + v, k = 0, 1, two per streaming wave v (the waves of a
     // workgroup work on neighbouring heads of one chunk position).  Tickets number the segments
     // after these.
-    const bool single_mode = seg_tokens == chunk_tokens;
+    const bool single_mode = p.mode != kModeSegments;
     const bool have_first = (int)blockIdx.x < total;
     const bool step_mode = p.k_new != nullptr;      // never together with single_mode
     // chunks of the first segment that are taken without the pool: the first NW, but not the
@@ -638,6 +870,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             r.nseg = __builtin_amdgcn_readlane(s.nseg, k);
             r.out_row = __builtin_amdgcn_readlane(s.out_row, k);
             r.tail = __builtin_amdgcn_readlane(s.tail, k);
+            r.len = __builtin_amdgcn_readlane(s.len, k);
             return r;
         };
         while (done_mask != (1 << NW) - 1 && idle < kSpinLimit) {
@@ -746,6 +979,9 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 progressed = true;
             }
             // ---- results
+            // partial results stored in this pass that are merged inside this launch: counted in
+            // after the pass, when their mailboxes have been handed back
+            Arrivals<NW> arrivals;
 #pragma unroll
             for (int v = 0; v < NW; ++v) {
                 if (done_mask & (1 << v)) continue;
@@ -759,17 +995,12 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 if (f != kMailFull) continue;
                 const int kind = __builtin_amdgcn_readfirstlane(mb.kind);
                 const int dest = __builtin_amdgcn_readfirstlane(mb.dest);
-                // a partial result that this launch merges itself: stored, then counted in once
-                // the mailbox has been handed back
-                bool arrive = false;
-                int arrive_dest = 0, arrive_nseg = 0, arrive_out = 0;
                 if (kind != kKindFold) {
                     if (kind == kKindPartial && p.arrivals) {
-                        store_partial_coherent<D, R>(mb.o, mb.lse, nullptr, dest, p, lane);
-                        arrive = true;
-                        arrive_dest = dest;
-                        arrive_nseg = __builtin_amdgcn_readfirstlane(mb.nseg);
-                        arrive_out = __builtin_amdgcn_readfirstlane(mb.out_row);
+                        store_partial_coherent<D, R>(mb.o, mb.lse, nullptr, dest, p, lane, spread);
+                        arrivals.add(dest, __builtin_amdgcn_readfirstlane(mb.nseg),
+                                     __builtin_amdgcn_readfirstlane(mb.out_row),
+                                     __builtin_amdgcn_readfirstlane(mb.len));
                     } else {
                         store_result<D, R>(mb.o, mb.lse, nullptr, kind, dest, p, lane);
                     }
@@ -785,12 +1016,10 @@ __global__ __launch_bounds__((NW + 1) * 64)
                         const float4 x = *reinterpret_cast<const float4 *>(&mb.o[r][d]);
                         float4 a = x;
                         if (cs > 0) {
-                            const float Mo = fs.M[r], lc = mb.lse[r];
-                            const float Mn = fmaxf(Mo, lc);
-                            const float so = fast_exp2(Mo - Mn), sc = fast_exp2(lc - Mn);
+                            const FoldCoef f = fold_coef(fs.M[r], mb.lse[r]);
                             const float4 y = *reinterpret_cast<const float4 *>(&fs.acc[r][d]);
-                            a = make_float4(fmaf(y.x, so, x.x * sc), fmaf(y.y, so, x.y * sc),
-                                            fmaf(y.z, so, x.z * sc), fmaf(y.w, so, x.w * sc));
+                            a = make_float4(fold_elem(y.x, x.x, f), fold_elem(y.y, x.y, f),
+                                            fold_elem(y.z, x.z, f), fold_elem(y.w, x.w, f));
                         }
                         *reinterpret_cast<float4 *>(&fs.acc[r][d]) = a;
                     }
@@ -799,9 +1028,9 @@ __global__ __launch_bounds__((NW + 1) * 64)
                         const float lc = mb.lse[lane];
                         float Mn = lc, Wn = 1.f;
                         if (cs > 0) {
-                            const float Mo = fs.M[lane];
-                            Mn = fmaxf(Mo, lc);
-                            Wn = fs.W[lane] * fast_exp2(Mo - Mn) + fast_exp2(lc - Mn);
+                            const FoldCoef f = fold_coef(fs.M[lane], lc);
+                            Mn = f.Mn;
+                            Wn = fold_weight(fs.W[lane], f);
                         }
                         fs.W[lane] = Wn;
                         // after the last chunk the slot holds the segment's log-sum-exp
@@ -813,11 +1042,9 @@ __global__ __launch_bounds__((NW + 1) * 64)
                         const int fkind = __builtin_amdgcn_readfirstlane(fs.kind);
                         const int fdest = __builtin_amdgcn_readfirstlane(fs.dest);
                         if (fkind == kKindPartial && p.arrivals) {
-                            store_partial_coherent<D, R>(fs.acc, fs.M, fs.W, fdest, p, lane);
-                            arrive = true;
-                            arrive_dest = fdest;
-                            arrive_nseg = __builtin_amdgcn_readfirstlane(fs.nseg);
-                            arrive_out = __builtin_amdgcn_readfirstlane(fs.out_row);
+                            store_partial_coherent<D, R>(fs.acc, fs.M, fs.W, fdest, p, lane, false);
+                            arrivals.add(fdest, __builtin_amdgcn_readfirstlane(fs.nseg),
+                                         __builtin_amdgcn_readfirstlane(fs.out_row), 0);
                         } else {
                             store_result<D, R>(fs.acc, fs.M, fs.W, fkind, fdest, p, lane);
                         }
@@ -827,8 +1054,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 mail_store(&mb.flag, kMailEmpty);
                 next_box[v] ^= 1;
                 progressed = true;
-                if (arrive) arrive_and_merge<D, R>(p, arrive_dest, arrive_nseg, arrive_out, lane);
             }
+            if (arrivals.n > 0) count_in_and_combine<D, R, NW>(p, arrivals, spread, batch * n_sel, lane);
             if (progressed) {
                 idle = 0;
             } else {
@@ -872,6 +1099,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         s.h.cs = __builtin_amdgcn_readfirstlane(d.cs);
         s.h.nseg = __builtin_amdgcn_readfirstlane(d.nseg);
         s.h.out_row = __builtin_amdgcn_readfirstlane(d.out_row);
+        s.h.len = __builtin_amdgcn_readfirstlane(d.len);
         s.exists = (flags & kItemExists) != 0;
         s.h.nblk = s.exists ? (n_tok + kBlockTokens - 1) / kBlockTokens : 0;
         s.h.rem = n_tok & (kBlockTokens - 1);
@@ -1013,6 +1241,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             mb.cs = cur.h.cs;
             mb.nseg = cur.h.nseg;
             mb.out_row = cur.h.out_row;
+            mb.len = cur.h.len;
         }
         mail_store(&mb.flag, kMailFull);
         if (!nxt.exists) break;

@@ -2,6 +2,7 @@
 // Every argument error is reported before the first HIP call, so the checks can be
 // exercised on a machine without a GPU.
 #include "../../include/hetis_attn.h"
+#include "../../include/hetis_kv.h"
 
 #include <hip/hip_ext.h>
 
@@ -56,6 +57,9 @@ constexpr int kWgsPerCu = 1;    // persistent workgroups per compute unit
 // Rows (sequences, or pairs) per launch: what the persistent kernel's LDS tables hold.  Larger
 // batches run as several launches over slices of the rows.
 constexpr int kMaxPersistBatch = 2048;
+// Arrival counters of a decode workspace (see the workspace layout below).
+constexpr size_t kArrivalSlots = (size_t)1 << 18;
+constexpr size_t kArrivalBytes = kArrivalSlots * sizeof(unsigned int);
 constexpr int kMaxPersistHeads = 1024;
 // A wave keeps the block ids of one chunk in one register (64 lanes).
 constexpr int kMaxChunkTokens = 64 * kBlockTokens;
@@ -200,14 +204,17 @@ static int launch_chunk(const AttnParams &p0, int rows, hipStream_t st)
 {
     const bool pairs = p0.pair_seq != nullptr;
     const int n_sel = pairs ? 1 : p0.n_sel;
-    for (int row0 = 0; row0 < rows; row0 += kMaxPersistBatch) {
-        const int n = std::min(kMaxPersistBatch, rows - row0);
+    // the arrival counters are indexed by (row of the slice, head): a slice has no more
+    // (row, head) combinations than there are counters
+    const int slice = p0.arrivals ? std::min<int64_t>(kMaxPersistBatch, (int64_t)kArrivalSlots / n_sel)
+                                  : kMaxPersistBatch;
+    for (int row0 = 0; row0 < rows; row0 += slice) {
+        const int n = std::min(slice, rows - row0);
         AttnParams p = p0;
         p.block_table += (int64_t)row0 * p.max_blocks_per_seq;
         const int64_t part0 = (int64_t)row0 * n_sel * p.max_segs * R;
         if (p.o_partial) p.o_partial += part0 * D;
         if (p.lse_partial) p.lse_partial += part0;
-        if (p.arrivals) p.arrivals += (int64_t)row0 * n_sel;
         if (pairs) {
             p.pair_seq += row0;
             p.pair_head += row0;
@@ -250,49 +257,72 @@ static void launch_merge(const AttnParams &p, int D, int r, int batch, hipStream
 
 // ---- workspaces.  Layout of a decode workspace (all offsets multiples of 256 bytes):
 //   [0, kControlBytes)   control words (tickets drawn, workgroups finished, error word)
-//   arrivals             uint32 [kArrivalSlots]: entry row * n_sel + head counts the segments of
-//                        that row whose partial result is stored.  The area has a fixed size so
+//   arrivals             uint32 [kArrivalSlots]: entry row * n_sel + head counts the partial
+//                        results of that row that are stored.  The area has a fixed size so
 //                        that it sits at the same place whatever the shape: calls of different
 //                        shapes can then share one workspace, since no call's partial results
 //                        ever land on another call's counters, and every launch leaves the
 //                        counters it used at zero.
-//   o_partial            fp32 [rows, n_sel, max_segs, r, D]
-//   lse_partial          fp32 [rows, n_sel, max_segs, r]
-// rows = sequences, or pairs in pairs mode (n_sel = 1 there); max_segs = segments of the
-// longest row the block table allows.  A shape whose rows fit one segment needs the control
-// words only.
-constexpr size_t kArrivalSlots = (size_t)1 << 18;
-constexpr size_t kArrivalBytes = kArrivalSlots * sizeof(unsigned int);
+//   o_partial            fp32 [rows, n_sel, slots, r, D]
+//   lse_partial          fp32 [rows, n_sel, slots, r]
+// rows = sequences, or pairs in pairs mode (n_sel = 1 there).  Segment scheduling: slots =
+// segments of the longest row the block table allows, and a shape whose rows fit one segment
+// needs the control words only.  Spread scheduling (few rows): slots = chunks of the longest
+// row, segment by segment.
+// Launches with fewer rows (enumeration rows x selected heads) than this cut the work into
+// single chunks instead of whole segments: with so few rows whole segments would leave most
+// compute units without work.  Twice the number of compute units of the target.
+#ifndef HETIS_SPREAD_BELOW_ROWS
+#define HETIS_SPREAD_BELOW_ROWS 512
+#endif
 struct WsLayout {
     size_t arrivals = 0, o_partial = 0, lse_partial = 0, total = kControlBytes;
     size_t zeroed = kControlBytes;     // leading bytes this shape needs to be zero between launches
-    bool fused = false;                // partial results are merged inside the launch
+    int slots = 1;                     // partial-result slots per row
+    int part_stride = 1;
+    bool spread = false;
 };
 constexpr size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-
-static WsLayout decode_ws_layout(int64_t rows, int n_sel, int group, int D, int max_segs)
-{
-    WsLayout w;
-    if (max_segs <= 1 || rows <= 0) return w;        // every row is written directly
-    const size_t partial_rows = (size_t)rows * n_sel * group * max_segs;
-    w.arrivals = kControlBytes;
-    w.o_partial = kControlBytes + kArrivalBytes;
-    // more rows than counters: the partial results are merged by a separate launch
-#ifndef HETIS_FUSED_MERGE
-#define HETIS_FUSED_MERGE 1
-#endif
-    w.fused = HETIS_FUSED_MERGE && (size_t)rows * n_sel <= kArrivalSlots;
-    if (w.fused) w.zeroed = align256(w.arrivals + (size_t)rows * n_sel * sizeof(unsigned int));
-    w.lse_partial = align256(w.o_partial + partial_rows * D * sizeof(float));
-    w.total = align256(w.lse_partial + partial_rows * sizeof(float));
-    return w;
-}
 
 static int decode_max_segs(const hetis_attn_shape *s, int group)
 {
     const int seg = decode_seg_tokens(group);
     const int64_t max_tokens = (int64_t)s->max_blocks_per_seq * kBlockTokens;
     return (int)((max_tokens + seg - 1) / seg);
+}
+
+// `spread`: lay the workspace out for spread scheduling.
+static WsLayout decode_ws_layout(const hetis_attn_shape *s, int64_t rows, int n_sel, int group,
+                                 bool spread)
+{
+    WsLayout w;
+    const int max_segs = decode_max_segs(s, group);
+    w.spread = spread;
+    w.part_stride = spread ? decode_seg_tokens(group) / decode_chunk_tokens(group) : 1;
+    w.slots = max_segs * w.part_stride;
+    if (w.slots <= 1 || rows <= 0) return w;         // every row is written directly
+    const size_t partial_rows = (size_t)rows * n_sel * group * w.slots;
+    w.arrivals = kControlBytes;
+    w.o_partial = kControlBytes + kArrivalBytes;
+    // counters in use: one per (row, head) of a launch; spread scheduling: one more per segment
+    w.zeroed = align256(w.arrivals + (size_t)std::min<int64_t>(rows, kMaxPersistBatch) * n_sel *
+                                         (spread ? 1 + max_segs : 1) * sizeof(unsigned int));
+    w.lse_partial = align256(w.o_partial + partial_rows * s->head_dim * sizeof(float));
+    w.total = align256(w.lse_partial + partial_rows * sizeof(float));
+    return w;
+}
+
+// Scheduling of a decode call over `rows` enumeration rows: spread when there are few rows and
+// the workspace at hand (`have` bytes; SIZE_MAX: it will be made large enough) holds the chunk
+// results, whole segments otherwise.  The choice never changes a result.
+static WsLayout choose_layout(const hetis_attn_shape *s, int64_t rows, int n_sel, int group,
+                              size_t have)
+{
+    if (rows * n_sel < HETIS_SPREAD_BELOW_ROWS) {
+        const WsLayout w = decode_ws_layout(s, rows, n_sel, group, true);
+        if (w.total <= have && w.zeroed <= kControlBytes + kArrivalBytes) return w;
+    }
+    return decode_ws_layout(s, rows, n_sel, group, false);
 }
 
 static int check_workspace(const void *ws, size_t have, size_t need)
@@ -426,6 +456,26 @@ static AttnParams make_params(const hetis_attn_shape *s, const Checked &c, const
     return p;
 }
 
+// Token cut, scheduling mode and workspace pointers of a decode call.
+static void apply_layout(AttnParams &p, const WsLayout &lay, int group, void *workspace)
+{
+    p.chunk_tokens = decode_chunk_tokens(group);
+    p.seg_tokens = decode_seg_tokens(group);
+    p.max_segs = lay.slots;
+    p.part_stride = lay.part_stride;
+    p.mode = lay.spread ? kModeSpread : kModeSegments;
+    p.direct_single = 1;
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    p.control = reinterpret_cast<unsigned int *>(base);
+    if (lay.slots > 1) {
+        // Rows cut into several pieces leave one partial result per piece; the wave that
+        // stores a row's last one combines them, so there is no merge launch.
+        p.o_partial = reinterpret_cast<float *>(base + lay.o_partial);
+        p.lse_partial = reinterpret_cast<float *>(base + lay.lse_partial);
+        p.arrivals = reinterpret_cast<unsigned int *>(base + lay.arrivals);
+    }
+}
+
 }  // namespace hetis
 
 using namespace hetis;
@@ -468,9 +518,8 @@ static int decode_common(const hetis_attn_shape *shape, const void *q, const voi
     if (step && (!k_new || !v_new)) return HETIS_ERR_NULL;
     int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
-    const int max_segs = decode_max_segs(shape, c.group);
-    const WsLayout lay = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
-                                          max_segs);
+    const WsLayout lay = choose_layout(shape, shape->batch, n_sel_heads, c.group,
+                                       owned ? SIZE_MAX : workspace_bytes);
     hipStream_t st = (hipStream_t)stream;
     if (owned)
         rc = owned_workspace(lay.total, st, true, &workspace);
@@ -480,26 +529,22 @@ static int decode_common(const hetis_attn_shape *shape, const void *q, const voi
 
     AttnParams p = make_params(shape, c, q, k_cache, v_cache, block_table, seq_lens, head_ids,
                                n_sel_heads, scale, out);
-    p.chunk_tokens = decode_chunk_tokens(c.group);
-    p.seg_tokens = decode_seg_tokens(c.group);
-    p.max_segs = max_segs;
-    p.direct_single = 1;
+    apply_layout(p, lay, c.group, workspace);
     if (step) {
-        p.k_new = static_cast<const __half *>(k_new);
-        p.v_new = static_cast<const __half *>(v_new);
-    }
-    unsigned char *base = static_cast<unsigned char *>(workspace);
-    p.control = reinterpret_cast<unsigned int *>(base);
-    if (max_segs > 1) {
-        p.o_partial = reinterpret_cast<float *>(base + lay.o_partial);
-        p.lse_partial = reinterpret_cast<float *>(base + lay.lse_partial);
-        // rows longer than a segment leave one partial result per segment; the wave that
-        // stores a row's last one merges them, so there is no merge launch
-        if (lay.fused) p.arrivals = reinterpret_cast<unsigned int *>(base + lay.arrivals);
+        if (lay.spread) {
+            // single chunks are handed out without regard to which of them reads the new rows:
+            // the store runs as a launch of its own ahead of the Attention launch
+            rc = hetis_kv_append(shape, k_new, v_new, block_table, seq_lens, head_ids, n_sel_heads,
+                                 INT64_MAX, const_cast<void *>(k_cache), const_cast<void *>(v_cache),
+                                 stream);
+            if (rc != HETIS_OK) return rc;
+        } else {
+            p.k_new = static_cast<const __half *>(k_new);
+            p.v_new = static_cast<const __half *>(v_new);
+        }
     }
     rc = launch_chunks(p, shape->head_dim, c.group, shape->batch, st);
     if (rc != HETIS_OK) return rc;
-    if (max_segs > 1 && !lay.fused) launch_merge(p, shape->head_dim, c.group, shape->batch, st);
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
 
@@ -555,8 +600,7 @@ int hetis_attn_decode_static(const hetis_attn_shape *shape, const void *q, const
         return HETIS_ERR_NULL;
     int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
-    const WsLayout lay = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
-                                          decode_max_segs(shape, c.group));
+    const WsLayout lay = choose_layout(shape, shape->batch, n_sel_heads, c.group, kStaticScratchBytes);
     if (lay.total > kStaticScratchBytes) return HETIS_ERR_WORKSPACE;   // before any HIP call
     void *ws = nullptr;
     rc = static_scratch(&ws);
@@ -578,8 +622,7 @@ int hetis_attn_decode_workspace_bytes(const hetis_attn_shape *shape, int32_t n_s
     if (!shape || !bytes) return HETIS_ERR_NULL;
     const int rc = check_shape(shape, n_sel_heads, &c);
     if (rc != HETIS_OK) return rc;
-    *bytes = decode_ws_layout(shape->batch, n_sel_heads, c.group, shape->head_dim,
-                              decode_max_segs(shape, c.group)).total;
+    *bytes = choose_layout(shape, shape->batch, n_sel_heads, c.group, SIZE_MAX).total;
     return HETIS_OK;
 }
 
@@ -604,8 +647,7 @@ int hetis_attn_decode_pairs_workspace_bytes(const hetis_attn_shape *shape, int32
     if (!shape || !bytes) return HETIS_ERR_NULL;
     const int rc = check_pairs(shape, n_pairs, &c);
     if (rc != HETIS_OK) return rc;
-    *bytes = decode_ws_layout(n_pairs, 1, c.group, shape->head_dim,
-                              decode_max_segs(shape, c.group)).total;
+    *bytes = choose_layout(shape, n_pairs, 1, c.group, SIZE_MAX).total;
     return HETIS_OK;
 }
 
@@ -621,8 +663,7 @@ static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, con
         return HETIS_ERR_NULL;
     int rc = check_pairs(shape, n_pairs, &c);
     if (rc != HETIS_OK) return rc;
-    const int max_segs = decode_max_segs(shape, c.group);
-    const WsLayout lay = decode_ws_layout(n_pairs, 1, c.group, shape->head_dim, max_segs);
+    const WsLayout lay = choose_layout(shape, n_pairs, 1, c.group, owned ? SIZE_MAX : workspace_bytes);
     if (!owned) {
         rc = check_workspace(workspace, workspace_bytes, lay.total);
         if (rc != HETIS_OK) return rc;
@@ -638,20 +679,9 @@ static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, con
                                scale, out);
     p.pair_seq = pair_seq;
     p.pair_head = pair_head;
-    p.chunk_tokens = decode_chunk_tokens(c.group);
-    p.seg_tokens = decode_seg_tokens(c.group);
-    p.max_segs = max_segs;
-    p.direct_single = 1;
-    unsigned char *base = static_cast<unsigned char *>(workspace);
-    p.control = reinterpret_cast<unsigned int *>(base);
-    if (max_segs > 1) {
-        p.o_partial = reinterpret_cast<float *>(base + lay.o_partial);
-        p.lse_partial = reinterpret_cast<float *>(base + lay.lse_partial);
-        if (lay.fused) p.arrivals = reinterpret_cast<unsigned int *>(base + lay.arrivals);
-    }
+    apply_layout(p, lay, c.group, workspace);
     rc = launch_chunks(p, shape->head_dim, c.group, n_pairs, st);
     if (rc != HETIS_OK) return rc;
-    if (max_segs > 1 && !lay.fused) launch_merge(p, shape->head_dim, c.group, n_pairs, st);
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
 }
 
@@ -786,6 +816,8 @@ static int decode_split_common(const hetis_attn_shape *shape, const void *q, con
                                n_sel_heads, scale, nullptr);
     p.chunk_tokens = chunk_tokens;      // every chunk is a segment of its own
     p.seg_tokens = chunk_tokens;
+    p.mode = kModeSplit;
+    p.part_stride = 1;
     p.max_segs = hetis_attn_split_num_chunks(max_seq_len, chunk_tokens);
     p.direct_single = 0;
     p.o_partial = o_partial;

@@ -151,31 +151,49 @@ WS = 0x10000    # a fake, 256-byte aligned workspace address
 
 def test_workspace_sizes(lib):
     up = lambda x: (x + 255) // 256 * 256
-    # rows of up to one segment (4096 tokens) are combined inside a workgroup: a shape whose
-    # block table allows no more needs the control words only
+    fixed = 256 + 4 * (1 << 18)
+    # 512 or more rows (sequences x selected heads, or pairs): the work is handed out in whole
+    # segments.  Rows of up to one segment (4096 tokens) are combined inside a workgroup: a shape
+    # whose block table allows no more needs the control words only
     s = H.make_shape(128, 40, 40, 128, 256)
     assert H.hetis_attn_decode_workspace_bytes(s, 13) == (0, 256)
-    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 64, 16), 4) == (0, 256)
     assert H.hetis_attn_decode_pairs_workspace_bytes(s, 1721) == (0, 256)
     assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 256), 3) == (0, 256)
     # longer rows: control words, a fixed area of 2^18 arrival counters, then one partial result
     # of (D + 1) floats per segment and query row; each area rounded up to 256 bytes.
-    # c4's shape: up to 32768 tokens = 8 segments
-    long = H.make_shape(8, 40, 40, 128, 2048)
-    rows = 8 * 40 * 8
-    fixed = 256 + 4 * (1 << 18)
+    # up to 32768 tokens = 8 segments
+    long = H.make_shape(64, 40, 40, 128, 2048)
+    rows = 64 * 40 * 8
     assert H.hetis_attn_decode_workspace_bytes(long, 40) == (0, fixed + rows * 128 * 4 + up(rows * 4))
     # a grouped-query shape with up to 8192 tokens: 2 segments, r = 8 rows each
     rows = 256 * 3 * 2 * 8
     assert H.hetis_attn_decode_workspace_bytes(H.make_shape(256, 64, 8, 128, 512), 3) \
         == (0, fixed + rows * 128 * 4 + up(rows * 4))
     # one block more than a whole number of segments: one more segment
-    rows = 3 * 5 * 2 * 1
-    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(3, 8, 8, 64, 257), 5) \
+    rows = 300 * 5 * 2 * 1
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(300, 8, 8, 64, 257), 5) \
         == (0, fixed + rows * 64 * 4 + up(rows * 4))
     assert H.hetis_attn_decode_pairs_workspace_bytes(long, 0) == (0, 256)
-    rows = 77 * 8
+    rows = 777 * 8
+    assert H.hetis_attn_decode_pairs_workspace_bytes(long, 777) \
+        == (0, fixed + rows * 128 * 4 + up(rows * 4))
+    # fewer than 512 rows: the work is handed out in single chunks, whose results all pass
+    # through the workspace: one slot per chunk of a whole segment (4096 / 256 = 16, grouped-query
+    # shapes 4096 / 512 = 8) and segment the block table allows
+    rows = 4 * 4 * 16
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 64, 16), 4) \
+        == (0, fixed + rows * 64 * 4 + up(rows * 4))
+    rows = 8 * 40 * 8 * 16
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(8, 40, 40, 128, 2048), 40) \
+        == (0, fixed + rows * 128 * 4 + up(rows * 4))
+    rows = 3 * 5 * 2 * 16
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(3, 8, 8, 64, 257), 5) \
+        == (0, fixed + rows * 64 * 4 + up(rows * 4))
+    rows = 77 * 8 * 16
     assert H.hetis_attn_decode_pairs_workspace_bytes(long, 77) \
+        == (0, fixed + rows * 128 * 4 + up(rows * 4))
+    rows = 16 * 3 * 2 * 8 * 8
+    assert H.hetis_attn_decode_workspace_bytes(H.make_shape(16, 64, 8, 128, 512), 3) \
         == (0, fixed + rows * 128 * 4 + up(rows * 4))
     assert H.hetis_attn_decode_workspace_bytes(s, 0)[0] == binding.HETIS_ERR_BAD_HEADS
     assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 96, 16), 4)[0] == binding.HETIS_ERR_UNSUPPORTED
@@ -222,7 +240,12 @@ def test_ws_entry_points_argument_errors(lib):
         return H.hetis_attn_decode_ws(shape, q, P, P, P, P, P, n_sel, 0.125, P, ws, nbytes, 0)
     assert call(ws=None) == binding.HETIS_ERR_NULL
     assert call(q=None) == binding.HETIS_ERR_NULL
-    assert call(nbytes=need - 1) == binding.HETIS_ERR_WORKSPACE
+    # a call with few rows works with less than that (it then hands out whole segments, for
+    # which one slot per segment is enough), but not with less than what segments need
+    rows = 4 * 4 * 3
+    seg_need = 256 + 4 * (1 << 18) + rows * 64 * 4 + (rows * 4 + 255) // 256 * 256
+    assert seg_need < need
+    assert call(nbytes=seg_need - 1) == binding.HETIS_ERR_WORKSPACE
     assert call(ws=WS + 64) == binding.HETIS_ERR_WORKSPACE              # not 256-byte aligned
     assert call(n_sel=9) == binding.HETIS_ERR_BAD_HEADS
     assert call(shape=H.make_shape(4, 8, 8, 96, 16)) == binding.HETIS_ERR_UNSUPPORTED

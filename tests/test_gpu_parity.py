@@ -69,6 +69,8 @@ EDGE_LENS = [0, 1, 2, 15, 16, 17, 31, 33, 255, 256, 257, 300, 511, 512, 513, 100
     (8, 2, 64, [1]),           # r = 4
     (16, 2, 128, [0, 1]),      # r = 8
     (8, 1, 64, [0]),           # r = 8, D = 64
+    (40, 40, 128, list(range(1, 37))),   # 576 rows: handed out in whole segments
+    (80, 40, 64, list(range(2, 40))),    # the same with r = 2
 ])
 def test_edge_lengths(Hq, Hkv, D, hid):
     w = W.make_custom(EDGE_LENS, Hq, Hkv, D, hid, seed=31, max_seq_len=1024)

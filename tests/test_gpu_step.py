@@ -68,6 +68,8 @@ def check_step(w, heads, use_ws=False):
     (8, 4, 128, [0, 3]),       # r = 2
     (16, 2, 128, [1]),         # r = 8
     (8, 1, 64, [0]),           # r = 8, D = 64
+    (32, 32, 128, list(range(32))),      # 576 rows: whole segments, the store inside the kernel
+    (256, 32, 128, list(range(3, 32))),  # the same with r = 8
 ])
 def test_step_edge_lengths(Hq, Hkv, D, heads):
     # lengths around block, chunk and segment boundaries; the new token is the last one counted

@@ -33,14 +33,20 @@ def test_decode_ws_equals_decode_bitwise_and_reuses_its_workspace():
     orc = oracle.attn_decode(w.q.cpu().numpy(), w.k_cache.cpu().numpy(), w.v_cache.cpu().numpy(),
                              w.block_table, w.seq_lens, np.asarray(heads, dtype=np.int32), w.spec.scale)
     check_rows(out, orc, selected_rows(w.spec, heads), TOL, "decode_ws")
-    # a workspace one byte short, or misaligned, is refused before anything is launched
+    # a workspace too small even for whole segments (here: for the control words), or
+    # misaligned, is refused before anything is launched
     hid, n = d.heads(heads)
     out2 = d.new_out()
     args = (d.shape, d.q, d.k, d.v, d.bt, d.sl, hid, n, d.scale, out2)
-    assert H.hetis_attn_decode_ws(*args, ws, ws.numel() - 1) == H.binding.HETIS_ERR_WORKSPACE
+    assert H.hetis_attn_decode_ws(*args, ws, 255) == H.binding.HETIS_ERR_WORKSPACE
     assert H.hetis_attn_decode_ws(*args, ws.data_ptr() + 16, ws.numel()) == H.binding.HETIS_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert (bits(out2) == SENTINEL).all()
+    # one byte short of the size asked for: the call hands out whole segments instead of single
+    # chunks, which needs less, and gives the same bits
+    assert H.hetis_attn_decode_ws(*args, ws, ws.numel() - 1) == H.binding.HETIS_OK
+    torch.cuda.synchronize()
+    assert torch.equal(out2.view(torch.int16), ref.view(torch.int16))
 
 
 def test_concurrent_decode_ws_on_two_streams():
@@ -164,7 +170,7 @@ def test_decode_pairs_ws_and_split_ws():
     no_expired_wait(ws)
     assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
     assert H.hetis_attn_decode_pairs_ws(shape, pw.q, pw.k_tiles, pw.v_tiles, bt, sl, ps, ph,
-                                        pw.n_pairs, spec.scale, out, ws, nbytes - 256) \
+                                        pw.n_pairs, spec.scale, out, ws, 128) \
         == H.binding.HETIS_ERR_WORKSPACE
     # split form with the caller's control words
     w = W.make_custom([700, 64, 1300, 2000], 8, 8, 128, [2, 6], seed=210, device=DEV)
