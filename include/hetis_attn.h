@@ -122,13 +122,29 @@ const char *hetis_attn_status_string(int status);
  *   n_sel_heads  host, 1 .. Hkv
  *   scale        host, normally 1/sqrt(D)
  *   out          fp16 [B, Hq, D]; rows of unselected heads are left untouched
- * Sequences longer than an internal fixed chunk (a compile-time constant: 256
- * tokens for r < 4, 768 for r >= 4) are processed as several chunks whose fp32
- * partial results go through the workspace.
+ * The tokens of a (sequence, head) are cut, from token 0, into segments of 4096
+ * tokens and these into chunks (256 tokens for r < 4, 512 for r >= 4; a
+ * sequence's last, shorter segment into finer ones); chunk results are
+ * combined in ascending order into segment results, segment results into the
+ * row.  The cut and the order depend on the sequence's length and these
+ * constants only.  How the pieces are handed to the hardware does not change a
+ * bit of the result: a call with 512 or more (sequence, selected head)
+ * combinations hands out whole segments, whose chunks are combined on chip, so
+ * that only segment results of sequences longer than 4096 tokens pass through
+ * the workspace; a call with fewer hands out single chunks, whose results all
+ * pass through the workspace, so that a few long sequences still occupy the
+ * whole device.
  *
- * hetis_attn_decode_ws: the caller's workspace, at least
- *   hetis_attn_decode_workspace_bytes(shape, n_sel_heads) bytes (the size depends on
- *   batch, n_sel_heads, the group size, head_dim and max_blocks_per_seq only).
+ * hetis_attn_decode_ws: the caller's workspace.  hetis_attn_decode_workspace_bytes(shape,
+ *   n_sel_heads) is the size with which the call runs as described (it depends on batch,
+ *   n_sel_heads, the group size, head_dim and max_blocks_per_seq only, and is NOT monotonic
+ *   in n_sel_heads: size a workspace shared by calls with different head counts for each of
+ *   them).  A call with few combinations that is given less hands out whole segments
+ *   instead.  For that the control words (256 bytes) are enough when max_blocks_per_seq
+ *   <= 256; otherwise it takes 256 + 4 * 2^18 bytes of counters plus, per (sequence,
+ *   selected head), query head of the group and segment of the longest sequence the block
+ *   table allows, head_dim + 1 floats (the head_dim part and the 1 part are separate areas,
+ *   each rounded up to 256 bytes).  With less than that the call fails.
  *   Errors: NULL, BAD_SHAPE, UNSUPPORTED, BAD_HEADS, WORKSPACE (too small or not 256-byte
  *   aligned), LAUNCH.
  * hetis_attn_decode: convenience form of the same call on a workspace that the library
@@ -163,7 +179,9 @@ int hetis_attn_decode_ws(const hetis_attn_shape *shape, const void *q, const voi
  *   k_cache, v_cache  read and written
  * The cache ends up as hetis_kv_append leaves it and `out` as hetis_attn_decode computes it on
  * that cache, bit for bit; unlike hetis_kv_append this call does not range-check what it reads
- * from device memory (use hetis_attn_validate).  Workspace rules as for hetis_attn_decode /
+ * from device memory (use hetis_attn_validate).  A call that hands out whole segments stores
+ * the rows inside the Attention kernel; one that hands out single chunks enqueues the store as
+ * a launch of its own ahead of it.  Workspace rules as for hetis_attn_decode /
  * hetis_attn_decode_ws (same size).  Errors: those of hetis_attn_decode.
  */
 int hetis_attn_decode_step(const hetis_attn_shape *shape, const void *q, const void *k_new,

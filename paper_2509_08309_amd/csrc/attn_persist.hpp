@@ -83,6 +83,7 @@ constexpr int kSpinLimit = 1 << 22;     // polls before a wait gives up (far bey
 // whole segment each, then the last sixteenth split at 1/32, 1/64 and 1/128 of a segment.
 constexpr int kLinClasses = 15;
 constexpr int kClasses = kLinClasses + 4;
+static_assert(kClasses + 1 <= 32, "class number + 1 is packed into five bits");
 constexpr int kMaxSegChunks = 32;       // chunks of a segment, at most (one writer lane each)
 constexpr int kPoolSize = 2 * kMaxSegChunks;   // chunk descriptors the LDS pool can hold
 constexpr int kTicketBatch = 8;         // tickets per device atomic while segments are single chunks
@@ -97,6 +98,15 @@ constexpr int kTicketBatch = 8;         // tickets per device atomic while segme
 #define HETIS_POOL_AHEAD 2
 #endif
 enum : int { kItemExists = 1 };
+
+// x / d for x >= 0, d > 0 the same in all lanes: integer division has no instruction of its
+// own and costs about forty; the divisors of the enumeration are powers of two unless a caller
+// of the split entry points chooses otherwise.
+__device__ __forceinline__ int udiv(int x, int d)
+{
+    if ((d & (d - 1)) == 0) return x >> __builtin_ctz(d);
+    return x / d;
+}
 
 // Tokens per chunk of a segment of n_tok tokens: the shorter the segment, the later it is
 // handed out and the finer it is cut, so that the chunks still running when the work runs out
@@ -443,7 +453,7 @@ __device__ __forceinline__ void count_in_and_combine(const AttnParams &p, const 
             continue;
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        merge_partials<D, R>(p, row * p.max_segs, n_segs, p.part_stride, out_row, lane);
+        merge_partials<D, R>(p, row * p.max_segs, n_segs, spread ? p.part_stride : 1, out_row, lane);
         if (lane == 0)
             __hip_atomic_store(p.arrivals + row, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -460,14 +470,17 @@ struct ItemHdr {
 
 __host__ __device__ constexpr size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
-// Table bytes: lens, firstF (int), order (uint16), cls (uint8), then the selected heads, or in
-// pairs mode the head and the sequence of every pair.
+// Table bytes: lens, firstF (int), order (uint16), then the selected heads, or in pairs mode
+// the head and the sequence of every pair.
 __host__ __device__ constexpr size_t persist_table_bytes(int rows, int n_sel, bool pairs)
 {
     return align16((size_t)(2 * rows + 2) * sizeof(int)) +
-           align16((size_t)rows * sizeof(unsigned short)) + align16((size_t)rows) +
+           align16((size_t)rows * sizeof(unsigned short)) +
            align16((size_t)(pairs ? 2 * rows : n_sel) * sizeof(int));
 }
+// Rows of one launch, at most: bounds the static LDS of the enumeration (groups of 64 rows).
+constexpr int kMaxRows = 2048;
+constexpr int kMaxRowGroups = kMaxRows / 64;
 
 template <class Policy, int NW>
 __host__ __device__ constexpr size_t persist_lds_bytes(int rows, int n_sel, bool pairs)
@@ -531,10 +544,9 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // by the size class of that segment, largest first
     unsigned short *order =
         reinterpret_cast<unsigned short *>(smem + align16((size_t)(2 * batch + 2) * sizeof(int)));
-    unsigned char *cls_of = reinterpret_cast<unsigned char *>(order) +
-                            align16((size_t)batch * sizeof(unsigned short));   // class + 1, 0: none
     // KV head of position si in head_ids / of pair b; pairs mode: then the sequence of pair b
-    int *hids = reinterpret_cast<int *>(cls_of + align16((size_t)batch));
+    int *hids = reinterpret_cast<int *>(reinterpret_cast<unsigned char *>(order) +
+                                        align16((size_t)batch * sizeof(unsigned short)));
     int *pseq = hids + batch;
     const int n_sel = PAIRS ? 1 : p.n_sel;    // heads per enumeration row
     const int n_ids = PAIRS ? batch : p.n_sel;
@@ -549,60 +561,148 @@ __global__ __launch_bounds__((NW + 1) * 64)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int seg_tokens = p.seg_tokens;
     const int chunk_tokens = p.chunk_tokens;
-    const bool spread = p.mode == kModeSpread;
+    // kModeSpread is an offer: it is taken up only when some row is long enough to gain from
+    // being worked on by several workgroups (decided below, once the lengths are known)
+    bool spread = p.mode == kModeSpread;
     // kModeSpread: chunks of a row of L tokens (a row without tokens has one, which writes zeros)
     auto row_chunks = [&](int L) {
         if (L <= 0) return 1;
-        const int nF = L / seg_tokens, rt = L - nF * seg_tokens;
+        const int nF = udiv(L, seg_tokens), rt = L - nF * seg_tokens;
         const int ct = chunk_tokens_of(rt, chunk_tokens, seg_tokens);
-        return nF * p.part_stride + (rt + ct - 1) / ct;
+        return nF * p.part_stride + udiv(rt + ct - 1, ct);
     };
 
-    // ---- work enumeration.  All threads fetch the lengths and work out the counts of their
-    // rows (whole segments; size class of the last, shorter segment), four rows a thread and
-    // round so that the loads of a round are in flight together.  Wave 0 then turns the counts
-    // into running counts: lane l owns `per` consecutive rows, adds up their counts, the 64
-    // lane totals go through one in-wave scan, and a second pass over the lane's rows writes
-    // the tables.  `per` is odd so that the lanes' LDS accesses (stride `per` words) fall into
-    // different banks.
-    for (int i = tid; i < n_ids; i += NT) {
-        hids[i] = PAIRS ? p.pair_head[i] : p.head_ids[i];
-        if (PAIRS) pseq[i] = p.pair_seq[i];
+    // ---- work enumeration.  Rows are handled in groups of 64 consecutive rows, one row a lane:
+    // group u * (NW + 1) + wave belongs to round u of that wave, so a thread holds up to UR rows
+    // in registers and one round covers a whole launch.
+    //  1. All threads fetch the lengths of their rows (in pairs mode first the pair's sequence
+    //     and head; the loads of all rounds are in flight together) and work out, per row, the
+    //     number of whole segments and the size class of the last, shorter one.  Inside each
+    //     group a shuffle scan gives the running count of whole segments, and five ballots
+    //     (one per bit of the class number) give every row the set of rows of its class, hence
+    //     its rank among them and the class's count.
+    //  2. The per-(class, group) counts, laid out class-major, and the per-group segment
+    //     totals go through exclusive scans over the workgroup (three elements a thread, a
+    //     shuffle scan per wave, wave totals through LDS).
+    //  3. Every thread writes its rows' table entries: firstF[row] = whole segments before
+    //     the row; order[position] = row, position = rows of larger classes + rows of the
+    //     same class in lower groups + rank.
+    if (!PAIRS) {
+        for (int i0 = tid; i0 < n_ids; i0 += 4 * NT) {
+            int h[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) h[u] = p.head_ids[min(i0 + u * NT, n_ids - 1)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u * NT < n_ids) hids[i0 + u * NT] = h[u];
+        }
     }
     // size class of a last segment of `rt` tokens (0 < rt <= seg_tokens): 0 = the largest
     auto size_class = [&](int rt) {
-        const int j = (16 * rt - 1) / seg_tokens;       // rt in (j/16, (j+1)/16] of a segment
+        const int j = udiv(16 * rt - 1, seg_tokens);    // rt in (j/16, (j+1)/16] of a segment
         if (j >= 1) return kLinClasses - j;
         return kLinClasses + (rt <= (seg_tokens >> 5) ? 1 : 0) + (rt <= (seg_tokens >> 6) ? 1 : 0) +
                (rt <= (seg_tokens >> 7) ? 1 : 0);
     };
-    for (int i0 = tid; i0 < batch; i0 += 4 * NT) {
-        int row[4], L[4];
+    constexpr int UR = (kMaxRows + NT - 1) / NT;        // rounds
+    constexpr int kScanElems = kClasses * kMaxRowGroups + kMaxRowGroups;
+    constexpr int E = (kScanElems + NT - 1) / NT;       // scan elements per thread
+    __shared__ int scan[E * NT];                        // [class][group] counts, then [group] totals
+    __shared__ int wave_tot[2 * (NW + 1)];
+    const int n_groups = (batch + 63) / 64;
+    {
+        // The lengths go to LDS at once and the later steps run as loops that are not unrolled:
+        // the prologue must not need more registers than the streaming loop, or the register
+        // allocation of that loop suffers (measured: 12 % of the kernel's time).
+        int row[UR], L[UR], head[UR];
+        // (a round whose group lies beyond the last row is skipped as a whole: same in all lanes)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = min(i0 + u * NT, batch - 1);
-            row[u] = PAIRS ? p.pair_seq[i] : i;
+        for (int u = 0; u < UR; ++u) {
+            const int i = min(tid + u * NT, batch - 1);
+            row[u] = i;
+            head[u] = 0;
+            if (PAIRS && u * (NW + 1) + wave < n_groups) {
+                row[u] = p.pair_seq[i];
+                head[u] = p.pair_head[i];
+            }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) L[u] = p.seq_lens[row[u]];
+        for (int u = 0; u < UR; ++u) {
+            L[u] = 0;
+            if (u * (NW + 1) + wave < n_groups) L[u] = p.seq_lens[row[u]];
+        }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = i0 + u * NT;
+        for (int u = 0; u < UR; ++u) {
+            const int i = tid + u * NT;
             if (i >= batch) continue;
-            int nF = L[u] > 0 ? L[u] / seg_tokens : 0;
-            const int rt = L[u] > 0 ? L[u] - nF * seg_tokens : 0;
-            int cls = -1;
+            lens[i] = L[u];
+            if (PAIRS) {
+                hids[i] = head[u];
+                pseq[i] = row[u];
+            }
+        }
+        if (spread) {
+            // Single chunks pay a round trip through global memory per chunk result; rows that
+            // a workgroup's own waves finish in about two turns are better off as whole
+            // segments, folded in LDS.  All rows that short: hand out whole segments after all.
+            int longest = 0;
+#pragma unroll
+            for (int u = 0; u < UR; ++u) longest = max(longest, L[u]);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) longest = max(longest, __shfl_xor(longest, off, 64));
+            if (lane == 0) wave_tot[wave] = longest;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < NW + 1; ++w) longest = max(longest, wave_tot[w]);
+            // (readfirstlane: the compiler must see that the decision is the same in all lanes, or
+            // every branch on it, the streaming loop's included, is compiled as a divergent one;
+            // wave_tot is written again only after the next barrier)
+            spread = __builtin_amdgcn_readfirstlane((int)(longest > 2 * NW * chunk_tokens)) != 0;
+        }
+    }
+    // Per row, kept in the row's firstF entry until step 3:
+    // (whole segments of the group's lower rows) << 11 | (rank in its class) << 5 | (class + 1)
+#pragma unroll 1
+    for (int u = 0; u < UR; ++u) {
+        const int i = tid + u * NT;
+        const int g = u * (NW + 1) + wave;              // the row's group
+        if (g >= n_groups) break;                       // same in all lanes: no rows from here on
+        int nF = 0, cls = -1;
+        if (i < batch) {
+            const int L = lens[i];                      // this thread's own write
+            nF = L > 0 ? udiv(L, seg_tokens) : 0;
+            const int rt = L > 0 ? L - nF * seg_tokens : 0;
             if (spread) {
                 // chunks are counted instead of whole segments, and no row is listed
-                nF = row_chunks(L[u]);
+                nF = row_chunks(L);
             } else {
                 if (rt > 0) cls = size_class(rt);
-                if (L[u] <= 0 && p.direct_single) cls = kClasses - 1;   // the segment that writes the zeros
+                if (L <= 0 && p.direct_single) cls = kClasses - 1;   // the segment that writes the zeros
             }
-            lens[i] = L[u];
-            firstF[i] = nF;                             // counts for now; running counts after the scan
-            cls_of[i] = (unsigned char)(cls + 1);
         }
+        int incl = nF, rank = 0;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        // lanes of the same class, from one ballot per bit of the class number
+        unsigned long long same = ~0ull;
+#pragma unroll
+        for (int bit = 0; bit < 5; ++bit) {
+            const bool one = ((cls + 1) >> bit) & 1;
+            const unsigned long long b = __builtin_amdgcn_ballot_w64(one);
+            same &= one ? b : ~b;
+        }
+        rank = __builtin_amdgcn_mbcnt_hi((unsigned)(same >> 32),
+                                         __builtin_amdgcn_mbcnt_lo((unsigned)same, 0));
+        const int count = __builtin_popcountll(same);
+        if (i < batch) firstF[i] = ((incl - nF) << 11) | (rank << 5) | (cls + 1);
+        // class counts of the group: zero, then the last row of every class present writes its own
+        if (lane < kClasses) scan[lane * n_groups + g] = 0;
+        wave_lds_fence();
+        if (cls >= 0 && rank == count - 1) scan[cls * n_groups + g] = count;
+        if (lane == 63) scan[kClasses * n_groups + g] = incl;
     }
     if (tid < 2 * NW) mail[tid].flag = kMailEmpty;
     if (tid == 0) {
@@ -610,74 +710,70 @@ __global__ __launch_bounds__((NW + 1) * 64)
         pool.end = 0;
     }
     __syncthreads();
-    if (wave == 0) {
-        // Running count of whole segments, and a counting sort of the rows by class.  Class
-        // counts travel packed, two to an int (rows < 65536): classes 2j and 2j + 1.
-        constexpr int NP = (kClasses + 1) / 2;
-        const int per = ((batch + 63) / 64) | 1;
-        const int lo = min(lane * per, batch), hi = min(lo + per, batch);
-        auto one_of = [](int cls, int j) { return cls == 2 * j ? 1 : (cls == 2 * j + 1 ? 1 << 16 : 0); };
-        int sumF = 0, sumC[NP];
+    {
+        // exclusive scans of scan[0, n_cls) (class counts) and scan[n_cls, n_all) (segment totals)
+        const int n_cls = kClasses * n_groups, n_all = n_cls + n_groups;
+        int v[E], sumC = 0, sumF = 0;
 #pragma unroll
-        for (int j = 0; j < NP; ++j) sumC[j] = 0;
-        for (int b = lo; b < hi; ++b) {
-            const int cls = (int)cls_of[b] - 1;
-            sumF += firstF[b];
-#pragma unroll
-            for (int j = 0; j < NP; ++j) sumC[j] += one_of(cls, j);
+        for (int e = 0; e < E; ++e) {
+            const int idx = tid * E + e;
+            v[e] = idx < n_all ? scan[idx] : 0;
+            if (idx < n_cls)
+                sumC += v[e];
+            else
+                sumF += v[e];
         }
-        int inclF = sumF, inclC[NP];
-#pragma unroll
-        for (int j = 0; j < NP; ++j) inclC[j] = sumC[j];
+        int inclC = sumC, inclF = sumF;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            const int upF = __shfl_up(inclF, off, 64);
-            int upC[NP];
-#pragma unroll
-            for (int j = 0; j < NP; ++j) upC[j] = __shfl_up(inclC[j], off, 64);
+            const int upC = __shfl_up(inclC, off, 64), upF = __shfl_up(inclF, off, 64);
             if (lane >= off) {
+                inclC += upC;
                 inclF += upF;
-#pragma unroll
-                for (int j = 0; j < NP; ++j) inclC[j] += upC[j];
             }
         }
-        // where this lane's rows of class k go: rows of larger classes (all lanes), then rows
-        // of class k in lower lanes
-        int runF = inclF - sumF, runC[NP];
-        {
-            int before = 0;                         // rows of the classes handled so far
+        if (lane == 63) {
+            wave_tot[wave] = inclC;
+            wave_tot[NW + 1 + wave] = inclF;
+        }
+        __syncthreads();
+        int baseC = inclC - sumC, baseF = inclF - sumF, allC = 0, allF = 0;
 #pragma unroll
-            for (int j = 0; j < NP; ++j) {
-                const int tot = __builtin_amdgcn_readlane(inclC[j], 63);
-                const int excl = inclC[j] - sumC[j];
-                const int lo_half = before + (excl & 0xffff);
-                before += tot & 0xffff;
-                const int hi_half = before + (int)((unsigned)excl >> 16);
-                before += (int)((unsigned)tot >> 16);
-                runC[j] = lo_half | (hi_half << 16);
+        for (int w = 0; w < NW + 1; ++w) {
+            const int tc = wave_tot[w], tf = wave_tot[NW + 1 + w];
+            if (w < wave) {
+                baseC += tc;
+                baseF += tf;
             }
-            if (lane == 63) {
-                firstF[batch] = inclF;
-                // number of listed rows, kept in the table's spare word
-                lens[2 * batch + 1] = before;
+            allC += tc;
+            allF += tf;
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int idx = tid * E + e;
+            if (idx < n_cls) {
+                scan[idx] = baseC;
+                baseC += v[e];
+            } else if (idx < n_all) {
+                scan[idx] = baseF;
+                baseF += v[e];
             }
         }
-        for (int b = lo; b < hi; ++b) {
-            const int cls = (int)cls_of[b] - 1;
-            const int nF = firstF[b];
-            firstF[b] = runF;
-            runF += nF;
-            if (cls >= 0) {
-                int pos = 0;
-#pragma unroll
-                for (int j = 0; j < NP; ++j) {
-                    if (cls == 2 * j) pos = runC[j] & 0xffff;
-                    if (cls == 2 * j + 1) pos = (int)((unsigned)runC[j] >> 16);
-                    runC[j] += one_of(cls, j);
-                }
-                order[pos] = (unsigned short)b;
-            }
+        if (tid == 0) {
+            firstF[batch] = allF;               // whole segments of all rows
+            lens[2 * batch + 1] = allC;         // number of listed rows, kept in the table's spare word
         }
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int u = 0; u < UR; ++u) {
+        const int i = tid + u * NT;
+        const int g = u * (NW + 1) + wave;
+        if (i >= batch) break;
+        const int info = firstF[i];
+        const int cls = (info & 31) - 1, rank = (info >> 5) & 63;
+        firstF[i] = scan[kClasses * n_groups + g] + (int)((unsigned)info >> 11);
+        if (cls >= 0) order[scan[cls * n_groups + g] + rank] = (unsigned short)i;
     }
     __syncthreads();
     const int totalF = firstF[batch];                         // whole segments of all rows
@@ -716,10 +812,10 @@ __global__ __launch_bounds__((NW + 1) * 64)
         const int k = cg - firstF[s.b];                 // chunk of the row
         const int L = lens[s.b];
         const int gc = p.part_stride;
-        const int nF = L > 0 ? L / seg_tokens : 0;
+        const int nF = L > 0 ? udiv(L, seg_tokens) : 0;
         int j, c;
         if (k < nF * gc) {
-            j = k / gc;
+            j = udiv(k, gc);
             c = k - j * gc;
             s.ct = chunk_tokens;
             s.n_tok = chunk_tokens;
@@ -765,15 +861,15 @@ __global__ __launch_bounds__((NW + 1) * 64)
         } else {
             s.b = order[cg - totalF];
             L = lens[s.b];
-            j = L > 0 ? L / seg_tokens : 0;
+            j = L > 0 ? udiv(L, seg_tokens) : 0;
             s.n_tok = L > 0 ? L - j * seg_tokens : 0;
         }
         s.t0 = j * seg_tokens;
         s.ct = chunk_for(s.n_tok);
-        s.ns = max(1, (s.n_tok + s.ct - 1) / s.ct);
+        s.ns = max(1, udiv(s.n_tok + s.ct - 1, s.ct));
         s.g = hids[PAIRS ? s.b : si];
         s.seq = PAIRS ? pseq[s.b] : s.b;
-        const int n_segs = (L + seg_tokens - 1) / seg_tokens;
+        const int n_segs = udiv(max(L, 0) + seg_tokens - 1, seg_tokens);
         s.nseg = n_segs;
         s.out_row = s.seq * p.n_q_heads + s.g * R;
         s.tail = L > 0 && s.t0 + s.n_tok == L;
@@ -813,7 +909,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // (blockIdx.x + k gridDim.x) * NW + v, k = 0, 1, two per streaming wave v (the waves of a
     // workgroup work on neighbouring heads of one chunk position).  Tickets number the segments
     // after these.
-    const bool single_mode = p.mode != kModeSegments;
+    const bool single_mode = p.mode == kModeSplit || spread;
     const bool have_first = (int)blockIdx.x < total;
     const bool step_mode = p.k_new != nullptr;      // never together with single_mode
     // chunks of the first segment that are taken without the pool: the first NW, but not the

@@ -57,6 +57,7 @@ constexpr int kWgsPerCu = 1;    // persistent workgroups per compute unit
 // Rows (sequences, or pairs) per launch: what the persistent kernel's LDS tables hold.  Larger
 // batches run as several launches over slices of the rows.
 constexpr int kMaxPersistBatch = 2048;
+static_assert(kMaxPersistBatch == kMaxRows, "the kernel's enumeration is laid out for this many rows");
 // Arrival counters of a decode workspace (see the workspace layout below).
 constexpr size_t kArrivalSlots = (size_t)1 << 18;
 constexpr size_t kArrivalBytes = kArrivalSlots * sizeof(unsigned int);
