@@ -54,7 +54,10 @@ struct MfmaPolicy {
     static constexpr int kQBytes = R * D * 2;
     static constexpr int kWaveLdsBytes = kStageV + kQBytes;
     static constexpr int kWavesPerEu = 2;             // register budget: 512 / 2 per lane
-    static constexpr int kRing = D_ == 64 ? 4 : 3;   // tile pairs in flight per wave (a third pair at D = 128 was worth 2 % on the grouped-query workloads)
+#ifndef HETIS_MFMA_RING
+#define HETIS_MFMA_RING 3
+#endif
+    static constexpr int kRing = D_ == 64 ? 4 : HETIS_MFMA_RING;   // tile pairs in flight per wave (a third pair at D = 128 was worth 2 % on the grouped-query workloads)
 
     struct Tile {
         uint4 k[KS];

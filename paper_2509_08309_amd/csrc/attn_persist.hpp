@@ -16,20 +16,30 @@
 //
 // Work enumeration: every workgroup loads the row lengths and builds two tables in LDS: the
 // running count of whole segments per row, and the list of the rows that end in a shorter
-// segment, sorted by the size class of that segment (kClasses classes, a counting sort inside
-// one wave).  A flat segment number then decodes into (row, segment, head): whole segments
-// first (binary search in the running counts), then the shorter ones from the largest class
-// to the smallest (a look-up in the sorted list), so the segments handed out last are the
-// short ones, which keeps the end of the launch short.
+// segment, sorted by the size class of that segment (kClasses classes, a counting sort done by
+// the whole workgroup: see the prologue).  A flat segment number then decodes into (row,
+// segment, head): whole segments first (binary search in the running counts), then the shorter
+// ones from the largest class to the smallest (a look-up in the sorted list), so the segments
+// handed out last are the short ones, which keeps the end of the launch short.
 // Work distribution: segment number blockIdx.x belongs to the workgroup without asking (when
-// every segment is a single chunk: one such segment per streaming wave); the rest are tickets from a device counter, drawn by the workgroup's writer wave, which decodes
-// a segment, reserves a fold slot for it and puts its chunks, ready to use, into an LDS pool;
-// the streaming waves take chunks from the pool with an LDS atomic shortly before they finish
-// the chunk at hand.  Which wave or workgroup computes a chunk has no influence on the
-// arithmetic: a row's result is a function of its length and the compile-time constants alone.
+// every segment is a single chunk: two such segments per streaming wave); the rest are tickets
+// from a device counter, drawn by the workgroup's writer wave, which decodes a segment,
+// reserves a fold slot for it and puts its chunks, ready to use, into an LDS pool; the
+// streaming waves take chunks from the pool with an LDS atomic shortly before they finish the
+// chunk at hand.  Which wave or workgroup computes a chunk has no influence on the arithmetic:
+// a row's result is a function of its length and the compile-time constants alone.
 // The ticket counter and a counter of finished workgroups are control words of the call's
 // workspace (AttnParams::control); the workgroup that finishes last sets both back to zero
 // for the next launch.
+// Scheduling modes (AttnParams::mode).  kModeSegments is the above.  kModeSplit: seg_tokens =
+// chunk_tokens, every chunk leaves as a partial result for a separate merge launch.
+// kModeSpread, for launches with few rows, where whole segments would leave most workgroups
+// without work: the unit handed out is the chunk (the enumeration counts chunks per row, in
+// row order, no sorting), chunk results go through the partial buffers in global memory, and
+// the wave that stores the last chunk result of a segment folds that segment's chunks with the
+// operations and in the order of the in-LDS fold (fold_coef / fold_weight / fold_elem are
+// shared), so that the mode never shows in a result.  The kernel takes kModeSpread only when
+// some row is longer than two turns of a workgroup's waves.
 //
 // A workgroup is NW streaming waves plus one writer wave; after the prologue they never
 // meet at a barrier.
@@ -59,15 +69,17 @@
 // iteration bound, so that every wave reaches its end whatever happens; a wait that runs
 // into its bound sets a flag in the workspace's error word, which the host reads with
 // hetis_attn_workspace_status (the launch may then have lost a result).
-// Dynamic LDS: int lens[rows], int firstF[rows + 1], uint16 order[rows], uint8 cls[rows], int
-// hids[n_sel] (pairs mode: hids[rows], pseq[rows]); NW x 2 mailboxes; fold slots; NW per-wave
-// staging areas of Policy::kWaveLdsBytes.
+// Dynamic LDS: int lens[rows], int firstF[rows + 1] (and two spare words), uint16 order[rows],
+// int hids[n_sel] (pairs mode: hids[rows], pseq[rows]); NW x 2 mailboxes; fold slots; NW
+// per-wave staging areas of Policy::kWaveLdsBytes.  Static LDS: the chunk pool and the scan
+// array of the enumeration.
 // Decode step with the store folded in (AttnParams::k_new): the new token's K and V rows go
 // to position L - 1 of the cache inside this launch.  The writer wave stores the rows of a
 // (sequence, head) right before it puts the chunk that contains position L - 1 into the pool,
 // and waits for the stores to complete; the wave that takes the chunk runs on the same
 // compute unit and takes it with an acquire, so it reads the new rows.  That chunk is never
-// one of those taken without the pool.
+// one of those taken without the pool.  (kModeSegments only: the host runs the store as a
+// launch of its own when it offers kModeSpread.)
 // Pairs mode (per-request head subsets, Section 4.2 / 5.2.1): the rows of the enumeration are
 // (sequence, KV head) pairs instead of sequences, each with its own block-table row over a
 // pool of single-head tiles; everything else, the arithmetic included, is shared.
