@@ -59,6 +59,9 @@
  *     between calls.  The control words must be zero before the first call
  *     (hetis_attn_workspace_init, or any zero fill); every launch leaves them at
  *     zero again, so one workspace serves any number of calls in stream order.
+ *     (32-bit word 3 of a workspace records how the last launch handed out its
+ *     work: 1 whole segments, 2 chunks of a split call, 3 single chunks; a
+ *     statistic for tests and tuning.)
  *     Two launches that may run at the same time must not share a workspace.
  *
  * Supported: head_dim in {64, 128}; block_size 16; r in {1, 2, 4, 8}.

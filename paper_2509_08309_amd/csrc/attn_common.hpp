@@ -66,8 +66,9 @@ enum : int { kModeSegments = 0, kModeSplit = 1, kModeSpread = 2 };
 // Control words at the start of a call's workspace.  All are zero between launches: the last
 // workgroup to leave a launch sets the first two back; kCtlError is sticky (only the host
 // clears it) and records that a bounded wait inside a kernel expired, which means that the
-// launch may have dropped or overwritten a result.
-enum : int { kCtlTickets = 0, kCtlGone = 1, kCtlError = 2 };
+// launch may have dropped or overwritten a result.  kCtlLastMode: 1 + the scheduling mode the
+// last launch ran in (a statistic for tests and tuning; nothing reads it on the device).
+enum : int { kCtlTickets = 0, kCtlGone = 1, kCtlError = 2, kCtlLastMode = 3 };
 enum : unsigned { kErrWriterWait = 1u, kErrMailboxWait = 2u, kErrTicketWait = 4u };
 constexpr int kControlBytes = 256;
 

@@ -654,22 +654,38 @@ __global__ __launch_bounds__((NW + 1) * 64)
             }
         }
         if (spread) {
-            // Single chunks pay a round trip through global memory per chunk result; rows that
-            // a workgroup's own waves finish in about two turns are better off as whole
-            // segments, folded in LDS.  All rows that short: hand out whole segments after all.
-            int longest = 0;
+            // Single chunks pay a round trip through global memory per chunk result.  They are
+            // worth it only when whole segments would leave workgroups without work although
+            // there is work to share: when there are fewer segments than workgroups and some
+            // row is longer than a workgroup's own waves finish in one turn.  Otherwise:
+            // whole segments, folded in LDS, after all.
+            int longest = 0, n_segments = 0;
 #pragma unroll
-            for (int u = 0; u < UR; ++u) longest = max(longest, L[u]);
+            for (int u = 0; u < UR; ++u) {
+                longest = max(longest, L[u]);
+                if (tid + u * NT < batch) n_segments += max(1, udiv(max(L[u], 0) + seg_tokens - 1, seg_tokens));
+            }
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) longest = max(longest, __shfl_xor(longest, off, 64));
-            if (lane == 0) wave_tot[wave] = longest;
+            for (int off = 32; off >= 1; off >>= 1) {
+                longest = max(longest, __shfl_xor(longest, off, 64));
+                n_segments += __shfl_xor(n_segments, off, 64);
+            }
+            if (lane == 0) {
+                wave_tot[wave] = longest;
+                wave_tot[NW + 1 + wave] = n_segments;
+            }
             __syncthreads();
+            n_segments = 0;
 #pragma unroll
-            for (int w = 0; w < NW + 1; ++w) longest = max(longest, wave_tot[w]);
+            for (int w = 0; w < NW + 1; ++w) {
+                longest = max(longest, wave_tot[w]);
+                n_segments += wave_tot[NW + 1 + w];
+            }
             // (readfirstlane: the compiler must see that the decision is the same in all lanes, or
             // every branch on it, the streaming loop's included, is compiled as a divergent one;
             // wave_tot is written again only after the next barrier)
-            spread = __builtin_amdgcn_readfirstlane((int)(longest > 2 * NW * chunk_tokens)) != 0;
+            spread = __builtin_amdgcn_readfirstlane((int)(longest > NW * chunk_tokens &&
+                                                          (long long)n_segments * n_sel < (long long)gridDim.x)) != 0;
         }
     }
     // Per row, kept in the row's firstF entry until step 3:
@@ -1178,6 +1194,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             const unsigned gone = __hip_atomic_fetch_add(p.control + kCtlGone, 1u, __ATOMIC_RELAXED,
                                                          __HIP_MEMORY_SCOPE_AGENT);
             if (gone == gridDim.x - 1) {
+                p.control[kCtlLastMode] = 1u + (unsigned)(spread ? (int)kModeSpread : min(p.mode, (int)kModeSplit));
                 __hip_atomic_store(p.control + kCtlTickets, 0u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(p.control + kCtlGone, 0u, __ATOMIC_RELAXED,

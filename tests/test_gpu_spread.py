@@ -21,6 +21,12 @@ LENS = [0, 1, 17, 64, 65, 255, 256, 257, 1000, 1024, 1025, 2047, 3000, 4095, 409
         5000, 8192, 8193, 9000, 12288, 13001]
 
 
+def last_mode(ws):
+    """How the last launch on this workspace handed out its work: 1 whole segments, 3 single chunks."""
+    torch.cuda.synchronize()
+    return int(ws[:16].view(torch.int32)[3].item())
+
+
 def segments_workspace_bytes(shape, n_rows, r, D):
     """Size of a workspace that holds one slot per segment only."""
     segs = (shape.max_blocks_per_seq * 16 + 4095) // 4096
@@ -50,6 +56,11 @@ def test_subset_in_single_chunks_equals_all_heads_in_segments(Hq, Hkv, D, sub):
                              w.block_table, w.seq_lens, np.asarray(sub, dtype=np.int32), w.spec.scale)
     check_rows(part, ref, rows, TOL, "single chunks")
     assert np.array_equal(bits(d.decode(sub)), bits(part))          # deterministic
+    # the two runs really were handed out differently
+    ws = d.workspace(len(sub))
+    assert np.array_equal(bits(d.decode_ws(sub, ws)), bits(part)) and last_mode(ws) == 3
+    ws = d.workspace(Hkv)
+    assert np.array_equal(bits(d.decode_ws(list(range(Hkv)), ws)), bits(full)) and last_mode(ws) == 1
 
 
 @pytest.mark.parametrize("Hq,Hkv,D,heads", [(8, 8, 128, [0, 2, 5, 7]), (16, 2, 128, [1])])
@@ -62,9 +73,11 @@ def test_a_workspace_for_segments_only_gives_the_same_bits(Hq, Hkv, D, heads):
     assert n_small < big.numel()
     small = torch.empty(n_small, dtype=torch.uint8, device=DEV)
     H.check(H.hetis_attn_workspace_init(small, n_small), "workspace_init")
+    assert last_mode(big) == 3
     for _ in range(2):
         out = d.decode_ws(heads, small)
         assert np.array_equal(bits(out), bits(ref))
+    assert last_mode(small) == 1
     # one byte less is not enough for anything
     hid, n = d.heads(heads)
     rc = H.hetis_attn_decode_ws(d.shape, d.q, d.k, d.v, d.bt, d.sl, hid, n, d.scale, d.new_out(),
