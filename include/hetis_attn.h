@@ -205,8 +205,9 @@ int hetis_attn_decode_step_ws(const hetis_attn_shape *shape, const void *q, cons
  * array of HETIS_ATTN_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on
  * holds it from the first use until the process ends).  The call makes no hipMalloc / hipFree
  * and uses no allocating routine; it enqueues one small clearing kernel and the Attention
- * kernels on `stream`.  A shape whose workspace (hetis_attn_decode_workspace_bytes) exceeds the
- * array is refused with HETIS_ERR_WORKSPACE before anything is launched.  All calls on one GPU
+ * kernels on `stream`.  The array plays the part of the caller's workspace of
+ * hetis_attn_decode_ws: a call for which it is too small even when whole segments are handed
+ * out is refused with HETIS_ERR_WORKSPACE before anything is launched.  All calls on one GPU
  * share that GPU's array: calls that may overlap (different streams) race; serialise them, or
  * use hetis_attn_decode_ws.  Errors: NULL, BAD_SHAPE, UNSUPPORTED, BAD_HEADS, WORKSPACE, LAUNCH.
  */

@@ -113,7 +113,7 @@ def test_pairs_full_size(name):
 
 
 def test_more_pairs_than_the_persistent_kernel_holds():
-    """2500 pairs: the simple kernel takes over; same results as the checker."""
+    """2500 pairs: more than one launch holds; they run as two launches over slices of the pairs."""
     rng = np.random.default_rng(66)
     B, Hkv, D = 250, 10, 64
     lens = rng.integers(1, 400, size=B)

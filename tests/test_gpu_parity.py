@@ -275,7 +275,7 @@ def test_profile_events_bracket_the_chunk_kernel():
 
 
 def test_batch_beyond_the_persistent_kernel_limit():
-    # more than 2048 sequences: the simple one-workgroup-per-chunk-slot kernel takes over
+    # more than 2048 sequences: several launches over slices of the sequences
     rng = np.random.default_rng(43)
     lens = rng.integers(0, 300, size=4100).tolist()
     w = W.make_custom(lens, 2, 2, 64, [1], seed=43, max_seq_len=304)
