@@ -1194,7 +1194,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
             const unsigned gone = __hip_atomic_fetch_add(p.control + kCtlGone, 1u, __ATOMIC_RELAXED,
                                                          __HIP_MEMORY_SCOPE_AGENT);
             if (gone == gridDim.x - 1) {
-                p.control[kCtlLastMode] = 1u + (unsigned)(spread ? (int)kModeSpread : min(p.mode, (int)kModeSplit));
+                p.control[kCtlLastMode] =
+                    1u + (unsigned)(spread ? kModeSpread : (p.mode == kModeSplit ? kModeSplit : kModeSegments));
                 __hip_atomic_store(p.control + kCtlTickets, 0u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(p.control + kCtlGone, 0u, __ATOMIC_RELAXED,

@@ -138,3 +138,28 @@ def test_long_rows_few_heads_against_the_checker():
     check_rows(out, ref, selected_rows(w.spec, heads), TOL, "long rows")
     for _ in range(3):
         assert np.array_equal(bits(d.decode(heads)), bits(out))
+
+
+def test_few_rows_of_many_segments_are_handed_out_as_segments():
+    """Fewer than 512 rows, so the host lays the workspace out for single chunks, but more
+    segments than workgroups: the kernel hands out whole segments inside that layout, and the
+    partial results of the rows' segments are merged inside the launch."""
+    lens = [32768] * 20 + [20000] * 19 + [4097, 300, 0]
+    w = W.make_custom(lens, 2, 1, 64, [0], seed=906, device=DEV)           # r = 2
+    d = Dev(w)
+    ws = d.workspace(1)
+    out = d.decode_ws([0], ws)
+    assert last_mode(ws) == 1
+    ref = oracle.attn_decode(w.q.cpu().numpy(), w.k_cache.cpu().numpy(), w.v_cache.cpu().numpy(),
+                             w.block_table, w.seq_lens, np.asarray([0], dtype=np.int32), w.spec.scale)
+    check_rows(out, ref, selected_rows(w.spec, [0]), TOL, "segments inside the chunk layout")
+    # the first sequences alone: few segments, single chunks, same bits
+    k = 12
+    w2 = W.Workload(W.WorkloadSpec("custom", k, 2, 1, 64, (0,), 906, "fixed", (tuple(lens[:k]),), max(lens)),
+                    w.seq_lens[:k], w.block_table[:k], w.num_blocks, w.q[:k], w.k_cache, w.v_cache,
+                    np.asarray([0], dtype=np.int32))
+    d2 = Dev(w2)
+    ws2 = d2.workspace(1)
+    out2 = d2.decode_ws([0], ws2)
+    assert last_mode(ws2) == 3
+    assert np.array_equal(bits(out2), bits(out)[:k])
