@@ -85,23 +85,25 @@ struct MfmaPolicy {
 
     // Query rows: fetched as raw bytes one item ahead (kQBytes over 64 lanes), then passed
     // through the wave's LDS area into operand layout with zero columns for heads >= r.
+    // (two named members instead of an array: the array form was kept in scratch memory when it
+    // had two elements, and a scratch store in a streaming wave is a global store like any other)
     static constexpr int kQVec = (kQBytes / 16 + 63) / 64;
+    static_assert(kQVec <= 2, "query rows of one group: at most 2 x 64 x 16 bytes");
     struct QueryPrefetch {
-        uint4 raw[kQVec];
+        u32x4 raw0, raw1;
     };
     __device__ static __forceinline__ void q_prefetch(QueryPrefetch &pre, const __half *rows, int lane)
     {
-        const uint4 *src = reinterpret_cast<const uint4 *>(rows);
-#pragma unroll
-        for (int i = 0; i < kQVec; ++i) pre.raw[i] = src[min(lane + 64 * i, kQBytes / 16 - 1)];
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(rows);
+        pre.raw0 = src[min(lane, kQBytes / 16 - 1)];
+        pre.raw1 = kQVec > 1 ? src[min(lane + 64, kQBytes / 16 - 1)] : u32x4{0u, 0u, 0u, 0u};
     }
     __device__ static __forceinline__ void q_commit(Query &q, const QueryPrefetch &pre,
                                                     unsigned char *stage, int lane)
     {
-        uint4 *dst = reinterpret_cast<uint4 *>(stage + kStageV);
-#pragma unroll
-        for (int i = 0; i < kQVec; ++i)
-            if (lane + 64 * i < kQBytes / 16) dst[lane + 64 * i] = pre.raw[i];
+        u32x4 *dst = reinterpret_cast<u32x4 *>(stage + kStageV);
+        if (lane < kQBytes / 16) dst[lane] = pre.raw0;
+        if (kQVec > 1 && lane + 64 < kQBytes / 16) dst[lane + 64] = pre.raw1;
         const int j = lane & 15;
         const __half *src =
             reinterpret_cast<const __half *>(stage + kStageV) + min(j, R - 1) * D + (lane >> 4) * 8;

@@ -387,27 +387,7 @@ __device__ __forceinline__ void fold_segment_from_chunks(const AttnParams &p, in
 // long as the streaming waves of a workgroup need to produce the next results.
 template <int NW>
 struct Arrivals {
-    int n = 0;
-    int dest[NW], parts[NW], out_row[NW], len[NW];
-    __device__ __forceinline__ void add(int d, int np, int o, int l)
-    {
-#pragma unroll
-        for (int i = 0; i < NW; ++i)
-            if (i == n) {
-                dest[i] = d;
-                parts[i] = np;
-                out_row[i] = o;
-                len[i] = l;
-            }
-        ++n;
-    }
-    __device__ __forceinline__ int pick(const int (&a)[NW], int i) const
-    {
-        int v = a[0];
-#pragma unroll
-        for (int k = 1; k < NW; ++k) v = i == k ? a[k] : v;
-        return v;
-    }
+    int dest[NW], parts[NW], out_row[NW], len[NW];     // lives in LDS, used by the writer wave only
 };
 
 // Counters (AttnParams::arrivals), n_rows = (enumeration rows) x (selected heads) of the launch:
@@ -418,27 +398,27 @@ struct Arrivals {
 // result and counts it in for the row in turn.
 template <int D, int R, int NW>
 __device__ __forceinline__ void count_in_and_combine(const AttnParams &p, const Arrivals<NW> &arr,
-                                                     bool spread, int n_rows, int lane)
+                                                     int n_arr, bool spread, int n_rows, int lane)
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);                   // every store of this wave has completed
     const int seg_slots = p.max_segs / p.part_stride;   // segments per row (kModeSpread)
     unsigned old = 0;
-    if (lane < arr.n) {
-        const int d = arr.pick(arr.dest, lane);
+    if (lane < n_arr) {
+        const int d = arr.dest[lane];
         const int64_t row = d / p.max_segs;          // (enumeration row, head)
         const int64_t counter = spread ? n_rows + row * seg_slots + (d % p.max_segs) / p.part_stride : row;
         old = __hip_atomic_fetch_add(p.arrivals + counter, 1u, __ATOMIC_RELAXED,
                                      __HIP_MEMORY_SCOPE_AGENT);
     }
-    for (int i = 0; i < arr.n; ++i) {
+    for (int i = 0; i < n_arr; ++i) {
         const int before = __builtin_amdgcn_readlane((int)old, i);
-        const int d = arr.pick(arr.dest, i);
+        const int d = __builtin_amdgcn_readfirstlane(arr.dest[i]);
         const int64_t row = d / p.max_segs;
-        const int64_t out_row = arr.pick(arr.out_row, i);
-        int n_segs = arr.pick(arr.parts, i);
+        const int64_t out_row = __builtin_amdgcn_readfirstlane(arr.out_row[i]);
+        int n_segs = __builtin_amdgcn_readfirstlane(arr.parts[i]);
         if (spread) {
-            const int L = arr.pick(arr.len, i);
+            const int L = __builtin_amdgcn_readfirstlane(arr.len[i]);
             const int j = (d % p.max_segs) / p.part_stride;
             const int n_tok = min(p.seg_tokens, L - j * p.seg_tokens);
             const int ct = chunk_tokens_of(n_tok, p.chunk_tokens, p.seg_tokens);
@@ -564,6 +544,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
     const int n_ids = PAIRS ? batch : p.n_sel;
     unsigned char *after_tables = smem + persist_table_bytes(batch, p.n_sel, PAIRS);
     __shared__ ChunkPool pool;
+    __shared__ Arrivals<NW> arrivals;       // writer wave only
     Mail *mail = reinterpret_cast<Mail *>(after_tables);             // [NW][2]
     Fold *fold = reinterpret_cast<Fold *>(after_tables + 2 * NW * sizeof(Mail));
     unsigned char *staging = reinterpret_cast<unsigned char *>(fold + NS);
@@ -1105,7 +1086,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             // ---- results
             // partial results stored in this pass that are merged inside this launch: counted in
             // after the pass, when their mailboxes have been handed back
-            Arrivals<NW> arrivals;
+            int n_arr = 0;
 #pragma unroll
             for (int v = 0; v < NW; ++v) {
                 if (done_mask & (1 << v)) continue;
@@ -1122,9 +1103,13 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 if (kind != kKindFold) {
                     if (kind == kKindPartial && p.arrivals) {
                         store_partial_coherent<D, R>(mb.o, mb.lse, nullptr, dest, p, lane, spread);
-                        arrivals.add(dest, __builtin_amdgcn_readfirstlane(mb.nseg),
-                                     __builtin_amdgcn_readfirstlane(mb.out_row),
-                                     __builtin_amdgcn_readfirstlane(mb.len));
+                        if (lane == 0) {
+                            arrivals.dest[n_arr] = dest;
+                            arrivals.parts[n_arr] = mb.nseg;
+                            arrivals.out_row[n_arr] = mb.out_row;
+                            arrivals.len[n_arr] = mb.len;
+                        }
+                        ++n_arr;
                     } else {
                         store_result<D, R>(mb.o, mb.lse, nullptr, kind, dest, p, lane);
                     }
@@ -1167,8 +1152,13 @@ __global__ __launch_bounds__((NW + 1) * 64)
                         const int fdest = __builtin_amdgcn_readfirstlane(fs.dest);
                         if (fkind == kKindPartial && p.arrivals) {
                             store_partial_coherent<D, R>(fs.acc, fs.M, fs.W, fdest, p, lane, false);
-                            arrivals.add(fdest, __builtin_amdgcn_readfirstlane(fs.nseg),
-                                         __builtin_amdgcn_readfirstlane(fs.out_row), 0);
+                            if (lane == 0) {
+                                arrivals.dest[n_arr] = fdest;
+                                arrivals.parts[n_arr] = fs.nseg;
+                                arrivals.out_row[n_arr] = fs.out_row;
+                                arrivals.len[n_arr] = 0;
+                            }
+                            ++n_arr;
                         } else {
                             store_result<D, R>(fs.acc, fs.M, fs.W, fkind, fdest, p, lane);
                         }
@@ -1179,7 +1169,10 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 next_box[v] ^= 1;
                 progressed = true;
             }
-            if (arrivals.n > 0) count_in_and_combine<D, R, NW>(p, arrivals, spread, batch * n_sel, lane);
+            if (n_arr > 0) {
+                wave_lds_fence();           // lane 0's entries are read by all lanes
+                count_in_and_combine<D, R, NW>(p, arrivals, n_arr, spread, batch * n_sel, lane);
+            }
             if (progressed) {
                 idle = 0;
             } else {
@@ -1206,12 +1199,16 @@ __global__ __launch_bounds__((NW + 1) * 64)
     }
 
     // ---------------------------------------------------------------- streaming waves
+    // (no padding bytes anywhere: a struct with holes is copied through scratch memory, and a
+    // scratch store in a streaming wave is a global store like any other)
     struct Slot {
+        int64_t head_off;
         ItemHdr h;
         int ids;            // lane i: physical block of the chunk's i-th tile
-        int64_t head_off;
-        bool exists;
+        int exists;
     };
+    static_assert(sizeof(ItemHdr) == 12 * sizeof(int) && sizeof(Slot) == 8 + sizeof(ItemHdr) + 8,
+                  "Slot has no padding");
     // chunk descriptor -> the wave's (uniform) bookkeeping, and the load of its block ids
     auto fill = [&](const ChunkDesc &d, Slot &s) {
         const int flags = __builtin_amdgcn_readfirstlane(d.flags);
@@ -1226,7 +1223,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         s.h.nseg = __builtin_amdgcn_readfirstlane(d.nseg);
         s.h.out_row = __builtin_amdgcn_readfirstlane(d.out_row);
         s.h.len = __builtin_amdgcn_readfirstlane(d.len);
-        s.exists = (flags & kItemExists) != 0;
+        s.exists = (flags & kItemExists) != 0 ? 1 : 0;
         s.h.nblk = s.exists ? (n_tok + kBlockTokens - 1) / kBlockTokens : 0;
         s.h.rem = n_tok & (kBlockTokens - 1);
         s.head_off = PAIRS ? 0 : (int64_t)s.h.g * p.stride_head;   // pairs: single-head tiles
