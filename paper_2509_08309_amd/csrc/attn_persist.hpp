@@ -28,9 +28,9 @@
 // streaming waves take chunks from the pool with an LDS atomic shortly before they finish the
 // chunk at hand.  Which wave or workgroup computes a chunk has no influence on the arithmetic:
 // a row's result is a function of its length and the compile-time constants alone.
-// The ticket counter and a counter of finished workgroups are control words of the call's
-// workspace (AttnParams::control); the workgroup that finishes last sets both back to zero
-// for the next launch.
+// The ticket counter and a counter of workgroups that will draw no more are control words of
+// the call's workspace (AttnParams::control); the last workgroup to count itself out sets both
+// back to zero for the next launch.
 // Scheduling modes (AttnParams::mode).  kModeSegments is the above.  kModeSplit: seg_tokens =
 // chunk_tokens, every chunk leaves as a partial result for a separate merge launch.
 // kModeSpread, for launches with few rows, where whole segments would leave most workgroups
@@ -949,6 +949,19 @@ __global__ __launch_bounds__((NW + 1) * 64)
         int pool_end = 0;                 // entries published so far
         unsigned busy = 0;                // fold slots in use
         bool exhausted = total <= n_fixed;            // no segment left to draw
+        // A workgroup that will draw no more tickets counts itself out at once, not when it
+        // ends: the answer (was it the last one?) is needed only at the end, and by then the
+        // atomic's round trip, which would otherwise be the last thing the kernel waits for,
+        // is long over.  The last workgroup to count itself out rearms both counters; that is
+        // safe while others still compute, since none of them draws again.
+        bool counted_out = false;
+        unsigned gone_before = 0;                     // lane 0: workgroups counted out before this one
+        auto count_out = [&]() {
+            if (lane == 0)
+                gone_before = __hip_atomic_fetch_add(p.control + kCtlGone, 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+            counted_out = true;
+        };
         bool first = have_first && !single_mode;      // the next segment to publish is the workgroup's first
         bool closed = false;              // the "no work left" entries have been published
         // Segments drawn and decoded (one per lane, lanes [pend_i, pend_n) still to publish)
@@ -980,6 +993,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
         };
         while (done_mask != (1 << NW) - 1 && idle < kSpinLimit) {
             bool progressed = false;
+            if (exhausted && !counted_out) count_out();
             // ---- keep the chunk pool ahead of the streaming waves
             const int taken = __builtin_amdgcn_readfirstlane(
                 __hip_atomic_load(&pool.next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
@@ -1180,13 +1194,10 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 __builtin_amdgcn_s_sleep(4);
             }
         }
-        // every streaming wave of this workgroup is done, so no more tickets will be drawn
-        // here: count the workgroup out; the last one to leave rearms both counters
+        if (!counted_out) count_out();        // (only after a wait that gave up)
         if (lane == 0) {
             if (done_mask != (1 << NW) - 1) report_error(p.control, kErrWriterWait);
-            const unsigned gone = __hip_atomic_fetch_add(p.control + kCtlGone, 1u, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-            if (gone == gridDim.x - 1) {
+            if (gone_before == gridDim.x - 1) {
                 p.control[kCtlLastMode] =
                     1u + (unsigned)(spread ? kModeSpread : (p.mode == kModeSplit ? kModeSplit : kModeSegments));
                 __hip_atomic_store(p.control + kCtlTickets, 0u, __ATOMIC_RELAXED,
