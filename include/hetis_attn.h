@@ -126,8 +126,8 @@ const char *hetis_attn_status_string(int status);
  *   scale        host, normally 1/sqrt(D)
  *   out          fp16 [B, Hq, D]; rows of unselected heads are left untouched
  * The tokens of a (sequence, head) are cut, from token 0, into segments of 4096
- * tokens and these into chunks of 256 tokens (a sequence's last, shorter
- * segment into finer ones); chunk results are
+ * tokens and these into chunks (256 tokens for r < 4, 512 for r >= 4; a
+ * sequence's last, shorter segment into finer ones); chunk results are
  * combined in ascending order into segment results, segment results into the
  * row.  The cut and the order depend on the sequence's length and these
  * constants only.  How the pieces are handed to the hardware does not change a

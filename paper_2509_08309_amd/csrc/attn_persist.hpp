@@ -109,6 +109,10 @@ constexpr int kTicketBatch = 8;         // tickets per device atomic while segme
 #ifndef HETIS_POOL_AHEAD
 #define HETIS_POOL_AHEAD 2
 #endif
+// ... until so many segments are left to draw, in quarters of the number of workgroups.
+#ifndef HETIS_LATE_SEGMENTS_X4
+#define HETIS_LATE_SEGMENTS_X4 2
+#endif
 enum : int { kItemExists = 1 };
 
 // x / d for x >= 0, d > 0 the same in all lanes: integer division has no instruction of its
@@ -1011,7 +1015,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 ahead = n_draw;
             } else {
                 n_draw = max(1, min(kTicketBatch, chunk_tokens / max(last_tok, 1)));
-                ahead = max(left > (long long)gridDim.x / 4 ? HETIS_POOL_AHEAD : 1, n_draw);
+                ahead = max(4 * left > (long long)gridDim.x * HETIS_LATE_SEGMENTS_X4 ? HETIS_POOL_AHEAD : 1, n_draw);
             }
             if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
                 unsigned t = 0;

@@ -25,7 +25,7 @@ namespace hetis {
 #define HETIS_DECODE_CHUNK_TOKENS 256
 #endif
 #ifndef HETIS_DECODE_CHUNK_TOKENS_GQA
-#define HETIS_DECODE_CHUNK_TOKENS_GQA 256
+#define HETIS_DECODE_CHUNK_TOKENS_GQA 512
 #endif
 #ifndef HETIS_DECODE_SEG_TOKENS
 #define HETIS_DECODE_SEG_TOKENS 4096

@@ -178,8 +178,8 @@ def test_workspace_sizes(lib):
     assert H.hetis_attn_decode_pairs_workspace_bytes(long, 777) \
         == (0, fixed + rows * 128 * 4 + up(rows * 4))
     # fewer than 512 rows: the work is handed out in single chunks, whose results all pass
-    # through the workspace: one slot per chunk of a whole segment (4096 / 256 = 16) and
-    # segment the block table allows
+    # through the workspace: one slot per chunk of a whole segment (4096 / 256 = 16, grouped-query
+    # shapes 4096 / 512 = 8) and segment the block table allows
     rows = 4 * 4 * 16
     assert H.hetis_attn_decode_workspace_bytes(H.make_shape(4, 8, 8, 64, 16), 4) \
         == (0, fixed + rows * 64 * 4 + up(rows * 4))
@@ -192,7 +192,7 @@ def test_workspace_sizes(lib):
     rows = 77 * 8 * 16
     assert H.hetis_attn_decode_pairs_workspace_bytes(long, 77) \
         == (0, fixed + rows * 128 * 4 + up(rows * 4))
-    rows = 16 * 3 * 2 * 16 * 8
+    rows = 16 * 3 * 2 * 8 * 8
     assert H.hetis_attn_decode_workspace_bytes(H.make_shape(16, 64, 8, 128, 512), 3) \
         == (0, fixed + rows * 128 * 4 + up(rows * 4))
     assert H.hetis_attn_decode_workspace_bytes(s, 0)[0] == binding.HETIS_ERR_BAD_HEADS
