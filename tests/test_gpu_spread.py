@@ -163,3 +163,21 @@ def test_few_rows_of_many_segments_are_handed_out_as_segments():
     out2 = d2.decode_ws([0], ws2)
     assert last_mode(ws2) == 3
     assert np.array_equal(bits(out2), bits(out)[:k])
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(2, 2, 64), (8, 2, 128), (16, 2, 64)])
+def test_one_or_two_very_long_rows(Hq, Hkv, D):
+    """A launch of a handful of rows of tens of segments each: single chunks all over the device,
+    per-segment folds, one merge per row."""
+    lens = [100000, 70001]
+    w = W.make_custom(lens, Hq, Hkv, D, [0, 1], seed=907, device=DEV)
+    d = Dev(w)
+    ws = d.workspace(2)
+    out = d.decode_ws([0, 1], ws)
+    assert last_mode(ws) == 3
+    ref = oracle.attn_decode(w.q.cpu().numpy(), w.k_cache.cpu().numpy(), w.v_cache.cpu().numpy(),
+                             w.block_table, w.seq_lens, np.asarray([0, 1], dtype=np.int32), w.spec.scale)
+    check_rows(out, ref, selected_rows(w.spec, [0, 1]), TOL, "very long rows")
+    one = d.decode([1])
+    rows = selected_rows(w.spec, [1])
+    assert np.array_equal(bits(one)[:, rows], bits(out)[:, rows])
