@@ -11,6 +11,10 @@ namespace hetis {
 typedef unsigned int kv_u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kKvBlockTokens = 16;
+// Head rows a thread of the row kernel loads before it stores the first of them.
+#ifndef HETIS_KV_ROWS_IN_FLIGHT
+#define HETIS_KV_ROWS_IN_FLIGHT 8
+#endif
 // Workgroups of the tile-copy kernel: 256 CUs x 8 resident workgroups of 4 waves.
 constexpr int kKvCopyMaxWorkgroups = 2048;
 
@@ -54,10 +58,10 @@ __global__ void __launch_bounds__(256) kv_rows_kernel(KvRowParams p)
     uint4 *rows = is_v ? p.rows_v : p.rows_k;
     const int64_t cache_row = blk * p.stride_block + (int64_t)slot * LR + c;
     const int64_t rows_row = n * p.n_kv_heads * LR + c;
-    // heads in batches of four: the four loads of a batch are in flight together before the
+    // heads in batches of U: the loads of a batch are in flight together before the
     // first store (a thread that alternates one load and one store leaves the memory system
     // with a single access per thread in flight)
-    constexpr int U = 4;
+    constexpr int U = HETIS_KV_ROWS_IN_FLIGHT;
     for (int s0 = blockIdx.y; s0 < p.n_sel; s0 += U * gridDim.y) {
         int g[U];
         bool ok[U];
