@@ -359,6 +359,28 @@ int hetis_attn_decode_pairs_ws(const hetis_attn_shape *shape, const void *q, con
                                const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * One decode step of the pairs form in one call (Section 5.1): hetis_kv_append_pairs
+ * (hetis_kv.h) followed by hetis_attn_decode_pairs.  k_new, v_new fp16 [B, Hkv, D]: pair p
+ * stores the rows of (pair_seq[p], pair_head[p]) at position seq_lens[b] - 1 of its own
+ * block-table row (length 0 stores nothing); k_tiles, v_tiles are read and written.  Pools
+ * and `out` end up as the two calls leave them, bit for bit; what is read from device
+ * memory is not range-checked (use hetis_attn_validate_pairs).  A (sequence, head) listed
+ * twice with different block-table rows stores the rows through both.  Workspace rules,
+ * sizes and errors as for hetis_attn_decode_pairs / hetis_attn_decode_pairs_ws.
+ */
+int hetis_attn_decode_pairs_step(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                                 const void *v_new, void *k_tiles, void *v_tiles,
+                                 const int32_t *block_table, const int32_t *seq_lens,
+                                 const int32_t *pair_seq, const int32_t *pair_head,
+                                 int32_t n_pairs, float scale, void *out, void *stream);
+int hetis_attn_decode_pairs_step_ws(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                                    const void *v_new, void *k_tiles, void *v_tiles,
+                                    const int32_t *block_table, const int32_t *seq_lens,
+                                    const int32_t *pair_seq, const int32_t *pair_head,
+                                    int32_t n_pairs, float scale, void *out, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
 /* Debug helper like hetis_attn_validate for the pairs form: sequence ids, head ids, lengths
  * and every tile id a call would read (0 <= id < num_tiles). */
 int hetis_attn_validate_pairs(const hetis_attn_shape *shape, const int32_t *block_table,

@@ -9,7 +9,7 @@ its absence is an error, never a fallback.
 from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     HetisError, check, hetis_attn_decode, hetis_attn_decode_pairs, hetis_attn_decode_split,
-    hetis_attn_decode_static, hetis_attn_decode_step, hetis_attn_decode_step_ws, hetis_attn_decode_ws, hetis_attn_decode_pairs_ws, hetis_attn_decode_split_ws,
+    hetis_attn_decode_static, hetis_attn_decode_step, hetis_attn_decode_step_ws, hetis_attn_decode_ws, hetis_attn_decode_pairs_ws, hetis_attn_decode_pairs_step, hetis_attn_decode_pairs_step_ws, hetis_attn_decode_split_ws,
     hetis_attn_decode_workspace_bytes, hetis_attn_decode_pairs_workspace_bytes,
     hetis_attn_workspace_init, hetis_attn_workspace_status, hetis_attn_reserve_workspace,
     hetis_attn_validate_pairs, hetis_attn_merge, hetis_attn_profile_events,

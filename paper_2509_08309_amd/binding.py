@@ -105,6 +105,11 @@ def load(build_if_missing: bool = False):
     lib.hetis_attn_decode_split_ws.restype = C.c_int
     lib.hetis_attn_decode_split_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32, f32, i32, i32,
                                                vp, vp, vp, vp]
+    lib.hetis_attn_decode_pairs_step.restype = C.c_int
+    lib.hetis_attn_decode_pairs_step.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
+    lib.hetis_attn_decode_pairs_step_ws.restype = C.c_int
+    lib.hetis_attn_decode_pairs_step_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp,
+                                                    vp, C.c_size_t, vp]
     lib.hetis_attn_decode_pairs_ws.restype = C.c_int
     lib.hetis_attn_decode_pairs_ws.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp,
                                                C.c_size_t, vp]
@@ -328,6 +333,25 @@ def hetis_attn_decode_pairs_ws(shape, q, k_tiles, v_tiles, block_table, seq_lens
                                              _ptr(pair_head), int(n_pairs), float(scale),
                                              _ptr(out), _ptr(workspace), int(workspace_bytes),
                                              _stream(stream))
+
+
+def hetis_attn_decode_pairs_step(shape, q, k_new, v_new, k_tiles, v_tiles, block_table, seq_lens,
+                                 pair_seq, pair_head, n_pairs, scale, out, stream=None) -> int:
+    return load().hetis_attn_decode_pairs_step(C.byref(shape), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                               _ptr(k_tiles), _ptr(v_tiles), _ptr(block_table),
+                                               _ptr(seq_lens), _ptr(pair_seq), _ptr(pair_head),
+                                               int(n_pairs), float(scale), _ptr(out), _stream(stream))
+
+
+def hetis_attn_decode_pairs_step_ws(shape, q, k_new, v_new, k_tiles, v_tiles, block_table,
+                                    seq_lens, pair_seq, pair_head, n_pairs, scale, out, workspace,
+                                    workspace_bytes, stream=None) -> int:
+    return load().hetis_attn_decode_pairs_step_ws(C.byref(shape), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                  _ptr(k_tiles), _ptr(v_tiles), _ptr(block_table),
+                                                  _ptr(seq_lens), _ptr(pair_seq), _ptr(pair_head),
+                                                  int(n_pairs), float(scale), _ptr(out),
+                                                  _ptr(workspace), int(workspace_bytes),
+                                                  _stream(stream))
 
 
 def hetis_attn_validate_pairs(shape, block_table, seq_lens, pair_seq, pair_head, n_pairs,

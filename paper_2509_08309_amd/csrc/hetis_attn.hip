@@ -483,7 +483,7 @@ using namespace hetis;
 
 extern "C" {
 
-int hetis_attn_version(void) { return 200; }
+int hetis_attn_version(void) { return 201; }
 
 const char *hetis_attn_status_string(int status)
 {
@@ -652,7 +652,8 @@ int hetis_attn_decode_pairs_workspace_bytes(const hetis_attn_shape *shape, int32
     return HETIS_OK;
 }
 
-static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
+static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                               const void *v_new, bool step, const void *k_tiles,
                                const void *v_tiles, const int32_t *block_table,
                                const int32_t *seq_lens, const int32_t *pair_seq,
                                const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
@@ -662,6 +663,7 @@ static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, con
     if (!shape || !q || !k_tiles || !v_tiles || !block_table || !seq_lens || !pair_seq ||
         !pair_head || !out)
         return HETIS_ERR_NULL;
+    if (step && (!k_new || !v_new)) return HETIS_ERR_NULL;
     int rc = check_pairs(shape, n_pairs, &c);
     if (rc != HETIS_OK) return rc;
     const WsLayout lay = choose_layout(shape, n_pairs, 1, c.group, owned ? SIZE_MAX : workspace_bytes);
@@ -681,6 +683,18 @@ static int decode_pairs_common(const hetis_attn_shape *shape, const void *q, con
     p.pair_seq = pair_seq;
     p.pair_head = pair_head;
     apply_layout(p, lay, c.group, workspace);
+    if (step) {
+        if (lay.spread) {
+            // as in decode_common: the store runs as a launch of its own ahead of the Attention launch
+            rc = hetis_kv_append_pairs(shape, k_new, v_new, block_table, seq_lens, pair_seq, pair_head,
+                                       n_pairs, INT64_MAX, const_cast<void *>(k_tiles),
+                                       const_cast<void *>(v_tiles), stream);
+            if (rc != HETIS_OK) return rc;
+        } else {
+            p.k_new = static_cast<const __half *>(k_new);
+            p.v_new = static_cast<const __half *>(v_new);
+        }
+    }
     rc = launch_chunks(p, shape->head_dim, c.group, n_pairs, st);
     if (rc != HETIS_OK) return rc;
     return hipGetLastError() == hipSuccess ? HETIS_OK : HETIS_ERR_LAUNCH;
@@ -692,8 +706,9 @@ int hetis_attn_decode_pairs(const hetis_attn_shape *shape, const void *q, const 
                             const int32_t *pair_head, int32_t n_pairs, float scale, void *out,
                             void *stream)
 {
-    return decode_pairs_common(shape, q, k_tiles, v_tiles, block_table, seq_lens, pair_seq,
-                               pair_head, n_pairs, scale, out, nullptr, 0, true, stream);
+    return decode_pairs_common(shape, q, nullptr, nullptr, false, k_tiles, v_tiles, block_table,
+                               seq_lens, pair_seq, pair_head, n_pairs, scale, out, nullptr, 0, true,
+                               stream);
 }
 
 int hetis_attn_decode_pairs_ws(const hetis_attn_shape *shape, const void *q, const void *k_tiles,
@@ -703,9 +718,33 @@ int hetis_attn_decode_pairs_ws(const hetis_attn_shape *shape, const void *q, con
                                void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!workspace) return HETIS_ERR_NULL;
-    return decode_pairs_common(shape, q, k_tiles, v_tiles, block_table, seq_lens, pair_seq,
-                               pair_head, n_pairs, scale, out, workspace, workspace_bytes, false,
+    return decode_pairs_common(shape, q, nullptr, nullptr, false, k_tiles, v_tiles, block_table,
+                               seq_lens, pair_seq, pair_head, n_pairs, scale, out, workspace,
+                               workspace_bytes, false, stream);
+}
+
+int hetis_attn_decode_pairs_step(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                                 const void *v_new, void *k_tiles, void *v_tiles,
+                                 const int32_t *block_table, const int32_t *seq_lens,
+                                 const int32_t *pair_seq, const int32_t *pair_head,
+                                 int32_t n_pairs, float scale, void *out, void *stream)
+{
+    return decode_pairs_common(shape, q, k_new, v_new, true, k_tiles, v_tiles, block_table,
+                               seq_lens, pair_seq, pair_head, n_pairs, scale, out, nullptr, 0, true,
                                stream);
+}
+
+int hetis_attn_decode_pairs_step_ws(const hetis_attn_shape *shape, const void *q, const void *k_new,
+                                    const void *v_new, void *k_tiles, void *v_tiles,
+                                    const int32_t *block_table, const int32_t *seq_lens,
+                                    const int32_t *pair_seq, const int32_t *pair_head,
+                                    int32_t n_pairs, float scale, void *out, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return HETIS_ERR_NULL;
+    return decode_pairs_common(shape, q, k_new, v_new, true, k_tiles, v_tiles, block_table,
+                               seq_lens, pair_seq, pair_head, n_pairs, scale, out, workspace,
+                               workspace_bytes, false, stream);
 }
 
 int hetis_attn_workspace_init(void *workspace, size_t bytes, void *stream)

@@ -370,6 +370,24 @@ def test_pairs_null_pointers(lib, arg):
     assert decode_pairs(good(), **{arg: None}) == binding.HETIS_ERR_NULL
 
 
+def test_pairs_step_argument_errors(lib):
+    s = good()
+
+    def call(kn=P, vn=P, ps=P, n_pairs=5, ws=None):
+        if ws is None:
+            return H.hetis_attn_decode_pairs_step(s, P, kn, vn, P, P, P, P, ps, P, n_pairs, 0.125, P, 0)
+        return H.hetis_attn_decode_pairs_step_ws(s, P, kn, vn, P, P, P, P, ps, P, n_pairs, 0.125, P,
+                                                 ws[0], ws[1], 0)
+    assert call(kn=None) == binding.HETIS_ERR_NULL
+    assert call(vn=None) == binding.HETIS_ERR_NULL
+    assert call(ps=None) == binding.HETIS_ERR_NULL
+    assert call(n_pairs=-1) == binding.HETIS_ERR_BAD_SHAPE
+    assert call(n_pairs=0) == binding.HETIS_OK                          # nothing to do, no HIP call
+    assert call(ws=(None, 256)) == binding.HETIS_ERR_NULL
+    assert call(ws=(WS, 128)) == binding.HETIS_ERR_WORKSPACE
+    assert call(kn=None, ws=(WS, 256)) == binding.HETIS_ERR_NULL
+
+
 def test_pairs_argument_errors(lib):
     assert decode_pairs(good(), n_pairs=-1) == binding.HETIS_ERR_BAD_SHAPE
     assert decode_pairs(good(), n_pairs=65536) == binding.HETIS_ERR_UNSUPPORTED

@@ -217,3 +217,66 @@ def test_append_pairs_skips_what_points_outside():
     assert np.array_equal(bits(k), ref_k) and np.array_equal(bits(v), ref_v)
     # only the pair of sequence 2 was stored (sequence 3 is empty)
     assert int((bits(k) != bits(pw.k_tiles)).any(axis=-1).sum()) == 1
+
+
+@pytest.mark.parametrize("name", ["few", "many", "c3_13b_subset", "c5_70b_gqa"])
+def test_decode_pairs_step_equals_append_pairs_then_decode_pairs(name):
+    """One call for the decode step of the pairs form: pools and outputs bit-identical to
+    hetis_kv_append_pairs + hetis_attn_decode_pairs, and within tolerance of the checker on the
+    checker's appended pools.  `few`: a handful of pairs (the store runs as a launch of its own);
+    `many` and the named shapes: the store inside the Attention kernel."""
+    if name in ("few", "many"):
+        lens = [1, 16, 17, 255, 256, 300, 0, 1025, 4095, 4096, 4097, 5000]
+        if name == "many":
+            lens = lens * 12
+        rng = np.random.default_rng(76)
+        subsets = W.draw_head_subsets(len(lens), 8, 4, rng)
+        subsets[0] = np.arange(8, dtype=np.int32)
+        subsets[6] = np.array([2], dtype=np.int32)
+        pw = W.make_pairs_workload(spec_of(lens, 16, 8, 128, 77), device=DEV, subsets=subsets)
+        assert (pw.n_pairs >= 512) == (name == "many")
+    else:
+        pw = W.make_pairs_workload(W.SPECS[name], device=DEV)
+    s = pw.spec
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(78)
+    kn = torch.randn((s.batch, s.n_kv_heads, s.head_dim), generator=gen, device=DEV).half()
+    vn = torch.randn((s.batch, s.n_kv_heads, s.head_dim), generator=gen, device=DEV).half()
+    shape = H.make_shape(s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim, pw.block_table.shape[1])
+    bt, sl, ps, ph = i32(pw.block_table), i32(pw.seq_lens), i32(pw.pair_seq), i32(pw.pair_head)
+    new_out = lambda: torch.full_like(pw.q, 0).view(torch.int16).fill_(np.int16(SENTINEL)).view(torch.float16)
+    # two calls on copies of the pools
+    k2, v2, out2 = pw.k_tiles.clone(), pw.v_tiles.clone(), new_out()
+    H.check(H.hetis_kv_append_pairs(shape, kn, vn, bt, sl, ps, ph, pw.n_pairs, pw.num_tiles, k2, v2),
+            "hetis_kv_append_pairs")
+    H.check(H.hetis_attn_decode_pairs(shape, pw.q, k2, v2, bt, sl, ps, ph, pw.n_pairs, s.scale, out2),
+            "hetis_attn_decode_pairs")
+    # one call, once on the library's workspace and once on the caller's
+    for use_ws in (False, True):
+        k1, v1, out1 = pw.k_tiles.clone(), pw.v_tiles.clone(), new_out()
+        if use_ws:
+            rc, nbytes = H.hetis_attn_decode_pairs_workspace_bytes(shape, pw.n_pairs)
+            H.check(rc, "pairs_workspace_bytes")
+            ws = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+            H.check(H.hetis_attn_decode_pairs_step_ws(shape, pw.q, kn, vn, k1, v1, bt, sl, ps, ph,
+                                                      pw.n_pairs, s.scale, out1, ws, nbytes),
+                    "hetis_attn_decode_pairs_step_ws")
+        else:
+            ws = None
+            H.check(H.hetis_attn_decode_pairs_step(shape, pw.q, kn, vn, k1, v1, bt, sl, ps, ph,
+                                                   pw.n_pairs, s.scale, out1),
+                    "hetis_attn_decode_pairs_step")
+        torch.cuda.synchronize()
+        no_expired_wait(ws)
+        assert torch.equal(k1.view(torch.int16), k2.view(torch.int16))
+        assert torch.equal(v1.view(torch.int16), v2.view(torch.int16))
+        assert torch.equal(out1.view(torch.int16), out2.view(torch.int16))
+    ref_k, ref_v = oracle.kv_append_pairs(bits(pw.k_tiles), bits(pw.v_tiles), bits(kn), bits(vn),
+                                          pw.block_table, pw.seq_lens, pw.pair_seq, pw.pair_head)
+    same = lambda t, ref: bool(torch.equal(t.view(torch.int16).reshape(-1),
+                                           torch.from_numpy(ref.view(np.int16)).to(DEV).reshape(-1)))
+    assert same(k1, ref_k) and same(v1, ref_v)
+    ref = oracle.attn_decode_pairs(pw.q.cpu().numpy(), ref_k.view(np.float16), ref_v.view(np.float16),
+                                   pw.block_table, pw.seq_lens, pw.pair_seq, pw.pair_head,
+                                   s.n_kv_heads, s.scale)
+    check_mask(out1, ref, named_rows(pw), TOL, "decode_pairs_step")
