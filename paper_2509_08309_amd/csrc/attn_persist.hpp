@@ -584,16 +584,6 @@ __global__ __launch_bounds__((NW + 1) * 64)
     //  3. Every thread writes its rows' table entries: firstF[row] = whole segments before
     //     the row; order[position] = row, position = rows of larger classes + rows of the
     //     same class in lower groups + rank.
-    if (!PAIRS) {
-        for (int i0 = tid; i0 < n_ids; i0 += 4 * NT) {
-            int h[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) h[u] = p.head_ids[min(i0 + u * NT, n_ids - 1)];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (i0 + u * NT < n_ids) hids[i0 + u * NT] = h[u];
-        }
-    }
     // size class of a last segment of `rt` tokens (0 < rt <= seg_tokens): 0 = the largest
     auto size_class = [&](int rt) {
         const int j = udiv(16 * rt - 1, seg_tokens);    // rt in (j/16, (j+1)/16] of a segment
@@ -611,23 +601,26 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // The lengths go to LDS at once and the later steps run as loops that are not unrolled:
         // the prologue must not need more registers than the streaming loop, or the register
         // allocation of that loop suffers (measured: 12 % of the kernel's time).
+        // Every load is issued unconditionally (indices clamped) and before the first use of any
+        // of them, so that all of them are in flight together: a conditional load ends up
+        // behind a branch and a full wait, and the prologue then pays one memory latency per
+        // round instead of one in all (two in pairs mode).
         int row[UR], L[UR], head[UR];
-        // (a round whose group lies beyond the last row is skipped as a whole: same in all lanes)
 #pragma unroll
         for (int u = 0; u < UR; ++u) {
             const int i = min(tid + u * NT, batch - 1);
-            row[u] = i;
-            head[u] = 0;
-            if (PAIRS && u * (NW + 1) + wave < n_groups) {
-                row[u] = p.pair_seq[i];
-                head[u] = p.pair_head[i];
-            }
+            row[u] = PAIRS ? p.pair_seq[i] : i;
+            head[u] = PAIRS ? p.pair_head[i] : 0;
         }
 #pragma unroll
-        for (int u = 0; u < UR; ++u) {
-            L[u] = 0;
-            if (u * (NW + 1) + wave < n_groups) L[u] = p.seq_lens[row[u]];
-        }
+        for (int u = 0; u < UR; ++u) L[u] = p.seq_lens[row[u]];
+        constexpr int UH = 4;                           // n_sel <= 1024 < UH * NT
+        int sel[UH];
+#pragma unroll
+        for (int u = 0; u < UH; ++u) sel[u] = PAIRS ? 0 : p.head_ids[min(tid + u * NT, n_ids - 1)];
+#pragma unroll
+        for (int u = 0; u < UH; ++u)
+            if (!PAIRS && tid + u * NT < n_ids) hids[tid + u * NT] = sel[u];
 #pragma unroll
         for (int u = 0; u < UR; ++u) {
             const int i = tid + u * NT;
