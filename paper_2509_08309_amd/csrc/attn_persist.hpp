@@ -254,8 +254,10 @@ __device__ __forceinline__ void store_partial_coherent(const float (&o)[R][D], c
                                                        const float *w, int64_t dest,
                                                        const AttnParams &p, int lane, bool base2)
 {
+    static_assert(R * D % 64 == 0, "whole steps of one word a lane");
 #pragma unroll
-    for (int idx = lane; idx < R * D; idx += 64) {
+    for (int k = 0; k < R * D / 64; ++k) {
+        const int idx = k * 64 + lane;
         float v = (&o[0][0])[idx];
         if (w) v *= __builtin_amdgcn_rcpf(w[idx / D]);
         coherent_store(p.o_partial + dest * (R * D) + idx, v);
