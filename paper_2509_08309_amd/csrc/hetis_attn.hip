@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "attn_mfma.hpp"
@@ -167,11 +168,11 @@ static void launch_timed(Kernel kernel, dim3 grid, dim3 block, size_t lds, hipSt
     }
 }
 
-template <class Policy, bool PAIRS>
+template <class Policy, bool PAIRS, bool MERGE>
 static int launch_persistent(AttnParams p, int batch, hipStream_t st)
 {
     constexpr int NW = kVecWaves;
-    auto kernel = attn_chunk_persistent_kernel<Policy, NW, PAIRS>;
+    auto kernel = attn_chunk_persistent_kernel<Policy, NW, PAIRS, MERGE>;
     const size_t lds = persist_lds_bytes<Policy, NW>(batch, p.n_sel, PAIRS);
     int occ = resident_per_cu(kernel, (NW + 1) * 64, lds);
     if (occ < 1) return HETIS_ERR_LAUNCH;
@@ -224,13 +225,16 @@ static int launch_chunk(const AttnParams &p0, int rows, hipStream_t st)
             p.q += (int64_t)row0 * p.n_q_heads * D;
             if (p.out) p.out += (int64_t)row0 * p.n_q_heads * D;
         }
+        // the instantiation without the in-launch merge when no row can need it
+        const bool merge = p.arrivals != nullptr;
+        using Policy = std::conditional_t<(R >= 4), MfmaPolicy<D, R>, VecPolicy<D, R>>;
         int rc;
-        if constexpr (R >= 4)
-            rc = pairs ? launch_persistent<MfmaPolicy<D, R>, true>(p, n, st)
-                       : launch_persistent<MfmaPolicy<D, R>, false>(p, n, st);
+        if (pairs)
+            rc = merge ? launch_persistent<Policy, true, true>(p, n, st)
+                       : launch_persistent<Policy, true, false>(p, n, st);
         else
-            rc = pairs ? launch_persistent<VecPolicy<D, R>, true>(p, n, st)
-                       : launch_persistent<VecPolicy<D, R>, false>(p, n, st);
+            rc = merge ? launch_persistent<Policy, false, true>(p, n, st)
+                       : launch_persistent<Policy, false, false>(p, n, st);
         if (rc != HETIS_OK) return rc;
     }
     return HETIS_OK;
