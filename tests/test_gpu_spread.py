@@ -181,3 +181,29 @@ def test_one_or_two_very_long_rows(Hq, Hkv, D):
     one = d.decode([1])
     rows = selected_rows(w.spec, [1])
     assert np.array_equal(bits(one)[:, rows], bits(out)[:, rows])
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 8, 128), (16, 8, 64), (32, 8, 128), (64, 8, 128)])
+def test_a_wider_block_table_changes_nothing(Hq, Hkv, D):
+    """The same rows described by a block table that would allow rows of several segments: the
+    launch then runs the kernel's other instantiation (the one that can combine partial results
+    inside the launch) on a workspace with arrival counters, and must give the same bits."""
+    lens = [4096, 4095, 3000, 2049, 2048, 1025, 1024, 513, 300, 256, 255, 100, 17, 16, 1, 0] * 20
+    heads = list(range(Hkv))
+    narrow = W.make_custom(lens, Hq, Hkv, D, heads, seed=908, device=DEV)
+    wide = W.make_custom(lens, Hq, Hkv, D, heads, seed=908, device=DEV, max_seq_len=3 * 4096)
+    assert narrow.block_table.shape[1] == 256 and wide.block_table.shape[1] == 768
+    assert np.array_equal(wide.block_table[:, :256], narrow.block_table)
+    assert torch.equal(wide.k_cache.view(torch.int16), narrow.k_cache.view(torch.int16))     # (NaN in unused slots)
+    assert torch.equal(wide.v_cache.view(torch.int16), narrow.v_cache.view(torch.int16))
+    assert torch.equal(wide.q, narrow.q)
+    dn, dw = Dev(narrow), Dev(wide)
+    rc, n_narrow = H.hetis_attn_decode_workspace_bytes(dn.shape, Hkv)
+    rc2, n_wide = H.hetis_attn_decode_workspace_bytes(dw.shape, Hkv)
+    assert rc == 0 and rc2 == 0 and n_narrow == 256 < n_wide       # control words only / counters and slots
+    a, b = dn.decode(heads), dw.decode(heads)
+    assert np.array_equal(bits(a), bits(b))
+    sub = [1, 6]
+    assert np.array_equal(bits(dn.decode(sub)), bits(dw.decode(sub)))
+    rows = selected_rows(narrow.spec, sub)
+    assert np.array_equal(bits(dw.decode(sub))[:, rows], bits(a)[:, rows])
