@@ -238,10 +238,12 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(const AttnParams p, int g
     const int64_t base = ((int64_t)b * n_sel + j / group) * p.max_segs * group + j % group;
     const float *lse = p.lse_partial + base;
     const float *op = p.o_partial + base * D + d;
+    // (unrolled so that the loads of 16 segments are in flight together; the sums keep their order)
     float M = lse[0];
+#pragma unroll 16
     for (int c = 1; c < n_segs; ++c) M = fmaxf(M, lse[(int64_t)c * group]);
     float W = 0.f, acc = 0.f;
-#pragma unroll 4
+#pragma unroll 16
     for (int c = 0; c < n_segs; ++c) {
         const float w = fast_exp2((lse[(int64_t)c * group] - M) * kLog2e);
         W += w;

@@ -18,10 +18,12 @@ def test_reduced_sweep_and_fit():
     assert rec["b_us_per_token_head"] > 0
     # 512 B per unit of g: the slope is a bandwidth; it must lie between 2 and 8 TB/s
     assert 2000 < rec["b_as_GBps"] < 8000
-    assert rec["accuracy"] > 0.85
-    assert rec["fig7a_requests"]["spread"] < 0.15
-    assert rec["fig7b_r2_linear_in_g"] > 0.98
-    assert rec["held_out_ragged"]["accuracy"] > 0.8
+    # Timings depend on the device and on what else it is doing, so these are sanity bounds far
+    # from the measured values (0.95, 0.02, 0.999, 0.98), not claims about the model's quality.
+    assert rec["accuracy"] > 0.7
+    assert rec["fig7a_requests"]["spread"] < 0.3
+    assert rec["fig7b_r2_linear_in_g"] > 0.9
+    assert rec["held_out_ragged"]["accuracy"] > 0.6
     # the library's fit is the checker's fit on the measured points
     pts = rec["points"]
     h = [p["h"] for p in pts]
