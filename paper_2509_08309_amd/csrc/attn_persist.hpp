@@ -113,6 +113,11 @@ constexpr int kTicketBatch = 8;         // tickets per device atomic while segme
 #ifndef HETIS_LATE_SEGMENTS_X4
 #define HETIS_LATE_SEGMENTS_X4 2
 #endif
+// Launches of up to this many segments a workgroup give every workgroup two segments without
+// a ticket (0: one, always).
+#ifndef HETIS_STATIC_SECOND_UPTO
+#define HETIS_STATIC_SECOND_UPTO 4
+#endif
 enum : int { kItemExists = 1 };
 
 // x / d for x >= 0, d > 0 the same in all lanes: integer division has no instruction of its
@@ -940,7 +945,17 @@ __global__ __launch_bounds__((NW + 1) * 64)
         const int64_t off = (int64_t)blk * p.stride_block + (PAIRS ? 0 : (int64_t)sg.g * p.stride_head);
         store_new_rows<D>(p, sg.seq, sg.g, off, pos % kBlockTokens, p.n_q_heads / R, lane);
     };
-    const long long n_fixed = (long long)gridDim.x * (single_mode ? 2 * NW : 1);
+    // Segments a workgroup has without a ticket: its first, and, in launches of at most
+    // HETIS_STATIC_SECOND_UPTO segments a workgroup, a second one taken from the other end of
+    // the next gridDim.x segments of the sorted list, so that the two together hold about the
+    // same number of tokens in every workgroup.  With so few segments the draws of all
+    // workgroups come in bursts (every pool runs low at the same moment) and pair long first
+    // segments with long second ones as often as not; with many segments a workgroup the
+    // tickets even the load out by themselves, and fixing more of it only takes room from them.
+    const bool two_fixed = HETIS_STATIC_SECOND_UPTO > 0 && !single_mode &&
+                           (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x;
+    const long long n_fixed = (long long)gridDim.x * (single_mode ? 2 * NW : (two_fixed ? 2 : 1));
+    const long long second_no = 2ll * gridDim.x - 1 - blockIdx.x;
 
     if (wave == NW) {
         // ------------------------------------------------------------ writer wave
@@ -974,6 +989,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             mine = decode(blockIdx.x);
             pend_n = 1;
         }
+        bool second_pending = two_fixed && second_no < total;
         long long last_base = n_fixed;    // number of the last segment drawn here
         int last_tok = seg_tokens;        // tokens of the last segment seen
         const long long wave_round = (long long)gridDim.x * NW;
@@ -1016,7 +1032,14 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 n_draw = max(1, min(kTicketBatch, chunk_tokens / max(last_tok, 1)));
                 ahead = max(4 * left > (long long)gridDim.x * HETIS_LATE_SEGMENTS_X4 ? HETIS_POOL_AHEAD : 1, n_draw);
             }
-            if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
+            if (pend_i == pend_n && second_pending && !first) {
+                // the workgroup's second segment needs no ticket
+                mine = decode((int)second_no);
+                pend_i = 0;
+                pend_n = 1;
+                second_pending = false;
+                progressed = true;
+            } else if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
                 unsigned t = 0;
                 if (lane == 0)
                     t = __hip_atomic_fetch_add(p.control + kCtlTickets, (unsigned)n_draw,
@@ -1089,7 +1112,8 @@ __global__ __launch_bounds__((NW + 1) * 64)
                     }
                 }
             }
-            if (exhausted && pend_i == pend_n && !closed && pool_end + NW - taken <= kPoolSize) {
+            if (exhausted && pend_i == pend_n && !second_pending && !closed &&
+                pool_end + NW - taken <= kPoolSize) {
                 // one "no work left" entry per streaming wave
                 if (lane < NW) {
                     ChunkDesc none{};
