@@ -113,8 +113,8 @@ constexpr int kTicketBatch = 8;         // tickets per device atomic while segme
 #ifndef HETIS_LATE_SEGMENTS_X4
 #define HETIS_LATE_SEGMENTS_X4 2
 #endif
-// Launches of up to this many segments a workgroup give every workgroup two segments without
-// a ticket (0: one, always).
+// Launches of up to this many segments a workgroup give every workgroup up to three segments
+// without a ticket (0: one, always).
 #ifndef HETIS_STATIC_SECOND_UPTO
 #define HETIS_STATIC_SECOND_UPTO 4
 #endif
@@ -946,15 +946,19 @@ __global__ __launch_bounds__((NW + 1) * 64)
         store_new_rows<D>(p, sg.seq, sg.g, off, pos % kBlockTokens, p.n_q_heads / R, lane);
     };
     // Segments a workgroup has without a ticket: its first, and, in launches of at most
-    // HETIS_STATIC_SECOND_UPTO segments a workgroup, a second one taken from the other end of
-    // the next gridDim.x segments of the sorted list, so that the two together hold about the
-    // same number of tokens in every workgroup.  With so few segments the draws of all
-    // workgroups come in bursts (every pool runs low at the same moment) and pair long first
-    // segments with long second ones as often as not; with many segments a workgroup the
-    // tickets even the load out by themselves, and fixing more of it only takes room from them.
+    // HETIS_STATIC_SECOND_UPTO segments a workgroup, a second and a third.  The second comes from
+    // the other end of the next gridDim.x segments of the sorted list, so that the two together
+    // hold about the same number of tokens in every workgroup; the third goes by the rank of
+    // that sum (the largest sum takes the shortest of the following gridDim.x segments).  With
+    // so few segments the draws of all workgroups come in bursts (every pool runs low at the
+    // same moment) and pair long segments with long ones as often as not; with many segments a
+    // workgroup the tickets even the load out by themselves, and fixing more of it only takes
+    // room from them.
     const bool two_fixed = HETIS_STATIC_SECOND_UPTO > 0 && !single_mode &&
                            (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x;
-    const long long n_fixed = (long long)gridDim.x * (single_mode ? 2 * NW : (two_fixed ? 2 : 1));
+    const bool three_fixed = two_fixed && (long long)total > 2ll * gridDim.x;
+    const long long n_fixed =
+        (long long)gridDim.x * (single_mode ? 2 * NW : (three_fixed ? 3 : (two_fixed ? 2 : 1)));
     const long long second_no = 2ll * gridDim.x - 1 - blockIdx.x;
 
     if (wave == NW) {
@@ -990,6 +994,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
             pend_n = 1;
         }
         bool second_pending = two_fixed && second_no < total;
+        bool third_pending = three_fixed;
         long long last_base = n_fixed;    // number of the last segment drawn here
         int last_tok = seg_tokens;        // tokens of the last segment seen
         const long long wave_round = (long long)gridDim.x * NW;
@@ -1038,6 +1043,31 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 pend_i = 0;
                 pend_n = 1;
                 second_pending = false;
+                progressed = true;
+            } else if (pend_i == pend_n && third_pending && !second_pending && !first) {
+                // The third: the workgroup whose first two hold the most tokens takes the
+                // shortest of the next gridDim.x segments, and so on (rank among the sums, which
+                // every workgroup can work out for itself).
+                const int Gn = (int)gridDim.x;
+                auto two_sum = [&](int b) {
+                    const int s2 = 2 * Gn - 1 - b;
+                    return decode(b).n_tok + (s2 < total ? decode(s2).n_tok : 0);
+                };
+                const int my = __builtin_amdgcn_readfirstlane(two_sum((int)blockIdx.x));
+                int rank = 0;
+                for (int b0 = 0; b0 < Gn; b0 += 64) {
+                    const int b = b0 + lane;
+                    const int sum_b = two_sum(min(b, Gn - 1));
+                    const bool larger = b < Gn && (sum_b > my || (sum_b == my && b < (int)blockIdx.x));
+                    rank += __builtin_popcountll(__builtin_amdgcn_ballot_w64(larger));
+                }
+                const long long third_no = 3ll * Gn - 1 - rank;
+                if (third_no < total) {
+                    mine = decode((int)third_no);
+                    pend_i = 0;
+                    pend_n = 1;
+                }
+                third_pending = false;
                 progressed = true;
             } else if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
                 unsigned t = 0;
@@ -1112,7 +1142,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
                     }
                 }
             }
-            if (exhausted && pend_i == pend_n && !second_pending && !closed &&
+            if (exhausted && pend_i == pend_n && !second_pending && !third_pending && !closed &&
                 pool_end + NW - taken <= kPoolSize) {
                 // one "no work left" entry per streaming wave
                 if (lane < NW) {

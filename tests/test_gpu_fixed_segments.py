@@ -1,6 +1,7 @@
 """Launches around the numbers of segments at which the hand-out changes: up to one segment a
 workgroup (no tickets), up to two (every workgroup's second segment is fixed as well: some have
-one, some none), up to four (two fixed, the rest drawn), more (one fixed, the rest drawn).
+one, some none), up to three (a fixed third for some), up to four (three fixed, the rest drawn),
+more (one fixed, the rest drawn).
 Every row against the fp64 checker, the decode step against append + decode bit for bit, and
 a head subset against the all-heads run bit for bit (the two launches are on different sides of
 such a boundary)."""
@@ -32,7 +33,7 @@ def lengths(n, seed, longest):
 
 
 @pytest.mark.parametrize("delta", [-1, 0, 1])
-@pytest.mark.parametrize("per_wg", [1, 2, 4])
+@pytest.mark.parametrize("per_wg", [1, 2, 3, 4])
 @pytest.mark.parametrize("Hq,Hkv,D", [(2, 2, 128), (16, 2, 64)])
 def test_rows_around_the_boundaries(per_wg, delta, Hq, Hkv, D):
     G = workgroups()
