@@ -527,16 +527,23 @@ __device__ __forceinline__ void store_new_rows(const AttnParams &p, int seq, int
     }
 }
 
-// MERGE: rows may leave several partial results that are combined inside the launch
-// (AttnParams::arrivals is set).  Without it that code, a fifth of the kernel, is not compiled
-// in: launches of shapes whose rows fit one segment measured 1 % faster for it.
-template <class Policy, int NW, bool PAIRS, bool MERGE>
+// VARIANT selects what is compiled in besides the common path; code that a launch cannot reach
+// still costs it (launches measured 0.5 to 1.5 % faster without each of the two parts):
+//   kVariantPlain  many rows, none of which can leave partial results
+//   kVariantFew    also the fixed second and third segments of launches with few segments a
+//                  workgroup
+//   kVariantMerge  also partial results that are combined inside the launch
+//                  (AttnParams::arrivals is set), and single-chunk scheduling
+enum : int { kVariantPlain = 0, kVariantFew = 1, kVariantMerge = 2 };
+template <class Policy, int NW, bool PAIRS, int VARIANT>
 __global__ __launch_bounds__((NW + 1) * 64)
     __attribute__((amdgpu_waves_per_eu(Policy::kWavesPerEu))) void attn_chunk_persistent_kernel(
         const AttnParams p, const int batch)
 {
     constexpr int D = Policy::D;
     constexpr int R = Policy::R;
+    constexpr bool MERGE = VARIANT == kVariantMerge;
+    constexpr bool FEW = VARIANT >= kVariantFew;
     constexpr int NT = (NW + 1) * 64;
     constexpr int kTileBytes = kBlockTokens * D * 2;
     constexpr int NS = fold_slots<R>();
@@ -954,7 +961,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // same moment) and pair long segments with long ones as often as not; with many segments a
     // workgroup the tickets even the load out by themselves, and fixing more of it only takes
     // room from them.
-    const bool two_fixed = HETIS_STATIC_SECOND_UPTO > 0 && !single_mode &&
+    const bool two_fixed = FEW && HETIS_STATIC_SECOND_UPTO > 0 && !single_mode &&
                            (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x;
     const bool three_fixed = two_fixed && (long long)total > 2ll * gridDim.x;
     const long long n_fixed =

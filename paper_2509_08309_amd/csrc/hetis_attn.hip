@@ -168,26 +168,31 @@ static void launch_timed(Kernel kernel, dim3 grid, dim3 block, size_t lds, hipSt
     }
 }
 
-template <class Policy, bool PAIRS, bool MERGE>
+// One workgroup (NW streaming waves) per compute unit already keeps enough bytes in flight to
+// saturate HBM; more only lengthens the tail.  HETIS_ATTN_WGS_PER_CU (optional, read once)
+// overrides this, up to what fits.  It changes how items are spread over workgroups, never the
+// arithmetic of an item.
+static int wgs_per_cu_cap()
+{
+    static const int cap = [] {
+        const char *e = std::getenv("HETIS_ATTN_WGS_PER_CU");
+        const int v = e ? std::atoi(e) : 0;
+        return v > 0 ? v : kWgsPerCu;
+    }();
+    return cap;
+}
+
+template <class Policy, bool PAIRS, int VARIANT>
 static int launch_persistent(AttnParams p, int batch, hipStream_t st)
 {
     constexpr int NW = kVecWaves;
-    auto kernel = attn_chunk_persistent_kernel<Policy, NW, PAIRS, MERGE>;
+    auto kernel = attn_chunk_persistent_kernel<Policy, NW, PAIRS, VARIANT>;
     const size_t lds = persist_lds_bytes<Policy, NW>(batch, p.n_sel, PAIRS);
     int occ = resident_per_cu(kernel, (NW + 1) * 64, lds);
     if (occ < 1) return HETIS_ERR_LAUNCH;
     const int cus = device_cu_count();
     if (cus <= 0) return HETIS_ERR_LAUNCH;
-    // One workgroup (NW streaming waves) per compute unit already keeps enough bytes in
-    // flight to saturate HBM; more only lengthens the tail.  HETIS_ATTN_WGS_PER_CU (optional,
-    // read once) overrides this, up to what fits.  It changes how items are spread over
-    // workgroups, never the arithmetic of an item.
-    static const int env_wgs = [] {
-        const char *e = std::getenv("HETIS_ATTN_WGS_PER_CU");
-        const int v = e ? std::atoi(e) : 0;
-        return v > 0 ? v : kWgsPerCu;
-    }();
-    if (occ > env_wgs) occ = env_wgs;
+    if (occ > wgs_per_cu_cap()) occ = wgs_per_cu_cap();
     int64_t G = (int64_t)cus * occ;
     const int64_t most = (int64_t)batch * p.max_segs * p.n_sel;    // segments, at most
     if (G > most) G = most;
@@ -225,16 +230,23 @@ static int launch_chunk(const AttnParams &p0, int rows, hipStream_t st)
             p.q += (int64_t)row0 * p.n_q_heads * D;
             if (p.out) p.out += (int64_t)row0 * p.n_q_heads * D;
         }
-        // the instantiation without the in-launch merge when no row can need it
-        const bool merge = p.arrivals != nullptr;
+        // the leanest instantiation that holds what this launch can need: the in-launch merge
+        // when rows can leave partial results; the fixed second and third segments when the
+        // launch may have few segments a workgroup (every row has at least one segment)
+        const int64_t few_rows =
+            (int64_t)HETIS_STATIC_SECOND_UPTO * std::max(device_cu_count(), 1) * wgs_per_cu_cap();
+        const int variant = p.arrivals ? kVariantMerge
+                                       : ((int64_t)n * n_sel <= few_rows ? kVariantFew : kVariantPlain);
         using Policy = std::conditional_t<(R >= 4), MfmaPolicy<D, R>, VecPolicy<D, R>>;
         int rc;
         if (pairs)
-            rc = merge ? launch_persistent<Policy, true, true>(p, n, st)
-                       : launch_persistent<Policy, true, false>(p, n, st);
+            rc = variant == kVariantMerge ? launch_persistent<Policy, true, kVariantMerge>(p, n, st)
+                 : variant == kVariantFew ? launch_persistent<Policy, true, kVariantFew>(p, n, st)
+                                          : launch_persistent<Policy, true, kVariantPlain>(p, n, st);
         else
-            rc = merge ? launch_persistent<Policy, false, true>(p, n, st)
-                       : launch_persistent<Policy, false, false>(p, n, st);
+            rc = variant == kVariantMerge ? launch_persistent<Policy, false, kVariantMerge>(p, n, st)
+                 : variant == kVariantFew ? launch_persistent<Policy, false, kVariantFew>(p, n, st)
+                                          : launch_persistent<Policy, false, kVariantPlain>(p, n, st);
         if (rc != HETIS_OK) return rc;
     }
     return HETIS_OK;

@@ -32,7 +32,7 @@ def kernel_metadata(source, tmp_path):
 
 
 @pytest.mark.skipif(shutil.which(HIPCC) is None, reason="hipcc not found")
-@pytest.mark.parametrize("source,expected", [("hetis_attn.hip", 32), ("hetis_kv.hip", 8)])
+@pytest.mark.parametrize("source,expected", [("hetis_attn.hip", 48), ("hetis_kv.hip", 8)])
 def test_no_kernel_uses_scratch_memory(source, expected, tmp_path):
     meta = kernel_metadata(source, tmp_path)
     main = {k: v for k, v in meta.items() if "persistent_kernel" in k or "kv_" in k}
