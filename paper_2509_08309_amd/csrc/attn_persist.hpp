@@ -961,8 +961,14 @@ __global__ __launch_bounds__((NW + 1) * 64)
     // same moment) and pair long segments with long ones as often as not; with many segments a
     // workgroup the tickets even the load out by themselves, and fixing more of it only takes
     // room from them.
-    const bool two_fixed = FEW && HETIS_STATIC_SECOND_UPTO > 0 && !single_mode &&
-                           (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x;
+    // (Beyond two segments a workgroup only when the longest segment has at least as many chunks
+    // as a workgroup has streaming waves: shorter rows need no balancing, and the waves would
+    // wait for the writer wave's sums and for the first draw behind them.)
+    const bool long_rows = FEW && decode(0).ns >= NW;
+    const bool two_fixed =
+        FEW && HETIS_STATIC_SECOND_UPTO > 0 && !single_mode &&
+        ((long long)total <= 2ll * gridDim.x ||
+         (long_rows && (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x));
     const bool three_fixed = two_fixed && (long long)total > 2ll * gridDim.x;
     const long long n_fixed =
         (long long)gridDim.x * (single_mode ? 2 * NW : (three_fixed ? 3 : (two_fixed ? 2 : 1)));
