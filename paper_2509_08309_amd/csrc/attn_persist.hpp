@@ -118,6 +118,11 @@ constexpr int kTicketBatch = 8;         // tickets per device atomic while segme
 #ifndef HETIS_STATIC_SECOND_UPTO
 #define HETIS_STATIC_SECOND_UPTO 4
 #endif
+// ... and only when the longest segment holds at most this many sixteenths of the tokens a
+// workgroup gets on average.
+#ifndef HETIS_STATIC_FLAT_X16
+#define HETIS_STATIC_FLAT_X16 14
+#endif
 enum : int { kItemExists = 1 };
 
 // x / d for x >= 0, d > 0 the same in all lanes: integer division has no instruction of its
@@ -952,30 +957,50 @@ __global__ __launch_bounds__((NW + 1) * 64)
         const int64_t off = (int64_t)blk * p.stride_block + (PAIRS ? 0 : (int64_t)sg.g * p.stride_head);
         store_new_rows<D>(p, sg.seq, sg.g, off, pos % kBlockTokens, p.n_q_heads / R, lane);
     };
-    // Segments a workgroup has without a ticket: its first, and, in launches of at most
-    // HETIS_STATIC_SECOND_UPTO segments a workgroup, a second and a third.  The second comes from
-    // the other end of the next gridDim.x segments of the sorted list, so that the two together
-    // hold about the same number of tokens in every workgroup; the third goes by the rank of
-    // that sum (the largest sum takes the shortest of the following gridDim.x segments).  With
-    // so few segments the draws of all workgroups come in bursts (every pool runs low at the
-    // same moment) and pair long segments with long ones as often as not; with many segments a
-    // workgroup the tickets even the load out by themselves, and fixing more of it only takes
-    // room from them.
-    // (Beyond two segments a workgroup only when the longest segment has at least as many chunks
-    // as a workgroup has streaming waves: shorter rows need no balancing, and the waves would
-    // wait for the writer wave's sums and for the first draw behind them.)
-    const bool long_rows = FEW && decode(0).ns >= NW;
-    const bool two_fixed =
-        FEW && HETIS_STATIC_SECOND_UPTO > 0 && !single_mode &&
-        ((long long)total <= 2ll * gridDim.x ||
-         (long_rows && (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x));
-    const bool three_fixed = two_fixed && (long long)total > 2ll * gridDim.x;
-    const long long n_fixed =
-        (long long)gridDim.x * (single_mode ? 2 * NW : (three_fixed ? 3 : (two_fixed ? 2 : 1)));
-    const long long second_no = 2ll * gridDim.x - 1 - blockIdx.x;
-
     if (wave == NW) {
         // ------------------------------------------------------------ writer wave
+        // Segments a workgroup has without a ticket: its first, and, in some launches of at most
+        // HETIS_STATIC_SECOND_UPTO segments a workgroup, a second and a third.  The second comes
+        // from the other end of the next gridDim.x segments of the sorted list, so that the two
+        // together hold about the same number of tokens in every workgroup; the third goes by
+        // the rank of that sum (the largest sum takes the shortest of the following gridDim.x
+        // segments).  With so few segments the draws of all workgroups come in bursts (every
+        // pool runs low at the same moment) and pair long segments with long ones as often as
+        // not; with many segments a workgroup the tickets even the load out by themselves, and
+        // fixing more of it only takes room from them.  Two conditions besides the number of
+        // segments.  The longest segment must be well below the tokens a workgroup gets on
+        // average: where a few long rows stand out (their workgroups are what the launch waits
+        // for), they must not be given more, and the tickets see to that.  And beyond two
+        // segments a workgroup the longest segment must have at least as many chunks as a
+        // workgroup has streaming waves: shorter rows need no balancing, and the waves would
+        // wait for the writer wave's sums and for the first draw behind them.
+        bool long_rows = false, flat = false;
+        if (FEW && !single_mode && (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x) {
+            const Segment s0 = decode(0);
+            long_rows = s0.ns >= NW;
+            // tokens of the launch from the class counts (a class's rows taken at the middle of
+            // its range): the same sum of integers in every workgroup
+            long long tokens = (long long)totalF * seg_tokens;
+            const int listed = lens[2 * batch + 1];
+            for (int c = 0; c < kClasses; ++c) {
+                const int first = scan[c * n_groups];
+                const int next = c + 1 < kClasses ? scan[(c + 1) * n_groups] : listed;
+                const int j = kLinClasses - c;                // classes of a sixteenth of a segment
+                const int mid = c < kLinClasses ? (2 * j + 1) * seg_tokens / 32
+                                                : (3 * seg_tokens) >> (c - kLinClasses + 6);
+                tokens += (long long)(next - first) * mid;
+            }
+            const long long mean_load = tokens * n_sel / gridDim.x;
+            flat = 16ll * s0.n_tok <= (long long)HETIS_STATIC_FLAT_X16 * mean_load;
+        }
+        const bool two_fixed =
+            FEW && HETIS_STATIC_SECOND_UPTO > 0 && !single_mode && flat &&
+            ((long long)total <= 2ll * gridDim.x ||
+             (long_rows && (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x));
+        const bool three_fixed = two_fixed && (long long)total > 2ll * gridDim.x;
+        const long long n_fixed =
+            (long long)gridDim.x * (single_mode ? 2 * NW : (three_fixed ? 3 : (two_fixed ? 2 : 1)));
+        const long long second_no = 2ll * gridDim.x - 1 - blockIdx.x;
         int next_box[NW];
 #pragma unroll
         for (int v = 0; v < NW; ++v) next_box[v] = 0;
