@@ -974,33 +974,73 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // segments a workgroup the longest segment must have at least as many chunks as a
         // workgroup has streaming waves: shorter rows need no balancing, and the waves would
         // wait for the writer wave's sums and for the first draw behind them.
-        bool long_rows = false, flat = false;
-        if (FEW && !single_mode && (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x) {
-            const Segment s0 = decode(0);
-            long_rows = s0.ns >= NW;
+        // The segments that need no ticket wait in a queue of three numbers (q0 next; -1: none),
+        // worked out here, before the loop, so that the loop itself carries no state for them.
+        const int Gn = (int)gridDim.x;
+        int n_fixed = Gn * (single_mode ? 2 * NW : 1);
+        int q0 = have_first && !single_mode ? (int)blockIdx.x : -1, q1 = -1, q2 = -1;
+        if (FEW && HETIS_STATIC_SECOND_UPTO > 0 && !single_mode && total > Gn &&
+            (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * Gn) {
+            // tokens of segment number `segno` (whole-segment scheduling): what decode() would
+            // put into n_tok, without the rest of it
+            auto seg_n_tok = [&](int segno) {
+                const int w = min(segno, max(total - 1, 0));
+                const int cg = PAIRS ? w : w / n_sel;
+                if (cg < totalF) return seg_tokens;
+                const int L = lens[order[cg - totalF]];
+                return L > 0 ? L - udiv(L, seg_tokens) * seg_tokens : 0;
+            };
+            const int tok0 = seg_n_tok(0);
+            const bool long_rows = udiv(tok0 + chunk_for(tok0) - 1, chunk_for(tok0)) >= NW;
             // tokens of the launch from the class counts (a class's rows taken at the middle of
-            // its range): the same sum of integers in every workgroup
-            long long tokens = (long long)totalF * seg_tokens;
+            // its range; one class a lane, then a sum over the wave): the same sum of integers in
+            // every workgroup
             const int listed = lens[2 * batch + 1];
-            for (int c = 0; c < kClasses; ++c) {
-                const int first = scan[c * n_groups];
-                const int next = c + 1 < kClasses ? scan[(c + 1) * n_groups] : listed;
+            long long part = 0;
+            if (lane < kClasses) {
+                const int c = lane;
+                const int first_c = scan[c * n_groups];
+                const int next_c = c + 1 < kClasses ? scan[(c + 1) * n_groups] : listed;
                 const int j = kLinClasses - c;                // classes of a sixteenth of a segment
                 const int mid = c < kLinClasses ? (2 * j + 1) * seg_tokens / 32
                                                 : (3 * seg_tokens) >> (c - kLinClasses + 6);
-                tokens += (long long)(next - first) * mid;
+                part = (long long)(next_c - first_c) * mid;
             }
-            const long long mean_load = tokens * n_sel / gridDim.x;
-            flat = 16ll * s0.n_tok <= (long long)HETIS_STATIC_FLAT_X16 * mean_load;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+            const long long mean_load = ((long long)totalF * seg_tokens + part) * n_sel / Gn;
+            const bool flat = 16ll * tok0 <= (long long)HETIS_STATIC_FLAT_X16 * mean_load;
+            // ... and there must be something to balance: with segments of (nearly) one size the
+            // tickets do better, they give the last segments to the workgroups that run fastest
+            const int tok_last = seg_n_tok(min(total, 3 * Gn) - 1);
+            const bool uneven = 4ll * tok0 > 5ll * tok_last;
+            if (flat && uneven && (total <= 2 * Gn || long_rows)) {
+                n_fixed = 2 * Gn;
+                const int second_no = 2 * Gn - 1 - (int)blockIdx.x;
+                if (second_no < total) q1 = second_no;
+                if (total > 2 * Gn) {
+                    // The third: the workgroup whose first two hold the most tokens takes the
+                    // shortest of the next Gn segments, and so on (rank among the sums, which
+                    // every workgroup can work out for itself).
+                    n_fixed = 3 * Gn;
+                    auto two_sum = [&](int b) {
+                        const int s2 = 2 * Gn - 1 - b;
+                        return seg_n_tok(b) + (s2 < total ? seg_n_tok(s2) : 0);
+                    };
+                    const int my = __builtin_amdgcn_readfirstlane(two_sum((int)blockIdx.x));
+                    int rank = 0;
+                    for (int b0 = 0; b0 < Gn; b0 += 64) {
+                        const int b = b0 + lane;
+                        const int sum_b = two_sum(min(b, Gn - 1));
+                        const bool larger =
+                            b < Gn && (sum_b > my || (sum_b == my && b < (int)blockIdx.x));
+                        rank += __builtin_popcountll(__builtin_amdgcn_ballot_w64(larger));
+                    }
+                    const int third_no = 3 * Gn - 1 - rank;
+                    if (third_no < total) q2 = third_no;
+                }
+            }
         }
-        const bool two_fixed =
-            FEW && HETIS_STATIC_SECOND_UPTO > 0 && !single_mode && flat &&
-            ((long long)total <= 2ll * gridDim.x ||
-             (long_rows && (long long)total <= (long long)HETIS_STATIC_SECOND_UPTO * gridDim.x));
-        const bool three_fixed = two_fixed && (long long)total > 2ll * gridDim.x;
-        const long long n_fixed =
-            (long long)gridDim.x * (single_mode ? 2 * NW : (three_fixed ? 3 : (two_fixed ? 2 : 1)));
-        const long long second_no = 2ll * gridDim.x - 1 - blockIdx.x;
         int next_box[NW];
 #pragma unroll
         for (int v = 0; v < NW; ++v) next_box[v] = 0;
@@ -1027,12 +1067,6 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // Segments drawn and decoded (one per lane, lanes [pend_i, pend_n) still to publish)
         Segment mine{};
         int pend_i = 0, pend_n = 0;
-        if (first) {
-            mine = decode(blockIdx.x);
-            pend_n = 1;
-        }
-        bool second_pending = two_fixed && second_no < total;
-        bool third_pending = three_fixed;
         long long last_base = n_fixed;    // number of the last segment drawn here
         int last_tok = seg_tokens;        // tokens of the last segment seen
         const long long wave_round = (long long)gridDim.x * NW;
@@ -1075,37 +1109,15 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 n_draw = max(1, min(kTicketBatch, chunk_tokens / max(last_tok, 1)));
                 ahead = max(4 * left > (long long)gridDim.x * HETIS_LATE_SEGMENTS_X4 ? HETIS_POOL_AHEAD : 1, n_draw);
             }
-            if (pend_i == pend_n && second_pending && !first) {
-                // the workgroup's second segment needs no ticket
-                mine = decode((int)second_no);
+            int want = -1;                // segment to decode in this pass (one a lane)
+            if (pend_i == pend_n && q0 >= 0) {
+                // the next of the workgroup's own segments
+                want = q0;
+                q0 = q1;
+                q1 = q2;
+                q2 = -1;
                 pend_i = 0;
                 pend_n = 1;
-                second_pending = false;
-                progressed = true;
-            } else if (pend_i == pend_n && third_pending && !second_pending && !first) {
-                // The third: the workgroup whose first two hold the most tokens takes the
-                // shortest of the next gridDim.x segments, and so on (rank among the sums, which
-                // every workgroup can work out for itself).
-                const int Gn = (int)gridDim.x;
-                auto two_sum = [&](int b) {
-                    const int s2 = 2 * Gn - 1 - b;
-                    return decode(b).n_tok + (s2 < total ? decode(s2).n_tok : 0);
-                };
-                const int my = __builtin_amdgcn_readfirstlane(two_sum((int)blockIdx.x));
-                int rank = 0;
-                for (int b0 = 0; b0 < Gn; b0 += 64) {
-                    const int b = b0 + lane;
-                    const int sum_b = two_sum(min(b, Gn - 1));
-                    const bool larger = b < Gn && (sum_b > my || (sum_b == my && b < (int)blockIdx.x));
-                    rank += __builtin_popcountll(__builtin_amdgcn_ballot_w64(larger));
-                }
-                const long long third_no = 3ll * Gn - 1 - rank;
-                if (third_no < total) {
-                    mine = decode((int)third_no);
-                    pend_i = 0;
-                    pend_n = 1;
-                }
-                third_pending = false;
                 progressed = true;
             } else if (pend_i == pend_n && !exhausted && pool_end - taken < ahead) {
                 unsigned t = 0;
@@ -1117,9 +1129,10 @@ __global__ __launch_bounds__((NW + 1) * 64)
                 if (base + n_draw >= total) exhausted = true;
                 pend_i = 0;
                 pend_n = (int)max(0ll, min((long long)n_draw, (long long)total - base));
-                if (pend_n > 0) mine = decode((int)min(base + lane, (long long)total - 1));
+                if (pend_n > 0) want = (int)min(base + lane, (long long)total - 1);
                 progressed = true;
             }
+            if (want >= 0) mine = decode(want);
             if (pend_i < pend_n) {
                 // all remaining drawn segments are single chunks: publish them together
                 const bool single = __builtin_amdgcn_ballot_w64(lane >= pend_i && lane < pend_n &&
@@ -1180,7 +1193,7 @@ __global__ __launch_bounds__((NW + 1) * 64)
                     }
                 }
             }
-            if (exhausted && pend_i == pend_n && !second_pending && !third_pending && !closed &&
+            if (exhausted && pend_i == pend_n && q0 < 0 && !closed &&
                 pool_end + NW - taken <= kPoolSize) {
                 // one "no work left" entry per streaming wave
                 if (lane < NW) {
