@@ -967,13 +967,14 @@ __global__ __launch_bounds__((NW + 1) * 64)
         // segments).  With so few segments the draws of all workgroups come in bursts (every
         // pool runs low at the same moment) and pair long segments with long ones as often as
         // not; with many segments a workgroup the tickets even the load out by themselves, and
-        // fixing more of it only takes room from them.  Two conditions besides the number of
+        // fixing more of it only takes room from them.  Three conditions besides the number of
         // segments.  The longest segment must be well below the tokens a workgroup gets on
         // average: where a few long rows stand out (their workgroups are what the launch waits
-        // for), they must not be given more, and the tickets see to that.  And beyond two
-        // segments a workgroup the longest segment must have at least as many chunks as a
-        // workgroup has streaming waves: shorter rows need no balancing, and the waves would
-        // wait for the writer wave's sums and for the first draw behind them.
+        // for), they must not be given more, and the tickets see to that.  The segments must
+        // differ in length, or there is nothing to balance.  And beyond two segments a
+        // workgroup the longest segment must have at least as many chunks as a workgroup has
+        // streaming waves: shorter rows need no balancing, and the waves would wait for the
+        // writer wave's sums and for the first draw behind them.
         // The segments that need no ticket wait in a queue of three numbers (q0 next; -1: none),
         // worked out here, before the loop, so that the loop itself carries no state for them.
         const int Gn = (int)gridDim.x;
